@@ -1,0 +1,202 @@
+/*
+ * coopt_attn.h -- C ABI of the MI355X (gfx950) paged FP8 grouped-query decode-attention library.
+ *
+ * The library implements the data-parallel hot path that the three LLM-CoOpt strategies act on:
+ * Opt-KV (skip-filtered, FP8-compressed KV-cache write and dequantising read), Opt-GQA (query
+ * heads grouped onto shared KV heads) and Opt-Pa (attention over the valid blocks of a paged
+ * cache only, with a numerically stable block-wise softmax), plus the partitioned form for long
+ * contexts that the paper's conclusion names and a chunked-prefill form for query length > 1.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Every pointer argument is a DEVICE pointer owned by the caller, except `const coopt_shape*`
+ *    (host) and `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Unless a comment says otherwise the library allocates nothing, frees nothing, copies nothing
+ *    to the host and never synchronises: kernels are enqueued on `hip_stream` and the call returns.
+ *  - Return value: COOPT_OK (0) or a negative coopt_status.  On any error NOTHING was launched.
+ *  - Indices: slots are int64, block numbers and lengths int32.  Floating point: q / new k,v /
+ *    out are IEEE binary16; scales and partials are binary32.
+ *
+ * Tensor layouts (NB = physical blocks, H_k = KV heads, B = block_size = 16, d = head_dim)
+ * ---------------------------------------------------------------------------------------
+ *   k_cache  [NB][H_k][B][d]   one element per (token, dim); u8 OCP-E4M3 code or fp16
+ *   v_cache  [NB][H_k][d][B]   token index innermost (the order the PV matrix-core operand reads)
+ *   k_scale  [NB][H_k][B]      binary32, E4M3 caches only: value = code * scale
+ *   v_scale  [NB][H_k][B]
+ *   block_tables [S][max_blocks_per_seq]   logical block -> physical block; only entries
+ *                                          b < ceil(context_len/B) are ever read (Opt-Pa, Eq. 9)
+ *   slot = physical_block * B + offset_in_block
+ *
+ * Device-side preconditions that are NOT checked: non-negative slots are < NB*B and unique within
+ * one write call; block table entries that are read lie in [0, NB); 0 <= context_lens[s] <=
+ * max_blocks_per_seq*B; inputs are finite.  Cache bytes of tokens >= context_len, and of blocks
+ * past the last valid one, may hold anything (NaN codes included): they never reach the result.
+ */
+#ifndef COOPT_ATTN_H
+#define COOPT_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum coopt_status {
+    COOPT_OK = 0,
+    COOPT_ERR_NULL = -1,        /* a required pointer is NULL */
+    COOPT_ERR_SHAPE = -2,       /* unsupported or inconsistent shape / argument value */
+    COOPT_ERR_WORKSPACE = -3,   /* workspace or partial buffers too small */
+    COOPT_ERR_LAUNCH = -4       /* the HIP runtime refused the launch */
+} coopt_status;
+
+enum { COOPT_KV_FP16 = 0, COOPT_KV_E4M3 = 1 };
+
+/*
+ * Problem shape.  Supported: head_dim 64 or 128; block_size 16; num_q_heads a multiple of
+ * num_kv_heads (Opt-GQA, Eq. 7 needs an integer group size H_g = H_q/H_k) with H_g <= 16.
+ */
+typedef struct coopt_shape {
+    int32_t num_seqs;            /* S */
+    int32_t num_q_heads;         /* H_q */
+    int32_t num_kv_heads;        /* H_k */
+    int32_t head_dim;            /* d */
+    int32_t block_size;          /* B */
+    int32_t num_blocks;          /* NB */
+    int32_t max_blocks_per_seq;  /* row stride of block_tables */
+    int32_t kv_dtype;            /* COOPT_KV_FP16 or COOPT_KV_E4M3 */
+    float softmax_scale;         /* multiplies q.k before the softmax; 1/sqrt(d) in Eq. 1 */
+} coopt_shape;
+
+/*
+ * Quantise-on-write of new tokens into the paged cache (Opt-KV: Eq. 5 and Alg. 1 phase 1).
+ * For token i: slot_mapping[i] < 0 means "skip, write nothing" (the filter of Eq. 5; any other
+ * skip set is expressed by the caller passing a negative slot).  Otherwise, for every KV head and
+ * for K and V separately: amax = max|x| over the d elements, scale = amax/448 in binary32
+ * (1.0 if amax == 0), code = E4M3(round-to-nearest-even(x/scale)), saturated at +-448, sign kept.
+ *   k, v           [num_tokens][H_k][d] fp16, contiguous            (read)
+ *   slot_mapping   [num_tokens] int64                               (read)
+ *   k_cache, v_cache, k_scale, v_scale                              (written at the named slots only)
+ * shape->kv_dtype must be COOPT_KV_E4M3.  num_tokens == 0 is a no-op.
+ */
+int coopt_kv_cache_write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
+                             int32_t num_tokens, uint8_t* k_cache, uint8_t* v_cache,
+                             float* k_scale, float* v_scale, const coopt_shape* shape,
+                             void* hip_stream);
+
+/*
+ * The same scatter without compression: fp16 bit patterns are stored unchanged (the unquantised
+ * cache the paper's Background describes, kept as the comparison case).  kv_dtype must be
+ * COOPT_KV_FP16; k_cache / v_cache hold fp16 in the layouts above.
+ */
+int coopt_kv_cache_write_fp16(const void* k, const void* v, const int64_t* slot_mapping,
+                              int32_t num_tokens, void* k_cache, void* v_cache,
+                              const coopt_shape* shape, void* hip_stream);
+
+/*
+ * Single-step grouped-query decode attention over the paged cache
+ * (Background Eq. 1; Opt-KV Eq. 6 and Alg. 1 phase 2; Opt-GQA Eq. 7-8 and Alg. 2; Opt-Pa Eq. 9-10
+ * and Alg. 3).  For sequence s and query head h, with KV head g = floor(h / (H_q/H_k)):
+ *   out[s][h] = softmax_j( softmax_scale * q[s][h] . k~[j][g] ) . v~[j][g],  j < context_lens[s],
+ * where k~, v~ are the dequantised cache rows reached through block_tables.  All H_g query heads
+ * of a group are served by one read of each K/V tile.
+ *   q [S][H_q][d] fp16 (read); out [S][H_q][d] fp16 (written; zeros where context_lens[s] == 0)
+ *   k_scale, v_scale: NULL iff kv_dtype == COOPT_KV_FP16
+ *   context_lens [S] int32: tokens visible, the token written this step included
+ *   workspace: scratch for the context split.  NULL (then workspace_bytes is ignored) runs one
+ *     workgroup per (sequence, KV head) over the whole context; otherwise it must hold at least
+ *     coopt_decode_workspace_bytes(shape) bytes, be 16-byte aligned, and its contents are
+ *     undefined afterwards.  Two calls that share a workspace must be ordered on one stream.
+ */
+int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cache,
+                           const float* k_scale, const float* v_scale,
+                           const int32_t* block_tables, const int32_t* context_lens, void* out,
+                           void* workspace, size_t workspace_bytes, const coopt_shape* shape,
+                           void* hip_stream);
+
+/* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under the current decode plan
+ * (0 if the shape is unsupported). */
+size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
+
+/*
+ * Launch plan of coopt_paged_gqa_decode's context split and of the partitioned call (tuning
+ * knobs, process-wide, not thread-safe against concurrent decode calls): a workgroup of
+ * `waves_per_group` wavefronts (1, 2, 4 or 8) serves `tokens_per_group` consecutive tokens (a
+ * positive multiple of 16) of one (sequence, KV head), each wavefront keeping `pipeline_depth`
+ * (1, 2, 3, 4 or 6) cache blocks in flight.  Zero keeps the current value.  Returns
+ * COOPT_ERR_SHAPE on a bad value and then changes nothing.  Changing tokens_per_group changes
+ * coopt_decode_workspace_bytes.
+ */
+int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves_per_group,
+                          int32_t pipeline_depth);
+
+/* Reads the current plan into the three host integers (any may be NULL). */
+void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves_per_group,
+                           int32_t* pipeline_depth);
+
+/*
+ * Partitioned decode for long contexts (the "partitioned parallel" reduction of the paper's
+ * conclusion; each partition is Opt-Pa Alg. 3 on its own token range).  Partition p of sequence s
+ * covers tokens [p*partition_size, min((p+1)*partition_size, context_lens[s])) and emits
+ *   max_logits[s][h][p] = m_p = max_j z_j            (natural-log units, z = softmax_scale*q.k~)
+ *   exp_sums  [s][h][p] = l_p = sum_j exp(z_j - m_p)
+ *   tmp_out   [s][h][p][:] = o_p = sum_j exp(z_j - m_p) v~_j / l_p
+ * Any running maximum is a legal m_p: only (l_p*exp(m_p), o_p) is determined, so callers must
+ * merge with coopt_paged_gqa_reduce or the same formula.  Partitions at or beyond
+ * ceil(context_lens[s]/partition_size) are not written.
+ *   partition_size: positive multiple of block_size
+ *   tmp_out [S][H_q][max_parts][d] f32, max_logits / exp_sums [S][H_q][max_parts] f32 (written)
+ *   max_parts >= ceil(max_blocks_per_seq*B / partition_size), else COOPT_ERR_WORKSPACE
+ */
+int coopt_paged_gqa_decode_partitioned(const void* q, const void* k_cache, const void* v_cache,
+                                       const float* k_scale, const float* v_scale,
+                                       const int32_t* block_tables, const int32_t* context_lens,
+                                       int32_t partition_size, float* tmp_out, float* max_logits,
+                                       float* exp_sums, int32_t max_parts,
+                                       const coopt_shape* shape, void* hip_stream);
+
+/*
+ * Cross-partition merge: M = max_p m_p, w_p = l_p*exp(m_p - M),
+ *   out[s][h] = sum_p w_p o_p / sum_p w_p   over p < ceil(context_lens[s]/partition_size),
+ * written as fp16 [S][H_q][d]; zeros where context_lens[s] == 0.  Uses num_seqs, num_q_heads and
+ * head_dim of `shape` only.
+ */
+int coopt_paged_gqa_reduce(const float* tmp_out, const float* max_logits, const float* exp_sums,
+                           const int32_t* context_lens, int32_t partition_size, int32_t max_parts,
+                           void* out, const coopt_shape* shape, void* hip_stream);
+
+/*
+ * Chunked prefill: causal attention of new query rows over a paged cache that already holds the
+ * chunk's own K/V (write them first with coopt_kv_cache_write_*).  The paper's abstract describes
+ * cutting long sequences into chunks; each row is Eq. 1 over its visible prefix.  Sequence s owns
+ * rows query_start[s] .. query_start[s+1]-1 of q and out; with C_s rows and t_s = context_lens[s]
+ * (chunk included), local row i attends to tokens j < t_s - C_s + i + 1.
+ *   q, out [query_start[S]][H_q][d] fp16;  query_start [S+1] int32 (device), increasing from 0
+ *   num_query_rows: query_start[S] as known to the host (sizes the launch); C_s <= t_s
+ */
+int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache, const void* v_cache,
+                                  const float* k_scale, const float* v_scale,
+                                  const int32_t* block_tables, const int32_t* context_lens,
+                                  const int32_t* query_start, int32_t num_query_rows,
+                                  int32_t max_chunk_len, void* out, const coopt_shape* shape,
+                                  void* hip_stream);
+
+/*
+ * Dequantising gather (the read half of Opt-KV, Eq. 6; the paper's gather_cached_kv): contiguous
+ * fp16 K and V of logical tokens [tok_begin, tok_end) of sequence `seq`:
+ *   k_out, v_out [tok_end - tok_begin][H_k][d] fp16, value = fp16(code * scale) (round to nearest
+ *   even) for E4M3 caches, the stored pattern for fp16 caches.
+ * The caller guarantees tok_end <= the sequence's context length.
+ */
+int coopt_gather_cached_kv(const void* k_cache, const void* v_cache, const float* k_scale,
+                           const float* v_scale, const int32_t* block_tables, int32_t seq,
+                           int32_t tok_begin, int32_t tok_end, void* k_out, void* v_out,
+                           const coopt_shape* shape, void* hip_stream);
+
+/* Static, human-readable text for a coopt_status value. */
+const char* coopt_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COOPT_ATTN_H */

@@ -1,0 +1,12 @@
+"""MI355X-native paged FP8 grouped-query decode attention (the LLM-CoOpt hot path).
+
+The product is ``libcoopt_attn.so`` (hand-written HIP for gfx950 behind the C ABI declared in
+``include/coopt_attn.h``).  This package is the thin Python binding over it: argument marshalling
+only.  There is no CPU fallback: importing works anywhere, calling needs the built library and a GPU.
+"""
+from .binding import (  # noqa: F401
+    COOPT_KV_E4M3, COOPT_KV_FP16, CooptError, Shape, decode_workspace_bytes, gather_cached_kv,
+    get_decode_plan,
+    kv_cache_write_fp16, kv_cache_write_fp8, lib_path, load_library, paged_gqa_decode,
+    paged_gqa_decode_partitioned, paged_gqa_prefill_chunk, paged_gqa_reduce, set_decode_plan,
+    status_string)

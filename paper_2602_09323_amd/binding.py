@@ -1,0 +1,166 @@
+"""ctypes binding of the C ABI in ``include/coopt_attn.h``: same names, argument marshalling only.
+
+Tensors are torch CUDA(HIP) tensors used purely as device memory; every step of the path runs in
+the library's own kernels on the current torch stream.  If the shared library is missing the
+binding raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcoopt_attn.so")
+_lib = None
+
+COOPT_KV_FP16 = 0
+COOPT_KV_E4M3 = 1
+
+EXPORTS = [
+    "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_paged_gqa_decode",
+    "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
+    "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
+    "coopt_status_string",
+]
+
+
+class CooptError(RuntimeError):
+    pass
+
+
+class Shape(ctypes.Structure):
+    """Mirror of ``coopt_shape``."""
+    _fields_ = [("num_seqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
+                ("max_blocks_per_seq", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libcoopt_attn.so (built by ``paper_2602_09323_amd.build``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise CooptError(f"{_LIB_PATH} is not built; run `python -m paper_2602_09323_amd.build`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
+        shp = ctypes.POINTER(Shape)
+        lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, i64p, i32, vp, vp, vp, vp, shp, vp]
+        lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, i64p, i32, vp, vp, shp, vp]
+        lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
+        lib.coopt_decode_workspace_bytes.argtypes = [shp]
+        lib.coopt_decode_workspace_bytes.restype = ctypes.c_size_t
+        lib.coopt_set_decode_plan.argtypes = [i32, i32, i32]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        lib.coopt_get_decode_plan.argtypes = [i32p, i32p, i32p]
+        lib.coopt_get_decode_plan.restype = None
+        lib.coopt_paged_gqa_decode_partitioned.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, shp, vp]
+        lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
+        lib.coopt_paged_gqa_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, shp, vp]
+        lib.coopt_gather_cached_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, shp, vp]
+        lib.coopt_status_string.argtypes = [ctypes.c_int]
+        lib.coopt_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("coopt_decode_workspace_bytes", "coopt_status_string",
+                            "coopt_get_decode_plan"):
+                getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().coopt_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise CooptError(f"{what}: status {status} ({status_string(status)})")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, shape: Shape,
+                       stream=None) -> None:
+    _check(load_library().coopt_kv_cache_write_fp8(
+        _ptr(k), _ptr(v), _ptr(slot_mapping), int(slot_mapping.numel()), _ptr(k_cache),
+        _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), ctypes.byref(shape), _stream(stream)),
+        "coopt_kv_cache_write_fp8")
+
+
+def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_kv_cache_write_fp16(
+        _ptr(k), _ptr(v), _ptr(slot_mapping), int(slot_mapping.numel()), _ptr(k_cache),
+        _ptr(v_cache), ctypes.byref(shape), _stream(stream)), "coopt_kv_cache_write_fp16")
+
+
+def decode_workspace_bytes(shape: Shape) -> int:
+    return int(load_library().coopt_decode_workspace_bytes(ctypes.byref(shape)))
+
+
+def set_decode_plan(tokens_per_group: int = 0, waves_per_group: int = 0,
+                    pipeline_depth: int = 0) -> None:
+    _check(load_library().coopt_set_decode_plan(tokens_per_group, waves_per_group, pipeline_depth),
+           "coopt_set_decode_plan")
+
+
+def get_decode_plan():
+    """(tokens_per_group, waves_per_group, pipeline_depth) currently in force."""
+    t, w, d = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    load_library().coopt_get_decode_plan(ctypes.byref(t), ctypes.byref(w), ctypes.byref(d))
+    return t.value, w.value, d.value
+
+
+def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, out,
+                     workspace, shape: Shape, stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().coopt_paged_gqa_decode(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
+        _ptr(context_lens), _ptr(out), _ptr(workspace), ctypes.c_size_t(nbytes),
+        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode")
+
+
+def paged_gqa_decode_partitioned(q, k_cache, v_cache, k_scale, v_scale, block_tables,
+                                 context_lens, partition_size: int, tmp_out, max_logits, exp_sums,
+                                 max_parts: int, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_decode_partitioned(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
+        _ptr(context_lens), int(partition_size), _ptr(tmp_out), _ptr(max_logits), _ptr(exp_sums),
+        int(max_parts), ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode_partitioned")
+
+
+def paged_gqa_reduce(tmp_out, max_logits, exp_sums, context_lens, partition_size: int,
+                     max_parts: int, out, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_reduce(
+        _ptr(tmp_out), _ptr(max_logits), _ptr(exp_sums), _ptr(context_lens), int(partition_size),
+        int(max_parts), _ptr(out), ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_reduce")
+
+
+def paged_gqa_prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                            query_start, num_query_rows: int, max_chunk_len: int, out,
+                            shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_prefill_chunk(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
+        _ptr(context_lens), _ptr(query_start), int(num_query_rows), int(max_chunk_len), _ptr(out),
+        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_prefill_chunk")
+
+
+def gather_cached_kv(k_cache, v_cache, k_scale, v_scale, block_tables, seq: int, tok_begin: int,
+                     tok_end: int, k_out, v_out, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_gather_cached_kv(
+        _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables), int(seq),
+        int(tok_begin), int(tok_end), _ptr(k_out), _ptr(v_out), ctypes.byref(shape),
+        _stream(stream)), "coopt_gather_cached_kv")

@@ -1,0 +1,85 @@
+// Internal helpers shared by the gfx950 kernels of the paged decode-attention library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "coopt_attn.h"
+
+namespace coopt {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 16;          // tokens per cache block (the only supported block_size)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kE4M3Max = 448.0f;
+
+// Host-side validation common to all entry points.  Returns COOPT_OK or the error to hand back.
+inline int check_shape(const coopt_shape* sh)
+{
+    if (!sh) return COOPT_ERR_NULL;
+    if (sh->num_seqs < 0 || sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return COOPT_ERR_SHAPE;
+    if (sh->head_dim != 64 && sh->head_dim != 128) return COOPT_ERR_SHAPE;
+    if (sh->block_size != kBlock) return COOPT_ERR_SHAPE;
+    if (sh->num_q_heads % sh->num_kv_heads != 0) return COOPT_ERR_SHAPE;
+    if (sh->num_q_heads / sh->num_kv_heads > 16) return COOPT_ERR_SHAPE;
+    if (sh->num_blocks <= 0 || sh->max_blocks_per_seq <= 0) return COOPT_ERR_SHAPE;
+    if (sh->kv_dtype != COOPT_KV_FP16 && sh->kv_dtype != COOPT_KV_E4M3) return COOPT_ERR_SHAPE;
+    return COOPT_OK;
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? COOPT_OK : COOPT_ERR_LAUNCH;
+}
+
+// Two E4M3 codes (bytes 0,1 or 2,3 of w) -> two fp16, exact (every E4M3 value is an fp16 value).
+template <bool HI>
+__device__ __forceinline__ half2_t e4m3x2_to_half2(uint32_t w)
+{
+    return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w, 1.0f, HI);
+}
+
+__device__ __forceinline__ half4_t e4m3x4_to_half4(uint32_t w)
+{
+    half2_t lo = e4m3x2_to_half2<false>(w);
+    half2_t hi = e4m3x2_to_half2<true>(w);
+    return half4_t{lo.x, lo.y, hi.x, hi.y};
+}
+
+__device__ __forceinline__ half8_t e4m3x8_to_half8(uint32_t w0, uint32_t w1)
+{
+    half2_t a = e4m3x2_to_half2<false>(w0);
+    half2_t b = e4m3x2_to_half2<true>(w0);
+    half2_t c = e4m3x2_to_half2<false>(w1);
+    half2_t d = e4m3x2_to_half2<true>(w1);
+    return half8_t{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
+}
+
+// Matrix-core tiles used throughout (wave64, lane = 16*grp + n):
+//   A operand: row n,  k-slots owned by lane group grp (8 per lane for x32, 4 for x16)
+//   B operand: column n, the same k-slots
+//   C/D:       D[4*grp + r][n] in register r (r = 0..3)
+// Any k-slot numbering works as long as A and B agree, because lanes of equal grp own equal slots.
+__device__ __forceinline__ floatx4 mfma_16x16x32(half8_t a, half8_t b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx4 mfma_16x16x16(half4_t a, half4_t b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float wave_uniform(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
+}
+__device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+}  // namespace coopt

@@ -1,0 +1,167 @@
+// Quantise-on-write of new K/V rows into the paged cache (Opt-KV: Eq. 5, Alg. 1 phase 1).
+//
+// One wavefront owns one (token, KV head) row: the 64 lanes hold the row's d elements (d/64 per
+// lane), a butterfly max gives the row's absmax, and each lane encodes and stores its own
+// elements.  K rows land as one contiguous d-byte run; V rows are scattered with stride 16
+// because the V tile keeps the token index innermost.  Write volume is a few hundred bytes per
+// row, against kilobytes per token read by attention, so this kernel is latency-, not
+// bandwidth-bound and is kept simple.
+#include "common.hpp"
+
+namespace coopt {
+
+__device__ __forceinline__ float wave_max(float a)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+    return a;
+}
+
+// Dynamic per-row scale and the scaled, clamped values (binary32, correctly rounded divisions so
+// that the stored bytes are defined bit for bit).
+template <int E>
+__device__ __forceinline__ float scale_row(const float (&x)[E], float (&y)[E])
+{
+    float amax = 0.0f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(x[e]));
+    amax = wave_max(amax);
+    const float scale = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kE4M3Max);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        float q = __fdiv_rn(x[e], scale);
+        y[e] = fminf(fmaxf(q, -kE4M3Max), kE4M3Max);
+    }
+    return scale;
+}
+
+// binary32 -> OCP E4M3 by the gfx950 convert (round to nearest even; inputs are already in
+// [-448, 448], so the instruction's overflow behaviour never comes into play).
+__device__ __forceinline__ uint32_t encode_pair(float a, float b)
+{
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
+}
+
+template <int HEAD_DIM>
+__global__ void __launch_bounds__(256)
+kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
+                    const int64_t* __restrict__ slot_mapping, int num_rows, int H_k,
+                    uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache,
+                    float* __restrict__ k_scale, float* __restrict__ v_scale)
+{
+    constexpr int E = HEAD_DIM / 64;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // token * H_k + head
+    if (row >= num_rows) return;
+    const int tok = row / H_k, head = row - tok * H_k;
+    const int64_t slot = slot_mapping[tok];
+    if (slot < 0) return;                                       // Eq. 5: filtered token
+    const int64_t blk = slot / kBlock;
+    const int off = (int)(slot - blk * kBlock);
+    const int lane = threadIdx.x & 63;
+    const size_t tile = (size_t)(blk * H_k + head);
+
+    float x[E], y[E];
+    // ---- K: [NB][H_k][B][d]
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = (float)k[(size_t)row * HEAD_DIM + lane * E + e];
+    float scale = scale_row<E>(x, y);
+    uint8_t* kdst = k_cache + (tile * kBlock + off) * HEAD_DIM + lane * E;
+    if constexpr (E == 2) {
+        *reinterpret_cast<uint16_t*>(kdst) = (uint16_t)encode_pair(y[0], y[1]);
+    } else {
+        *kdst = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
+    }
+    if (lane == 0) k_scale[tile * kBlock + off] = scale;
+
+    // ---- V: [NB][H_k][d][B]
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = (float)v[(size_t)row * HEAD_DIM + lane * E + e];
+    scale = scale_row<E>(x, y);
+    uint8_t* vdst = v_cache + (tile * HEAD_DIM + lane * E) * kBlock + off;
+    if constexpr (E == 2) {
+        const uint32_t c = encode_pair(y[0], y[1]);
+        vdst[0] = (uint8_t)(c & 0xffu);
+        vdst[kBlock] = (uint8_t)(c >> 8);
+    } else {
+        *vdst = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
+    }
+    if (lane == 0) v_scale[tile * kBlock + off] = scale;
+}
+
+template <int HEAD_DIM>
+__global__ void __launch_bounds__(256)
+kv_write_fp16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                     const int64_t* __restrict__ slot_mapping, int num_rows, int H_k,
+                     uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache)
+{
+    constexpr int E = HEAD_DIM / 64;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= num_rows) return;
+    const int tok = row / H_k, head = row - tok * H_k;
+    const int64_t slot = slot_mapping[tok];
+    if (slot < 0) return;
+    const int64_t blk = slot / kBlock;
+    const int off = (int)(slot - blk * kBlock);
+    const int lane = threadIdx.x & 63;
+    const size_t tile = (size_t)(blk * H_k + head);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int dim = lane * E + e;
+        k_cache[(tile * kBlock + off) * HEAD_DIM + dim] = k[(size_t)row * HEAD_DIM + dim];
+        v_cache[(tile * HEAD_DIM + dim) * kBlock + off] = v[(size_t)row * HEAD_DIM + dim];
+    }
+}
+
+}  // namespace coopt
+
+using namespace coopt;
+
+extern "C" int coopt_kv_cache_write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
+                                        int32_t num_tokens, uint8_t* k_cache, uint8_t* v_cache,
+                                        float* k_scale, float* v_scale, const coopt_shape* shape,
+                                        void* hip_stream)
+{
+    int st = check_shape(shape);
+    if (st != COOPT_OK) return st;
+    if (shape->kv_dtype != COOPT_KV_E4M3 || num_tokens < 0) return COOPT_ERR_SHAPE;
+    if (num_tokens == 0) return COOPT_OK;
+    if (!k || !v || !slot_mapping || !k_cache || !v_cache || !k_scale || !v_scale)
+        return COOPT_ERR_NULL;
+    const long long rows = (long long)num_tokens * shape->num_kv_heads;
+    if (rows > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (shape->head_dim == 128)
+        hipLaunchKernelGGL(kv_write_fp8_kernel<128>, grid, block, 0, stream, (const half_t*)k,
+                           (const half_t*)v, slot_mapping, (int)rows, shape->num_kv_heads, k_cache,
+                           v_cache, k_scale, v_scale);
+    else
+        hipLaunchKernelGGL(kv_write_fp8_kernel<64>, grid, block, 0, stream, (const half_t*)k,
+                           (const half_t*)v, slot_mapping, (int)rows, shape->num_kv_heads, k_cache,
+                           v_cache, k_scale, v_scale);
+    return launch_status();
+}
+
+extern "C" int coopt_kv_cache_write_fp16(const void* k, const void* v, const int64_t* slot_mapping,
+                                         int32_t num_tokens, void* k_cache, void* v_cache,
+                                         const coopt_shape* shape, void* hip_stream)
+{
+    int st = check_shape(shape);
+    if (st != COOPT_OK) return st;
+    if (shape->kv_dtype != COOPT_KV_FP16 || num_tokens < 0) return COOPT_ERR_SHAPE;
+    if (num_tokens == 0) return COOPT_OK;
+    if (!k || !v || !slot_mapping || !k_cache || !v_cache) return COOPT_ERR_NULL;
+    const long long rows = (long long)num_tokens * shape->num_kv_heads;
+    if (rows > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (shape->head_dim == 128)
+        hipLaunchKernelGGL(kv_write_fp16_kernel<128>, grid, block, 0, stream, (const uint16_t*)k,
+                           (const uint16_t*)v, slot_mapping, (int)rows, shape->num_kv_heads,
+                           (uint16_t*)k_cache, (uint16_t*)v_cache);
+    else
+        hipLaunchKernelGGL(kv_write_fp16_kernel<64>, grid, block, 0, stream, (const uint16_t*)k,
+                           (const uint16_t*)v, slot_mapping, (int)rows, shape->num_kv_heads,
+                           (uint16_t*)k_cache, (uint16_t*)v_cache);
+    return launch_status();
+}

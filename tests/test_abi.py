@@ -1,0 +1,90 @@
+"""The C-ABI library loads and exports every symbol the public header declares (no GPU needed);
+argument validation returns error codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_09323_amd as coopt
+from paper_2602_09323_amd import binding
+from paper_2602_09323_amd.build import build, needs_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "coopt_attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if needs_build():
+        build(force=True)
+    return coopt.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(coopt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_shape_struct_matches_header():
+    assert ctypes.sizeof(coopt.Shape) == 9 * 4
+    fields = re.findall(r"^\s+(?:int32_t|float)\s+(\w+);", open(HEADER).read(), flags=re.M)
+    assert [f[0] for f in coopt.Shape._fields_] == fields
+
+
+def test_status_strings(lib):
+    for code in (0, -1, -2, -3, -4, -99):
+        assert isinstance(coopt.status_string(code), str) and coopt.status_string(code)
+
+
+def _shape(**kw):
+    base = dict(num_seqs=2, num_q_heads=40, num_kv_heads=8, head_dim=128, block_size=16,
+                num_blocks=64, max_blocks_per_seq=8, kv_dtype=1, softmax_scale=0.088)
+    base.update(kw)
+    return coopt.Shape(*[base[f[0]] for f in coopt.Shape._fields_])
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block_size=32), dict(num_q_heads=41),
+                                 dict(num_q_heads=8 * 17), dict(kv_dtype=2), dict(num_blocks=0),
+                                 dict(num_kv_heads=0)])
+def test_unsupported_shapes_are_refused_without_launch(lib, bad):
+    sh = _shape(**bad)
+    one = ctypes.c_void_p(16)          # never dereferenced: validation comes first
+    assert lib.coopt_kv_cache_write_fp8(one, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -2
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, None, 0, ctypes.byref(sh), None) == -2
+    assert lib.coopt_paged_gqa_reduce(one, one, one, one, 16, 1, one, ctypes.byref(sh), None) == -2
+    assert lib.coopt_decode_workspace_bytes(ctypes.byref(sh)) == 0
+
+
+def test_null_pointers_and_bad_arguments(lib):
+    sh = _shape()
+    one = ctypes.c_void_p(16)
+    assert lib.coopt_kv_cache_write_fp8(None, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -1
+    assert lib.coopt_kv_cache_write_fp8(one, one, one, 1, one, one, None, one, ctypes.byref(sh), None) == -1
+    assert lib.coopt_kv_cache_write_fp8(one, one, one, 0, one, one, one, one, ctypes.byref(sh), None) == 0
+    assert lib.coopt_kv_cache_write_fp16(one, one, one, 1, one, one, ctypes.byref(sh), None) == -2  # wrong dtype
+    assert lib.coopt_paged_gqa_decode(one, one, one, None, one, one, one, one, None, 0, ctypes.byref(sh), None) == -1
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, None, None, 0, ctypes.byref(sh), None) == -1
+    # split decode with a workspace that is too small / misaligned
+    # (every call below is refused by validation before any launch: pointers are never read)
+    sh2 = _shape(max_blocks_per_seq=128)
+    need2 = lib.coopt_decode_workspace_bytes(ctypes.byref(sh2))
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, one, need2 - 1, ctypes.byref(sh2), None) == -3
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, ctypes.c_void_p(8), need2, ctypes.byref(sh2), None) == -3
+    # partitioned: partition size must be a positive multiple of 16; buffers must cover the table
+    assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 24, one, one, one, 8, ctypes.byref(sh), None) == -2
+    assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, one, one, one, 7, ctypes.byref(sh), None) == -3
+    assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, None, one, one, 8, ctypes.byref(sh), None) == -1
+    assert lib.coopt_gather_cached_kv(one, one, one, one, one, 5, 0, 4, one, one, ctypes.byref(sh), None) == -2
+    assert lib.coopt_gather_cached_kv(one, one, one, one, one, 0, 0, 999, one, one, ctypes.byref(sh), None) == -2
+    assert lib.coopt_set_decode_plan(100, 0, 0) == -2 and lib.coopt_set_decode_plan(0, 3, 0) == -2
+    assert lib.coopt_set_decode_plan(0, 0, 5) == -2 and lib.coopt_set_decode_plan(0, 0, 0) == 0

@@ -1,0 +1,84 @@
+"""GPU parity: chunked prefill over the paged cache and the dequantising gather."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_09323_amd as coopt
+import workloads
+from gpu_utils import alloc_dev_cache, assert_close, cache_to_dev, dev, hip_write, shape_of
+from helpers import oracle_fill
+
+pytestmark = pytest.mark.gpu
+
+
+def _hip_prefill(w, dcache, lens=None, query_start=None, max_chunk=None):
+    shape = shape_of(w)
+    qs = w.query_start if query_start is None else query_start
+    n_rows = int(qs[-1])
+    out = torch.full((n_rows, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
+    coopt.paged_gqa_prefill_chunk(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables),
+                                  dev(w.context_lens if lens is None else lens), dev(qs), n_rows,
+                                  w.new_per_seq if max_chunk is None else max_chunk, out, shape)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def _oracle_prefill(oracle, w, cache, rows=None):
+    return oracle.paged_gqa_prefill_chunk(w.q, *cache, w.block_tables, w.context_lens,
+                                          w.query_start, H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B,
+                                          softmax_scale=w.softmax_scale, rows=rows)
+
+
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "fp16"])
+@pytest.mark.parametrize("ctx,C,H_q,H_k,d", [(40, 24, 10, 2, 128), (0, 33, 4, 2, 64), (100, 1, 5, 1, 128),
+                                             (7, 130, 6, 3, 128), (256, 64, 40, 8, 128)])
+def test_small_chunks(oracle_mod, kv_dtype, ctx, C, H_q, H_k, d):
+    w = workloads.make_custom("pf", seed=51, S=3, H_q=H_q, H_k=H_k, d=d, B=16, NB=96,
+                              context_lens=[ctx + C] * 3, new_per_seq=C, kv_dtype=kv_dtype)
+    cache = oracle_fill(oracle_mod, w)
+    ref = _oracle_prefill(oracle_mod, w, cache)
+    got = _hip_prefill(w, cache_to_dev(cache))
+    assert_close(got, ref, f"prefill ctx={ctx} C={C} {kv_dtype}")
+
+
+def test_chunk_written_on_device_then_attended(oracle_mod):
+    w = workloads.make(4, shrink=16)
+    cache = oracle_fill(oracle_mod, w)
+    ref = _oracle_prefill(oracle_mod, w, cache)
+    devc = alloc_dev_cache(w, fill_byte=0x7F)
+    hip_write(w, devc, idx=w.history_index())
+    hip_write(w, devc, idx=w.new_index())
+    assert_close(_hip_prefill(w, devc), ref, "cfg4/16")
+
+
+def test_chunked_prefill_full_size_sampled_rows(oracle_mod):
+    """Full configuration; the oracle computes a sample of rows (first, last, tile edges, random)."""
+    w = workloads.make(4)
+    print(f"full cfg4: tokens={w.total_tokens}", flush=True)
+    cache = oracle_fill(oracle_mod, w)
+    got = _hip_prefill(w, cache_to_dev(cache))
+    rng = np.random.default_rng(0)
+    C = w.new_per_seq
+    local = np.array([0, 1, 15, 16, 17, C // 2, C - 2, C - 1])
+    rows = np.unique(np.concatenate([local, (w.S - 1) * C + local, rng.integers(0, w.S * C, 8)])).astype(np.int32)
+    ref = _oracle_prefill(oracle_mod, w, cache, rows=rows)
+    print("full cfg4 max-abs %.2e" % assert_close(got[rows], ref, "cfg4 sample"), flush=True)
+    assert np.isfinite(got).all()
+
+
+def test_gather_cached_kv(oracle_mod):
+    for kv_dtype in ("e4m3", "fp16"):
+        w = workloads.make_custom("ga", seed=52, S=2, H_q=4, H_k=2, d=128, B=16, NB=16,
+                                  context_lens=[70, 25], kv_dtype=kv_dtype)
+        cache = oracle_fill(oracle_mod, w)
+        kref, vref = oracle_mod.gather_cached_kv(*cache, w.block_tables, 0, 3, 61, H_k=2, d=128, B=16)
+        k_out = torch.zeros((58, 2, 128), dtype=torch.float16, device="cuda")
+        v_out = torch.zeros_like(k_out)
+        coopt.gather_cached_kv(*cache_to_dev(cache), dev(w.block_tables), 0, 3, 61, k_out, v_out, shape_of(w))
+        torch.cuda.synchronize()
+        for got, ref in ((k_out, kref), (v_out, vref)):
+            got = got.cpu().numpy().astype(np.float64)
+            want = ref.astype(np.float16).astype(np.float64)       # fp16 output rounding
+            ulp = np.maximum(np.abs(want) * 2.0 ** -10, 2.0 ** -24)
+            assert np.all(np.abs(got - want) <= ulp)               # product rounded twice on device
+            assert np.mean(got == want) > 0.99

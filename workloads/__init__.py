@@ -41,7 +41,7 @@ class Workload:
     q: np.ndarray             # decode: [S, H_q, d] fp16; prefill: [sum(new), H_q, d]
     new_per_seq: int          # tokens written by the timed step per sequence (1 = decode)
     partition_size: Optional[int] = None
-    query_start: Optional[np.ndarray] = None   # [S+1] int32, prefill only
+    query_start: Optional[np.ndarray] = None   # [S+1] int32 row offsets of each sequence in q
 
     @property
     def max_blocks(self) -> int:
@@ -111,9 +111,7 @@ def make_custom(name: str, *, seed: int, S: int, H_q: int, H_k: int, d: int, B: 
         k_ctx = k32.astype(np.float16)
     n_q = S * new_per_seq
     q = _normal_fp16(rng, (n_q, H_q, d))
-    query_start = None
-    if new_per_seq != 1:
-        query_start = (np.arange(S + 1, dtype=np.int32) * new_per_seq).astype(np.int32)
+    query_start = (np.arange(S + 1, dtype=np.int32) * new_per_seq).astype(np.int32)
     return Workload(name=name, S=S, H_q=H_q, H_k=H_k, d=d, B=B, NB=NB, kv_dtype=kv_dtype,
                     softmax_scale=float(np.float32(1.0 / math.sqrt(d))),
                     context_lens=context_lens, block_tables=block_tables, seq_start=seq_start,
