@@ -26,6 +26,16 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this script (FETCH_SIZE
+# and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain
+# 256 MiB device copy: FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  The summaries
+# with the commands are under profiles/; the figures belong to the default decode plan.
+PMC_TRAFFIC = {
+    "llama13b_gqa_fp8_decode": {"fetch_kib": 37907.6, "fetch_scale": 2.0,
+                                "write_kib": 3389.6, "write_scale": 1.0,
+                                "source": "profiles/flat_decode_kernel_llama13b_gqa_fp8_decode.md"},
+}
+
 
 def algorithmic_bytes(w):
     """Bytes the method itself must move per step (one layer): codes + scales of the visible tokens,
@@ -46,10 +56,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3],
+                    help="workload (1 = LLaMa-13B GQA FP8 decode, the headline configuration)")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
     ap.add_argument("--plan", type=str, default="", help="tokens_per_group,waves,depth (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain device copies of 256 MiB instead of the workload (the known "
+                         "traffic that scales the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this build has no multi-GPU path "
@@ -69,6 +84,15 @@ def main():
     torch.cuda.set_device(dev)
     if args.plan:
         coopt.set_decode_plan(*[int(x) for x in args.plan.split(",")])
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": src.numel(), "copies": 10}))
+        return
 
     w = workloads.make(args.config)
     ab = algorithmic_bytes(w)
@@ -113,55 +137,70 @@ def main():
             coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
         coopt.paged_gqa_decode(q, kc, vc, ks, vs, bt, lens, out, ws, shape)
 
-    # ---- whole step: W warm-up, then exactly K steps between two synchronisations
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, count):
+        """Mean GPU time per call of fn(i), i = 0..count-1, in ms.  The calls are captured into HIP
+        graphs of one rotation over the pools each (the step is ~3 launches of a few us, so eager
+        launches from Python would measure the host, not the GPU) and replayed back to back on the
+        current stream between two events."""
+        if args.no_graph:
+            e0.record()
+            for i in range(count):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / count
+        graphs = []
+        for n_in in (layers, count % layers):
+            if n_in == 0 or (n_in == layers and count < layers):
+                graphs.append(None)
+                continue
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(n_in):
+                    fn(i)
+            graphs.append(g)
+        full, rest = graphs
+        if full is not None:
+            full.replay()                     # untimed: first replay uploads the graph
+        if rest is not None:
+            rest.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(count // layers):
+            full.replay()
+        if rest is not None:
+            rest.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count
+
+    # ---- whole step: W warm-up steps, then exactly K steps between two synchronisations
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    e1.record()
-    torch.cuda.synchronize()
+    step_ms = timed(step, args.steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
-    step_ms = e0.elapsed_time(e1) / args.steps
 
-    # ---- dominant kernel alone (the split-context decode kernel), one event pair per launch on
-    # the launch stream, same rotation over pools.  coopt_paged_gqa_decode_partitioned launches
-    # exactly that kernel with the plan's token range as the partition size.
-    tokens_per_group, plan_waves, plan_depth = coopt.get_decode_plan()
-    parts = (w.max_blocks * w.B + tokens_per_group - 1) // tokens_per_group
-    kern_us = None
-    b2b_us = None
-    if parts > 1:
-        rows = w.S * w.H_q
-        tmp = torch.empty((rows, parts, w.d), dtype=torch.float32, device=dev)
-        ml = torch.empty((rows, parts), dtype=torch.float32, device=dev)
-        sm = torch.empty((rows, parts), dtype=torch.float32, device=dev)
+    # ---- dominant kernel alone (the balanced split kernel of the decode call): the same rotation
+    # over pools, launches back to back on the stream, one event pair around them.
+    tokens_per_group, plan_waves, plan_depth, plan_grid = coopt.get_decode_plan()
 
-        def kern(i):
-            kc, vc, ks, vs = pools[i % layers]
-            coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens, tokens_per_group, tmp,
-                                               ml, sm, parts, shape)
-        for i in range(args.warmup):
-            kern(i)
-        torch.cuda.synchronize()
-        n = min(args.steps, 500)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(n)]
-        for i, (a, b) in enumerate(evs):
-            a.record()
-            kern(i)
-            b.record()
-        torch.cuda.synchronize()
-        kern_us = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
-        e0.record()
-        for i in range(n):
-            kern(i)
-        e1.record()
-        torch.cuda.synchronize()
-        b2b_us = e0.elapsed_time(e1) / n * 1e3
+    def kern(i):
+        kc, vc, ks, vs = pools[i % layers]
+        coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape)
+    kern_us = timed(kern, args.steps) * 1e3
+
+    # the same kernel on empty contexts: what one launch costs before any byte moves (the gap
+    # between dependent launches in a stream plus the schedule prologue)
+    lens_zero = torch.zeros_like(lens)
+
+    def kern_empty(i):
+        kc, vc, ks, vs = pools[i % layers]
+        coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape)
+    floor_us = timed(kern_empty, min(args.steps, 200)) * 1e3
 
     kv_gbs = ab["kv"] / (step_ms * 1e-3) / 1e9
     result = {
@@ -175,7 +214,8 @@ def main():
                    "head_dim": w.d, "block_size": w.B, "context_tokens": ab["tokens"],
                    "kv_pools_rotated": layers,
                    "decode_plan": {"tokens_per_group": tokens_per_group, "waves": plan_waves,
-                                   "depth": plan_depth}, "step": "kv_cache_write + paged_gqa_decode, one layer"},
+                                   "depth": plan_depth, "grid_waves": plan_grid}, "step": "kv_cache_write + paged_gqa_decode, one layer",
+                   "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),
     }
@@ -183,13 +223,20 @@ def main():
         # algorithmic bytes of one decode-kernel launch: KV codes + scales of the visible tokens,
         # q, and the block-table entries used (partials are a by-product of the split, not counted)
         alg = ab["kv"] + ab["q_out"] // 2 + ab["tables"]
+        pmc = PMC_TRAFFIC.get(w.name)
+        traffic = None
+        if pmc and not args.plan:
+            traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
         achieved = alg / (kern_us * 1e-6) / 1e9
-        result["roofline"] = {"bound": "hbm", "kernel": "paged_decode_kernel",
+        result["roofline"] = {"bound": "hbm", "kernel": "flat_decode_kernel (coopt_paged_gqa_decode_split)",
                               "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                              "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                               "algorithmic_bytes_per_launch": int(alg),
-                              "kernel_us_event_pair_median": round(kern_us, 3),
-                              "kernel_us_back_to_back_mean": round(b2b_us, 3)}
+                              "kernel_us_mean": round(kern_us, 3),
+                              "launch_floor_us": round(floor_us, 3),
+                              "timing": "HIP events around back-to-back launches on the launch "
+                                        "stream; includes the inter-launch gap (launch_floor_us), "
+                                        "which a kernel trace's begin-to-end duration does not"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, ab)
     print(json.dumps(result), flush=True)
@@ -200,8 +247,8 @@ def cpu_baseline(w, ab):
     attention) on a bounded sample of the workload's sequences (about 10-30 s of CPU work)."""
     import oracle
     oracle.build()
-    # sample: the first sequences whose context tokens sum to <= ~1/4 of the batch
-    budget = max(int(w.context_lens[0]), ab["tokens"] // 4)
+    # sample: the whole batch when the oracle finishes it in about a second, else its first quarter
+    budget = ab["tokens"] if w.H_q * ab["tokens"] <= 4_000_000 else ab["tokens"] // 4
     n = 1
     while n < w.S and int(w.context_lens[:n + 1].sum()) <= budget:
         n += 1
@@ -223,7 +270,7 @@ def cpu_baseline(w, ab):
             oracle.kv_cache_write_fp16(k, v, s, kc, vc, H_k=w.H_k, d=w.d, B=w.B)
     write(hist)
     best = float("inf")
-    for _ in range(2):
+    for _ in range(5):
         t0 = time.perf_counter()
         write(new)
         oracle.paged_gqa_decode(np.ascontiguousarray(w.q[:n]), kc, vc, ks, vs,
@@ -235,7 +282,7 @@ def cpu_baseline(w, ab):
     return {"value": round(kv / best / 1e9, 5), "unit": "GB/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(best, 3),
             "sample": f"first {n} of {w.S} sequences ({tok_end} of {ab['tokens']} context tokens), "
-                      f"one layer, write + decode, best of 2"}
+                      f"one layer, write + decode, best of 5"}
 
 
 if __name__ == "__main__":

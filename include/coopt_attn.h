@@ -19,12 +19,19 @@
  *
  * Tensor layouts (NB = physical blocks, H_k = KV heads, B = block_size = 16, d = head_dim)
  * ---------------------------------------------------------------------------------------
- *   k_cache  [NB][H_k][B][d]   one element per (token, dim); u8 OCP-E4M3 code or fp16
- *   v_cache  [NB][H_k][d][B]   token index innermost (the order the PV matrix-core operand reads)
- *   k_scale  [NB][H_k][B]      binary32, E4M3 caches only: value = code * scale
- *   v_scale  [NB][H_k][B]
+ * The cache is a pool of tiles; one tile holds the B tokens x d dims of one (physical block, KV
+ * head), as u8 OCP-E4M3 codes or as fp16, in the order the matrix-core operands consume them, so
+ * that every wavefront load is 64 x 16 contiguous bytes.  With E = elements per 16 bytes (16 for
+ * E4M3, 8 for fp16), tile index = block * H_k + head, and element indices within a tile:
+ *   k_cache  [NB*H_k][d/E][B][E]            (tok, dim) -> ((dim/E)*B + tok)*E + dim%E
+ *                                           (16-byte chunks of a token's row, chunk-major)
+ *   v_cache  [NB*H_k][d/(4E)][B/4][16][E/4][4]   with c = dim/16, n = dim%16, W = E/4:
+ *                                           (tok, dim) -> ((((c/W)*(B/4) + tok/4)*16 + n)*W + c%W)*4 + tok%4
+ *                                           (token index innermost in runs of 4, then W dim groups)
+ *   k_scale  [NB*H_k][B]   binary32, E4M3 caches only: value = code * scale
+ *   v_scale  [NB*H_k][B]
  *   block_tables [S][max_blocks_per_seq]   logical block -> physical block; only entries
- *                                          b < ceil(context_len/B) are ever read (Opt-Pa, Eq. 9)
+ *                                          b < ceil(context_len/B) are ever used (Opt-Pa, Eq. 9)
  *   slot = physical_block * B + offset_in_block
  *
  * Device-side preconditions that are NOT checked: non-negative slots are < NB*B and unique within
@@ -103,9 +110,11 @@ int coopt_kv_cache_write_fp16(const void* k, const void* v, const int64_t* slot_
  *   q [S][H_q][d] fp16 (read); out [S][H_q][d] fp16 (written; zeros where context_lens[s] == 0)
  *   k_scale, v_scale: NULL iff kv_dtype == COOPT_KV_FP16
  *   context_lens [S] int32: tokens visible, the token written this step included
- *   workspace: scratch for the context split.  NULL (then workspace_bytes is ignored) runs one
- *     workgroup per (sequence, KV head) over the whole context; otherwise it must hold at least
- *     coopt_decode_workspace_bytes(shape) bytes, be 16-byte aligned, and its contents are
+ *   workspace: scratch for the load-balanced split of the batch's work over the whole chip (two
+ *     kernels: split attention into partial results, then their merge).  NULL (then
+ *     workspace_bytes is ignored) runs one workgroup per (sequence, KV head) over the whole context
+ *     instead, which is only adequate for small batches of short contexts.  Otherwise it must hold
+ *     at least coopt_decode_workspace_bytes(shape) bytes and be 16-byte aligned; its contents are
  *     undefined afterwards.  Two calls that share a workspace must be ordered on one stream.
  */
 int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cache,
@@ -114,25 +123,43 @@ int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cac
                            void* workspace, size_t workspace_bytes, const coopt_shape* shape,
                            void* hip_stream);
 
+/*
+ * The two kernels of coopt_paged_gqa_decode as separate calls, for callers that time or schedule
+ * them apart: `split` runs attention over equal shares of the batch's work and leaves one partial
+ * (reference max, exponential sum, normalised output) per share segment in the workspace; `merge`
+ * combines the partials of each (sequence, query head) into the fp16 output row.  Arguments as in
+ * coopt_paged_gqa_decode; the workspace is required, and shape, context_lens and the decode plan
+ * must be the same for both calls.
+ */
+int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
+                                 const float* k_scale, const float* v_scale,
+                                 const int32_t* block_tables, const int32_t* context_lens,
+                                 void* workspace, size_t workspace_bytes, const coopt_shape* shape,
+                                 void* hip_stream);
+int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* workspace,
+                                 size_t workspace_bytes, void* out, const coopt_shape* shape,
+                                 void* hip_stream);
+
 /* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under the current decode plan
  * (0 if the shape is unsupported). */
 size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
 
 /*
- * Launch plan of coopt_paged_gqa_decode's context split and of the partitioned call (tuning
- * knobs, process-wide, not thread-safe against concurrent decode calls): a workgroup of
- * `waves_per_group` wavefronts (1, 2, 4 or 8) serves `tokens_per_group` consecutive tokens (a
- * positive multiple of 16) of one (sequence, KV head), each wavefront keeping `pipeline_depth`
- * (1, 2, 3, 4 or 6) cache blocks in flight.  Zero keeps the current value.  Returns
- * COOPT_ERR_SHAPE on a bad value and then changes nothing.  Changing tokens_per_group changes
- * coopt_decode_workspace_bytes.
+ * Launch plan (tuning knobs, process-wide, not thread-safe against concurrent decode calls).
+ * coopt_paged_gqa_decode with a workspace cuts the flattened work of the batch into equal shares,
+ * one per workgroup: `grid_waves` wavefronts in the whole grid, `waves_per_group` (1, 2, 4 or 8)
+ * per workgroup, a share never smaller than `tokens_per_group` tokens (a positive multiple of 32).
+ * coopt_paged_gqa_decode_partitioned uses waves_per_group per partition.  In both, every wavefront
+ * keeps `pipeline_depth` (1, 2 or 3) two-block groups of the cache in flight.  Zero keeps the
+ * current value.  Returns COOPT_ERR_SHAPE on a bad value and then changes nothing.  Changing
+ * tokens_per_group changes coopt_decode_workspace_bytes.
  */
 int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves_per_group,
-                          int32_t pipeline_depth);
+                          int32_t pipeline_depth, int32_t grid_waves);
 
-/* Reads the current plan into the three host integers (any may be NULL). */
+/* Reads the current plan into the four host integers (any may be NULL). */
 void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves_per_group,
-                           int32_t* pipeline_depth);
+                           int32_t* pipeline_depth, int32_t* grid_waves);
 
 /*
  * Partitioned decode for long contexts (the "partitioned parallel" reduction of the paper's

@@ -47,6 +47,12 @@ def _p(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
+def _chk_dim(d, fp8):
+    """The tile layouts need whole 16-byte chunks and whole V load groups."""
+    if d % (64 if fp8 else 32) != 0:
+        raise ValueError(f"head_dim {d} does not fit the cache tile layout")
+
+
 def _chk(a, dtype, name):
     if a.dtype != np.dtype(dtype) or not a.flags.c_contiguous:
         raise TypeError(f"{name}: need C-contiguous {np.dtype(dtype)}, got {a.dtype}")
@@ -83,6 +89,7 @@ def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, *
     _chk(k_scale, np.float32, "k_scale"); _chk(v_scale, np.float32, "v_scale")
     T = int(slot_mapping.shape[0])
     assert k.size == T * H_k * d and v.size == T * H_k * d
+    _chk_dim(d, True)
     _load().orc_kv_cache_write_fp8(_p(k), _p(v), _p(slot_mapping), ctypes.c_int(T), _p(k_cache),
                                    _p(v_cache), _p(k_scale), _p(v_scale), ctypes.c_int(H_k),
                                    ctypes.c_int(d), ctypes.c_int(B))
@@ -93,6 +100,7 @@ def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, *, H_k, d, B):
     _chk(k_cache, np.float16, "k_cache"); _chk(v_cache, np.float16, "v_cache")
     T = int(slot_mapping.shape[0])
     assert k.size == T * H_k * d and v.size == T * H_k * d
+    _chk_dim(d, False)
     _load().orc_kv_cache_write_fp16(_p(k), _p(v), _p(slot_mapping), ctypes.c_int(T), _p(k_cache),
                                     _p(v_cache), ctypes.c_int(H_k), ctypes.c_int(d),
                                     ctypes.c_int(B))

@@ -26,8 +26,8 @@
  *
  * Tensor layouts (the oracle owns one index function per tensor):
  *   k, v (new tokens) ... [T, H_k, d]        fp16 bit patterns
- *   k_cache ............. [NB, H_k, B, d]    one code (u8) or fp16 pattern per element
- *   v_cache ............. [NB, H_k, d, B]    token index innermost
+ *   k_cache ............. [NB*H_k tiles][d/E][B][E]            E = elements per 16 bytes
+ *   v_cache ............. [NB*H_k tiles][d/(4E)][B/4][16][E/4][4]   (see idx_kcache / idx_vcache)
  *   k_scale, v_scale .... [NB, H_k, B]       binary32
  *   block_tables ........ [S, max_blocks]    int32, logical block -> physical block
  *   q, out .............. [S, H_q, d]
@@ -117,13 +117,20 @@ void orc_f32_to_e4m3_array(const float *y, uint8_t *out, size_t n)
 
 /* ------------------------------------------------------------ index functions */
 
-static size_t idx_kcache(int blk, int head, int off, int dim, int H_k, int B, int d)
+/* E = elements per 16 bytes: 16 for one-byte codes, 8 for fp16.
+ * K tile [d/E][B][E]: the 16-byte chunks of a token's row, chunk-major. */
+static size_t idx_kcache(int blk, int head, int off, int dim, int H_k, int B, int d, int E)
 {
-    return (((size_t)blk * H_k + head) * B + off) * d + dim;
+    size_t tile = (size_t)blk * H_k + head;
+    return tile * (size_t)(B * d) + (size_t)(((dim / E) * B + off) * E + dim % E);
 }
-static size_t idx_vcache(int blk, int head, int off, int dim, int H_k, int B, int d)
+/* V tile [d/(4E)][B/4][16][E/4][4]: tokens innermost in runs of 4, then W = E/4 groups of 16 dims. */
+static size_t idx_vcache(int blk, int head, int off, int dim, int H_k, int B, int d, int E)
 {
-    return (((size_t)blk * H_k + head) * d + dim) * B + off;
+    size_t tile = (size_t)blk * H_k + head;
+    int W = E / 4, c = dim / 16, n = dim % 16;
+    int inner = ((((c / W) * (B / 4) + off / 4) * 16 + n) * W + c % W) * 4 + off % 4;
+    return tile * (size_t)(B * d) + (size_t)inner;
 }
 static size_t idx_scale(int blk, int head, int off, int H_k, int B)
 {
@@ -173,11 +180,11 @@ void orc_kv_cache_write_fp8(const uint16_t *k, const uint16_t *v, const int64_t 
             quantise_row(krow, d, &s, codes);
             k_scale[idx_scale(blk, h, off, H_k, B)] = s;
             for (int x = 0; x < d; x++)
-                k_cache[idx_kcache(blk, h, off, x, H_k, B, d)] = codes[x];
+                k_cache[idx_kcache(blk, h, off, x, H_k, B, d, 16)] = codes[x];
             quantise_row(vrow, d, &s, codes);
             v_scale[idx_scale(blk, h, off, H_k, B)] = s;
             for (int x = 0; x < d; x++)
-                v_cache[idx_vcache(blk, h, off, x, H_k, B, d)] = codes[x];
+                v_cache[idx_vcache(blk, h, off, x, H_k, B, d, 16)] = codes[x];
         }
     }
     free(codes);
@@ -195,8 +202,8 @@ void orc_kv_cache_write_fp16(const uint16_t *k, const uint16_t *v, const int64_t
         int off = (int)(slot % B);
         for (int h = 0; h < H_k; h++)
             for (int x = 0; x < d; x++) {
-                k_cache[idx_kcache(blk, h, off, x, H_k, B, d)] = k[((size_t)i * H_k + h) * d + x];
-                v_cache[idx_vcache(blk, h, off, x, H_k, B, d)] = v[((size_t)i * H_k + h) * d + x];
+                k_cache[idx_kcache(blk, h, off, x, H_k, B, d, 8)] = k[((size_t)i * H_k + h) * d + x];
+                v_cache[idx_vcache(blk, h, off, x, H_k, B, d, 8)] = v[((size_t)i * H_k + h) * d + x];
             }
     }
 }
@@ -210,9 +217,9 @@ static double load_k(const void *k_cache, const float *k_scale, const int32_t *b
     int pb = bt_row[j / B];
     int off = j % B;
     if (kv_dtype == 1)
-        return orc_e4m3_to_f64(((const uint8_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d)]) *
+        return orc_e4m3_to_f64(((const uint8_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d, 16)]) *
                (double)k_scale[idx_scale(pb, g, off, H_k, B)];
-    return orc_f16_to_f64(((const uint16_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d)]);
+    return orc_f16_to_f64(((const uint16_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d, 8)]);
 }
 static double load_v(const void *v_cache, const float *v_scale, const int32_t *bt_row, int j,
                      int g, int x, int H_k, int d, int B, int kv_dtype)
@@ -220,9 +227,9 @@ static double load_v(const void *v_cache, const float *v_scale, const int32_t *b
     int pb = bt_row[j / B];
     int off = j % B;
     if (kv_dtype == 1)
-        return orc_e4m3_to_f64(((const uint8_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d)]) *
+        return orc_e4m3_to_f64(((const uint8_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d, 16)]) *
                (double)v_scale[idx_scale(pb, g, off, H_k, B)];
-    return orc_f16_to_f64(((const uint16_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d)]);
+    return orc_f16_to_f64(((const uint16_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d, 8)]);
 }
 
 /*

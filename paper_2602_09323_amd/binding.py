@@ -19,6 +19,7 @@ COOPT_KV_E4M3 = 1
 
 EXPORTS = [
     "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_paged_gqa_decode",
+    "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
     "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
     "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
     "coopt_status_string",
@@ -46,19 +47,22 @@ def load_library():
     """Load libcoopt_attn.so (built by ``paper_2602_09323_amd.build``); raises if absent."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise CooptError(f"{_LIB_PATH} is not built; run `python -m paper_2602_09323_amd.build`")
-        lib = ctypes.CDLL(_LIB_PATH)
+        path = os.environ.get("COOPT_ATTN_LIB", _LIB_PATH)   # another build of the same library
+        if not os.path.exists(path):
+            raise CooptError(f"{path} is not built; run `python -m paper_2602_09323_amd.build`")
+        lib = ctypes.CDLL(path)
         vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
         shp = ctypes.POINTER(Shape)
         lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, i64p, i32, vp, vp, vp, vp, shp, vp]
         lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, i64p, i32, vp, vp, shp, vp]
         lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
+        lib.coopt_paged_gqa_decode_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
+        lib.coopt_paged_gqa_decode_merge.argtypes = [vp, vp, ctypes.c_size_t, vp, shp, vp]
         lib.coopt_decode_workspace_bytes.argtypes = [shp]
         lib.coopt_decode_workspace_bytes.restype = ctypes.c_size_t
-        lib.coopt_set_decode_plan.argtypes = [i32, i32, i32]
+        lib.coopt_set_decode_plan.argtypes = [i32, i32, i32, i32]
         i32p = ctypes.POINTER(ctypes.c_int32)
-        lib.coopt_get_decode_plan.argtypes = [i32p, i32p, i32p]
+        lib.coopt_get_decode_plan.argtypes = [i32p, i32p, i32p, i32p]
         lib.coopt_get_decode_plan.restype = None
         lib.coopt_paged_gqa_decode_partitioned.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, shp, vp]
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
@@ -112,16 +116,17 @@ def decode_workspace_bytes(shape: Shape) -> int:
 
 
 def set_decode_plan(tokens_per_group: int = 0, waves_per_group: int = 0,
-                    pipeline_depth: int = 0) -> None:
-    _check(load_library().coopt_set_decode_plan(tokens_per_group, waves_per_group, pipeline_depth),
-           "coopt_set_decode_plan")
+                    pipeline_depth: int = 0, grid_waves: int = 0) -> None:
+    _check(load_library().coopt_set_decode_plan(tokens_per_group, waves_per_group, pipeline_depth,
+                                                grid_waves), "coopt_set_decode_plan")
 
 
 def get_decode_plan():
-    """(tokens_per_group, waves_per_group, pipeline_depth) currently in force."""
-    t, w, d = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
-    load_library().coopt_get_decode_plan(ctypes.byref(t), ctypes.byref(w), ctypes.byref(d))
-    return t.value, w.value, d.value
+    """(tokens_per_group, waves_per_group, pipeline_depth, grid_waves) currently in force."""
+    t, w, d, g = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    load_library().coopt_get_decode_plan(ctypes.byref(t), ctypes.byref(w), ctypes.byref(d),
+                                         ctypes.byref(g))
+    return t.value, w.value, d.value, g.value
 
 
 def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, out,
@@ -131,6 +136,22 @@ def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, contex
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
         _ptr(context_lens), _ptr(out), _ptr(workspace), ctypes.c_size_t(nbytes),
         ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode")
+
+
+def paged_gqa_decode_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                           workspace, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_decode_split(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
+        _ptr(context_lens), _ptr(workspace),
+        ctypes.c_size_t(workspace.numel() * workspace.element_size()), ctypes.byref(shape),
+        _stream(stream)), "coopt_paged_gqa_decode_split")
+
+
+def paged_gqa_decode_merge(context_lens, workspace, out, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_decode_merge(
+        _ptr(context_lens), _ptr(workspace),
+        ctypes.c_size_t(workspace.numel() * workspace.element_size()), _ptr(out),
+        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode_merge")
 
 
 def paged_gqa_decode_partitioned(q, k_cache, v_cache, k_scale, v_scale, block_tables,

@@ -1,23 +1,35 @@
 // Register-level building blocks shared by the decode and chunked-prefill kernels: the loads of
-// one (physical block, KV head) tile, its conversion to matrix-core operands, and one
-// online-softmax update of a 16-column score tile against it.
+// one (physical block, KV head) tile and one online-softmax update of a 16-column score tile
+// against a GROUP of two cache blocks (32 tokens).
 //
-// Per 16-token block, with lane = 16*grp + n:
-//   S^T[token][col] = K[token][:] . q[col][:]        A = K tile (row n = token n), B = q^T (col n
-//                                                    = query row / head slot n); 16x16x32 MFMAs.
-//   lane (n, grp) then holds the scores of column n for tokens 4*grp .. 4*grp+3.  They are scaled
-//   by k_scale[token]*softmax_scale, masked beyond the column's visible prefix, exponentiated
-//   against the running max of column n, multiplied by v_scale[token] and rounded to fp16:
-//   exactly the B operand (column n, k-slots = tokens 4*grp..4*grp+3) of
-//   O^T[dim][col] += V^T[dim][token] * P^T[token][col]   A = V tile rows (row n = dim 16c+n),
-//                                                    16x16x16 MFMAs, c = 0 .. d/16-1.
+// Lane numbering: lane = 16*grp + n, n = 0..15, grp = 0..3.
+//
+// Per group (blocks A and B, 16 tokens each):
+//   S^T[token][col] = K[token][:] . q[col][:]      per block: A operand = K tile (row n = token n),
+//       B operand = q^T (column n = query row / head slot n), 16x16x32 MFMAs over the head dims.
+//       Lane (n, grp) then holds the scores of column n for tokens 4grp..4grp+3 of each block.
+//   They are scaled by k_scale[token]*softmax_scale*log2(e), masked beyond the column's visible
+//   prefix (tail groups only), exponentiated against the running max of column n, multiplied by
+//   v_scale[token] and rounded to fp16.  The 8 values a lane holds are exactly its share of the
+//   B operand of
+//   O^T[dim][col] += V^T[dim][token] * P^T[token][col]     16x16x32 MFMAs over the 32 tokens, with
+//       k-slots 8grp..8grp+3 = tokens 4grp..4grp+3 of block A and 8grp+4..8grp+7 = the same tokens
+//       of block B; A operand = V tile rows (row n = dim 16c+n), c = 0 .. d/16-1.
 //   No cross-lane traffic is needed between the two products; the running max is kept equal in
 //   the four lanes (n, 0..3) by a two-step butterfly that only runs when some lane saw a larger
 //   score (a wave-uniform branch).
 //
-// E4M3 codes are exact in fp16, so both products are exact in the fp32 accumulators up to
-// accumulation order; the only rounding beyond fp32 is P*v_scale*2^8 -> fp16 (the 2^8 keeps small
-// weights out of the fp16 subnormal range; it is divided out at the end).
+// Numerics: E4M3 codes are exact in fp16, so both products are exact in the fp32 accumulators up
+// to accumulation order.  The weights are carried times a power of two (the reference max is
+// offset in the exponent, which costs nothing) so that P*v_scale stays out of the fp16 subnormal
+// range; the factor is common to the accumulator and the running sum and cancels in O/L.
+//
+// Cache tile layouts (one tile = 16 tokens x d dims of one KV head; E = elements per 16 bytes):
+//   K tile  [d/E chunks][16 tokens][E]             element (tok, dim) at ((dim/E)*16 + tok)*E + dim%E
+//   V tile  [d/(4E)][4 grp][16 n][E/4][4 tokens]   element (tok, dim), c = dim/16, n = dim%16:
+//           ((((c/(E/4))*4 + tok/4)*16 + n)*(E/4) + c%(E/4))*4 + tok%4
+// Both are the order in which the matrix-core operands consume them: every load instruction of a
+// wave reads 64 x 16 contiguous bytes.
 #pragma once
 
 #include "common.hpp"
@@ -31,60 +43,54 @@ struct CacheView {
     const float* v_scale;
 };
 
-// P is carried as P * v_scale * 2^8 in fp16 for E4M3 caches (plain P for fp16 caches).
-constexpr float kPScale = 256.0f;
-
-template <int KV>
-__device__ __forceinline__ constexpr float out_unscale()
-{
-    return KV == COOPT_KV_E4M3 ? 1.0f / kPScale : 1.0f;
-}
-
-// Raw bytes of one tile as loaded by lane (n, grp).
-template <int HEAD_DIM, int KV>
-struct BlockRegs {
-    static constexpr int NK = (KV == COOPT_KV_E4M3) ? HEAD_DIM / 64 : HEAD_DIM / 32;
-    static constexpr int NV = HEAD_DIM / 16;
-    static constexpr int VW = (KV == COOPT_KV_E4M3) ? 1 : 2;   // 32-bit words per V operand
-    uint4 k[NK];
-    uint32_t v[NV][VW];
-    floatx4 ks, vs;
-};
-
-// Matrix-core operands of one tile.
-template <int HEAD_DIM>
-struct BlockOps {
-    half8_t k[HEAD_DIM / 32];    // A of S^T: token n, 8 dims per MFMA (see q_dim_offset)
-    half4_t v[HEAD_DIM / 16];    // A of O^T: dim 16c+n, tokens 4grp..4grp+3
-    floatx4 ks, vs;
-};
+// Weights are carried as P * 2^kPShift, and the reference max m is only raised when a score
+// exceeds it by more than kRescaleSlack (log2 units), so weights stay <= 2^(kPShift+kRescaleSlack)
+// = 2^8: times a v_scale of at most 65504/448 that is still inside fp16.  Raising m lazily makes
+// the rescale branch rare after the first group (a later score must beat the running max by a
+// factor of 4), and any reference works: it cancels in O/L and in the merge of partials.
+constexpr float kPShift = 6.0f;
+constexpr float kRescaleSlack = 2.0f;
+constexpr float kPUnshift = 1.0f / 64.0f;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-// Loads of one (physical block, KV head) tile through buffer descriptors.  Each tile gets its own
-// descriptor (base = tile start, extent = tile bytes), built on the scalar unit from the
-// wave-uniform block number, so a lane's address is a per-lane constant plus an immediate: no
-// vector address arithmetic in the loop, no 4 GiB limit on the pool, and hardware bounds checking
-// confined to the tile.  An extent of zero turns the loads of a pipeline stage that has no block
-// left into no-ops that still count in program order, which keeps the number of loads in flight
-// the same on every path through the loop, so the waits the compiler inserts stay exact.
-//   K [tile][16 tokens][d]: lane (n, grp) reads 16 bytes of token n per K load;
-//   V [tile][d][16 tokens]: the lane's 4 tokens 4grp..4grp+3 of dim 16c+n, for every c;
-//   scales [tile][16]: the lane's 4 tokens.
+// Raw bytes of one tile as loaded by lane (n, grp): NL 16-byte pieces of K and of V, 4 + 4 scales.
 template <int HEAD_DIM, int KV>
+struct BlockRegs {
+    static constexpr int ES = (KV == COOPT_KV_E4M3) ? 1 : 2;
+    static constexpr int NL = HEAD_DIM * ES / 64;     // 16-byte loads per lane for K (and for V)
+    u32x4 k[NL];
+    u32x4 v[NL];
+    floatx4 ks, vs;
+};
+
+// Loads of one tile through buffer descriptors, so that a lane's address is the constant 16*lane
+// plus an immediate: no vector address arithmetic in the loop.  The wave-uniform tile number
+// reaches the address through the scalar unit, in one of two ways:
+//   BIG = false (pool < 2 GiB per tensor): one descriptor per tensor over the whole pool and the
+//         tile's byte offset in the instruction's scalar offset; per tile only a multiply/shift.
+//   BIG = true: one descriptor per tile (base = tile start, extent = tile bytes), 64-bit base
+//         arithmetic on the scalar unit; no limit on the pool size.
+// In both, an extent of zero turns the loads of a pipeline stage that has no block left into
+// no-ops that return zeros and still count in program order, which keeps the number of loads in
+// flight the same on every path through the loop, so the waits the compiler inserts stay exact.
+// Tile loads carry the non-temporal hint: every byte of the cache is read once per step.
+template <int HEAD_DIM, int KV, bool BIG>
 struct TileLoader {
     static constexpr int ES = (KV == COOPT_KV_E4M3) ? 1 : 2;
     static constexpr int kTileBytes = kBlock * HEAD_DIM * ES;
     static constexpr int kRsrcFlags = 0x00020000;      // gfx9 raw buffer, 32-bit data format
+    static constexpr int kAuxStream = 2;               // nt
     CacheView cv;
-    int k_off, v_off, s_off;
+    int lane_off, s_off;
+    int kv_pool_bytes, scale_pool_bytes;               // BIG = false only
 
-    __device__ __forceinline__ TileLoader(const CacheView& view, int n, int grp) : cv(view)
+    __device__ __forceinline__ TileLoader(const CacheView& view, int lane, int pool_tiles) : cv(view)
     {
-        k_off = n * HEAD_DIM * ES + 16 * grp;          // + 64*j per K load
-        v_off = (n * kBlock + 4 * grp) * ES;           // + 16*kBlock*ES*c per V load
-        s_off = 16 * grp;
+        lane_off = 16 * lane;
+        s_off = 16 * (lane >> 4);
+        kv_pool_bytes = pool_tiles * kTileBytes;
+        scale_pool_bytes = pool_tiles * kBlock * 4;
     }
 
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, int bytes)
@@ -92,44 +98,66 @@ struct TileLoader {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, kRsrcFlags);
     }
 
-    // `tile` must be wave-uniform.  valid == false issues the same loads against an empty extent.
-    __device__ __forceinline__ void issue(BlockRegs<HEAD_DIM, KV>& r, size_t tile, bool valid) const
+    // `tile` (= physical block * H_k + KV head) must be wave-uniform.
+    __device__ __forceinline__ void issue(BlockRegs<HEAD_DIM, KV>& r, int tile, bool valid) const
     {
-        const __amdgpu_buffer_rsrc_t rk = rsrc(cv.k_cache + tile * kTileBytes, valid ? kTileBytes : 0);
-        const __amdgpu_buffer_rsrc_t rv = rsrc(cv.v_cache + tile * kTileBytes, valid ? kTileBytes : 0);
+        constexpr int NL = BlockRegs<HEAD_DIM, KV>::NL;
+        if constexpr (BIG) {
+            const size_t off = (size_t)(uint32_t)tile * kTileBytes;
+            const int extent = valid ? kTileBytes : 0;
+            const __amdgpu_buffer_rsrc_t rk = rsrc(cv.k_cache + off, extent);
+            const __amdgpu_buffer_rsrc_t rv = rsrc(cv.v_cache + off, extent);
 #pragma unroll
-        for (int j = 0; j < BlockRegs<HEAD_DIM, KV>::NK; ++j) {
-            const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rk, k_off + 64 * j, 0, 0);
-            r.k[j] = uint4{w.x, w.y, w.z, w.w};
-        }
-        if constexpr (KV == COOPT_KV_E4M3) {
+            for (int j = 0; j < NL; ++j)
+                r.k[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane_off + 1024 * j, 0, kAuxStream);
 #pragma unroll
-            for (int c = 0; c < HEAD_DIM / 16; ++c)
-                r.v[c][0] = __builtin_amdgcn_raw_buffer_load_b32(rv, v_off + 16 * kBlock * c, 0, 0);
-            const __amdgpu_buffer_rsrc_t rks =
-                rsrc(cv.k_scale + tile * kBlock, valid ? kBlock * 4 : 0);
-            const __amdgpu_buffer_rsrc_t rvs =
-                rsrc(cv.v_scale + tile * kBlock, valid ? kBlock * 4 : 0);
-            r.ks = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rks, s_off, 0, 0));
-            r.vs = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rvs, s_off, 0, 0));
+            for (int j = 0; j < NL; ++j)
+                r.v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, lane_off + 1024 * j, 0, kAuxStream);
+            if constexpr (KV == COOPT_KV_E4M3) {
+                const size_t soff = (size_t)(uint32_t)tile * kBlock;
+                const int sext = valid ? kBlock * 4 : 0;
+                const __amdgpu_buffer_rsrc_t rks = rsrc(cv.k_scale + soff, sext);
+                const __amdgpu_buffer_rsrc_t rvs = rsrc(cv.v_scale + soff, sext);
+                r.ks = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rks, s_off, 0, 0));
+                r.vs = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rvs, s_off, 0, 0));
+            }
         } else {
+            const int extent = valid ? kv_pool_bytes : 0;
+            const __amdgpu_buffer_rsrc_t rk = rsrc(cv.k_cache, extent);
+            const __amdgpu_buffer_rsrc_t rv = rsrc(cv.v_cache, extent);
+            const int so = tile * kTileBytes;
 #pragma unroll
-            for (int c = 0; c < HEAD_DIM / 16; ++c) {
-                const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rv, v_off + 32 * kBlock * c, 0, 0);
-                r.v[c][0] = w.x;
-                r.v[c][1] = w.y;
+            for (int j = 0; j < NL; ++j)
+                r.k[j] = __builtin_amdgcn_raw_buffer_load_b128(rk, lane_off + 1024 * j, so, kAuxStream);
+#pragma unroll
+            for (int j = 0; j < NL; ++j)
+                r.v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, lane_off + 1024 * j, so, kAuxStream);
+            if constexpr (KV == COOPT_KV_E4M3) {
+                const int sext = valid ? scale_pool_bytes : 0;
+                const __amdgpu_buffer_rsrc_t rks = rsrc(cv.k_scale, sext);
+                const __amdgpu_buffer_rsrc_t rvs = rsrc(cv.v_scale, sext);
+                const int sso = tile * (kBlock * 4);
+                r.ks = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rks, s_off, sso, 0));
+                r.vs = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rvs, s_off, sso, 0));
             }
         }
     }
 };
 
-// First of the 8 head dims that lane group grp feeds into S^T MFMA number jj; the q^T operand
-// must use the same dims.
+// True when every tensor of the pool can be addressed with a 31-bit byte offset.
+inline bool pool_fits_small(const coopt_shape* sh)
+{
+    const long long es = sh->kv_dtype == COOPT_KV_E4M3 ? 1 : 2;
+    return (long long)sh->num_blocks * sh->num_kv_heads * kBlock * sh->head_dim * es < (1LL << 31);
+}
+
+// First of the 8 head dims that lane group grp feeds into S^T MFMA number jj (K chunk 4j+grp of
+// the lane's j-th K load, low or high half); the q^T operand must use the same dims.
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ int q_dim_offset(int jj, int grp)
 {
     if constexpr (KV == COOPT_KV_E4M3)
-        return 64 * (jj >> 1) + 16 * grp + 8 * (jj & 1);   // halves of one 16-byte K load
+        return 64 * (jj >> 1) + 16 * grp + 8 * (jj & 1);
     else
         return 32 * jj + 8 * grp;
 }
@@ -148,67 +176,114 @@ __device__ __forceinline__ void load_q_operand(half8_t (&qop)[HEAD_DIM / 32], co
     }
 }
 
-// Raw tile -> operands.  cache_valid = how many of this lane's 4 tokens exist in the cache at all
-// (>= 4 everywhere except in the last block of a context): V of the others is zeroed so that
-// stale NaN codes cannot poison the accumulators through 0 * NaN.
+// K operand number jj (8 dims of token n) of a loaded tile.
 template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void convert_block(BlockOps<HEAD_DIM>& o, const BlockRegs<HEAD_DIM, KV>& r,
-                                              int cache_valid)
+__device__ __forceinline__ half8_t k_operand(const BlockRegs<HEAD_DIM, KV>& r, int jj)
 {
-#pragma unroll
-    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) {
-        if constexpr (KV == COOPT_KV_E4M3) {
-            const uint4 w = r.k[jj >> 1];
-            o.k[jj] = (jj & 1) ? e4m3x8_to_half8(w.z, w.w) : e4m3x8_to_half8(w.x, w.y);
-        } else {
-            o.k[jj] = __builtin_bit_cast(half8_t, r.k[jj]);
-        }
+    if constexpr (KV == COOPT_KV_E4M3) {
+        const u32x4 w = r.k[jj >> 1];
+        return (jj & 1) ? e4m3x8_to_half8(w.z, w.w) : e4m3x8_to_half8(w.x, w.y);
+    } else {
+        return __builtin_bit_cast(half8_t, r.k[jj]);
     }
-    uint32_t mask0 = 0xffffffffu, mask1 = 0xffffffffu;
-    if (cache_valid < 4) {
-        if constexpr (KV == COOPT_KV_E4M3) {
-            mask0 = cache_valid <= 0 ? 0u : (0xffffffffu >> (8 * (4 - cache_valid)));
-        } else {
-            mask0 = cache_valid <= 0 ? 0u : (cache_valid == 1 ? 0x0000ffffu : 0xffffffffu);
-            mask1 = cache_valid <= 2 ? 0u : 0x0000ffffu;
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < HEAD_DIM / 16; ++c) {
-        if constexpr (KV == COOPT_KV_E4M3) {
-            o.v[c] = e4m3x4_to_half4(r.v[c][0] & mask0);
-        } else {
-            const uint2 w = {r.v[c][0] & mask0, r.v[c][1] & mask1};
-            o.v[c] = __builtin_bit_cast(half4_t, w);
-        }
-    }
-    o.ks = r.ks;
-    o.vs = r.vs;
 }
 
-// One online-softmax step of a 16-column tile against one block.
-//   n_visible: how many of this lane's 4 tokens column n may attend to (<= 0: none, >= 4: all).
-//   m: running max of column n in log2 units, identical in the four lanes (n, 0..3).
-//   l: this lane's share of the running sum.  acc[c][r] = O^T[16c + 4grp + r][n].
-// Requirement: whenever m is still -inf, the block holds a token visible to column n.
+// V operand half of dim group c (dim 16c+n, the lane's 4 tokens).
 template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void tile_update(const BlockOps<HEAD_DIM>& o,
-                                            const half8_t (&qop)[HEAD_DIM / 32], float& m, float& l,
-                                            floatx4 (&acc)[HEAD_DIM / 16], int n_visible,
-                                            float scale_log2e)
+__device__ __forceinline__ half4_t v_operand(const BlockRegs<HEAD_DIM, KV>& r, int c)
 {
-    floatx4 s = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (KV == COOPT_KV_E4M3) {
+        return e4m3x4_to_half4(r.v[c >> 2][c & 3]);
+    } else {
+        const u32x4 w = r.v[c >> 1];
+        const uint2 h = (c & 1) ? uint2{w.z, w.w} : uint2{w.x, w.y};
+        return __builtin_bit_cast(half4_t, h);
+    }
+}
+
+// Byte masks that zero the V entries of tokens beyond `cache_valid` (of this lane's 4 tokens).
+template <int KV>
+__device__ __forceinline__ void token_masks(int cache_valid, uint32_t& m0, uint32_t& m1)
+{
+    m0 = 0xffffffffu;
+    m1 = 0xffffffffu;
+    if (cache_valid < 4) {
+        if constexpr (KV == COOPT_KV_E4M3) {
+            m0 = cache_valid <= 0 ? 0u : (0xffffffffu >> (8 * (4 - cache_valid)));
+        } else {
+            m0 = cache_valid <= 0 ? 0u : (cache_valid == 1 ? 0x0000ffffu : 0xffffffffu);
+            m1 = cache_valid <= 2 ? 0u : (cache_valid == 3 ? 0x0000ffffu : 0xffffffffu);
+        }
+    }
+}
+
+// One online-softmax step of a 16-column tile against a group of two blocks.
+//   tail (wave-uniform) = false: every token of both blocks is in the cache and visible to every
+//                 column; the vis / cache arguments are ignored.
+//   tail = true:  visA / visB = how many of this lane's 4 tokens of block A / B column n may
+//                 attend to (<= 0 none, >= 4 all); cacheA / cacheB = how many exist in the cache.
+//                 Scores of invisible tokens are capped to -inf (Opt-Pa Eq. 9 / causal limit) with
+//                 a min, which also discards NaN scores from stale keys or scales; V bytes and
+//                 v_scale of absent tokens are zeroed in place, so stale NaN codes or scales
+//                 cannot reach the accumulators.  The fix-ups sit in small branches that touch only temporaries
+//                 and the loaded tile, so the accumulators stay in place across the loop.
+//   m: reference max of column n in log2 units (within kRescaleSlack of the true running max),
+//      identical in the four lanes (n, 0..3).
+//   l: this lane's share of the running sum, acc[c][r] = O^T[16c + 4grp + r][n], both times 2^kPShift.
+// Requirement: whenever m is still -inf, the group holds a token visible to column n.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
+                                             const half8_t (&qop)[HEAD_DIM / 32], float& m, float& l,
+                                             floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA,
+                                             int visB, int cacheA, int cacheB, float scale_log2e)
+{
+    floatx4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) s = mfma_16x16x32(o.k[jj], qop[jj], s);
-    float z[4];
+    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) {
+        sA = mfma_16x16x32(k_operand<HEAD_DIM, KV>(A, jj), qop[jj], sA);
+        sB = mfma_16x16x32(k_operand<HEAD_DIM, KV>(B, jj), qop[jj], sB);
+    }
+    float z[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        float zi = s[i] * scale_log2e;
-        if constexpr (KV == COOPT_KV_E4M3) zi *= o.ks[i];
-        z[i] = (i < n_visible) ? zi : -INFINITY;          // Opt-Pa Eq. 9 / causal limit
+        if constexpr (KV == COOPT_KV_E4M3) {
+            z[i] = sA[i] * (A.ks[i] * scale_log2e);
+            z[4 + i] = sB[i] * (B.ks[i] * scale_log2e);
+        } else {
+            z[i] = sA[i] * scale_log2e;
+            z[4 + i] = sB[i] * scale_log2e;
+        }
     }
-    const float bm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-    if (__builtin_amdgcn_ballot_w64(bm > m) != 0) {        // wave-uniform: someone saw a new max
+    if (tail) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);          // min drops a NaN score
+            z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
+        }
+        if constexpr (KV == COOPT_KV_E4M3) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {                 // a stale scale times a zero weight
+                A.vs[i] = (i < cacheA) ? A.vs[i] : 0.0f;
+                B.vs[i] = (i < cacheB) ? B.vs[i] : 0.0f;
+            }
+        }
+        uint32_t a0, a1, b0, b1;
+        token_masks<KV>(cacheA, a0, a1);
+        token_masks<KV>(cacheB, b0, b1);
+#pragma unroll
+        for (int j = 0; j < BlockRegs<HEAD_DIM, KV>::NL; ++j) {
+            if constexpr (KV == COOPT_KV_E4M3) {
+                A.v[j] &= a0;
+                B.v[j] &= b0;
+            } else {
+                A.v[j] &= u32x4{a0, a1, a0, a1};
+                B.v[j] &= u32x4{b0, b1, b0, b1};
+            }
+        }
+    }
+    const float bm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                           fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+    if (__builtin_amdgcn_ballot_w64(bm > m + kRescaleSlack) != 0) {   // wave-uniform, rare
         float nm = fmaxf(bm, __shfl_xor(bm, 16));
         nm = fmaxf(nm, __shfl_xor(nm, 32));
         nm = fmaxf(nm, m);
@@ -218,17 +293,29 @@ __device__ __forceinline__ void tile_update(const BlockOps<HEAD_DIM>& o,
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
         m = nm;
     }
-    half4_t pop;
+    const float mm = m - kPShift;
+    float p[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float p = __builtin_amdgcn_exp2f(z[i] - m);     // masked: exp2(-inf) = 0
-        l += p;
-        float pv = p;
-        if constexpr (KV == COOPT_KV_E4M3) pv = p * kPScale * o.vs[i];
-        pop[i] = (half_t)((i < n_visible) ? pv : 0.0f);       // stale scales must not leak NaN
+    for (int i = 0; i < 8; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(z[i] - mm);             // invisible: exp2(-inf) = 0
+        l += p[i];
     }
+    if constexpr (KV == COOPT_KV_E4M3) {
 #pragma unroll
-    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x16(o.v[c], pop, acc[c]);
+        for (int i = 0; i < 4; ++i) {
+            p[i] *= A.vs[i];
+            p[4 + i] *= B.vs[i];
+        }
+    }
+    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
+                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) {
+        const half4_t va = v_operand<HEAD_DIM, KV>(A, c);
+        const half4_t vb = v_operand<HEAD_DIM, KV>(B, c);
+        const half8_t vop = {va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
+        acc[c] = mfma_16x16x32(vop, pop, acc[c]);
+    }
 }
 
 }  // namespace coopt

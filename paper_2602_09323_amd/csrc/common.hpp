@@ -20,6 +20,22 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kE4M3Max = 448.0f;
 
+// Element index of (token, dim) inside one cache tile; ES = bytes per element, E = elements per
+// 16 bytes.  K tiles are [d/E chunks][16 tokens][E]; V tiles are [d/(4E)][4][16][E/4][4 tokens].
+template <int ES>
+__host__ __device__ __forceinline__ int k_tile_index(int tok, int dim)
+{
+    constexpr int E = 16 / ES;
+    return ((dim / E) * kBlock + tok) * E + dim % E;
+}
+template <int ES>
+__host__ __device__ __forceinline__ int v_tile_index(int tok, int dim)
+{
+    constexpr int W = 4 / ES;                    // 16-dim groups per 16 bytes
+    const int c = dim >> 4, n = dim & 15;
+    return ((((c / W) * (kBlock / 4) + (tok >> 2)) * 16 + n) * W + c % W) * 4 + (tok & 3);
+}
+
 // Host-side validation common to all entry points.  Returns COOPT_OK or the error to hand back.
 inline int check_shape(const coopt_shape* sh)
 {

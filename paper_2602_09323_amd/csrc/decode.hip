@@ -14,6 +14,8 @@
 //
 // The per-block arithmetic (two MFMA products around an in-register softmax) is in attn_tile.hpp.
 #include "attn_tile.hpp"
+#include "decode_internal.hpp"
+#include "partials.hpp"
 
 namespace coopt {
 
@@ -26,15 +28,16 @@ struct DecodeArgs {
     float* tmp_out;       // partition mode: [S][H_q][max_parts][d]
     float* max_logits;    //                 [S][H_q][max_parts]
     float* exp_sums;
-    int32_t H_q, H_k, G;
+    int32_t num_seqs, H_q, H_k, G;
     int32_t max_blocks;
     int32_t tokens_per_part;   // multiple of 16
     int32_t max_parts;         // parts per (seq, kv head) in the grid
     int32_t direct;            // 1: the single part writes `out`
+    int32_t pool_tiles;        // num_blocks * H_k
     float scale_log2e;         // softmax_scale * log2(e)
 };
 
-template <int HEAD_DIM, int KV, int DEPTH>
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG>
 __global__ void __launch_bounds__(512)
 paged_decode_kernel(const DecodeArgs a)
 {
@@ -44,12 +47,27 @@ paged_decode_kernel(const DecodeArgs a)
     const int nwaves = blockDim.x >> 6;
     const int n = lane & 15, grp = lane >> 4;
 
-    const int part = blockIdx.x % a.max_parts;
-    const int sg = blockIdx.x / a.max_parts;
-    const int g = sg % a.H_k;
-    const int seq = sg / a.H_k;
-    const int t = a.context_lens[seq];
+    // Work item order: token range slowest, then sequence, then KV head.  Consecutive workgroup
+    // ids land on different XCDs, so each XCD gets every 8th (sequence, head) pair of every token
+    // range instead of one token range of all of them, and the ranges that can be empty (beyond
+    // the shorter contexts) sit at the end of the grid.
+    const int g = blockIdx.x % a.H_k;
+    const int sp = blockIdx.x / a.H_k;
+    const int seq = sp % a.num_seqs;
+    const int part = sp / a.num_seqs;
     const int tok0 = part * a.tokens_per_part;
+    const int blk0 = tok0 / kBlock;
+
+    // The first 64 block numbers of this wave are fetched before the context length is known
+    // (bounded by the table row), so that the two loads overlap.  This wave's blocks are
+    // blk0 + wave + i * nwaves.
+    const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks;
+    int idv = 0;
+    {
+        const int b = blk0 + wave + lane * nwaves;
+        if (b < a.max_blocks) idv = bt[b];
+    }
+    const int t = a.context_lens[seq];
     if (tok0 >= t) {
         if (a.direct && part == 0) {                       // empty context: zero rows
             for (int i = threadIdx.x; i < a.G * HEAD_DIM; i += blockDim.x)
@@ -58,11 +76,8 @@ paged_decode_kernel(const DecodeArgs a)
         return;
     }
     const int tok1 = min(t, tok0 + a.tokens_per_part);
-    const int blk0 = tok0 / kBlock;
     const int nblk = (tok1 + kBlock - 1) / kBlock - blk0;
     const int nmine = wave < nblk ? (nblk - wave + nwaves - 1) / nwaves : 0;
-    // this wave's blocks are blk0 + wave + i * nwaves, i < nmine
-    const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks + blk0 + wave;
 
     // q^T operand: head slot n of this group, zero for slots beyond the group size
     half8_t qop[HEAD_DIM / 32];
@@ -74,37 +89,49 @@ paged_decode_kernel(const DecodeArgs a)
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const TileLoader<HEAD_DIM, KV> loader(a.cv, n, grp);
-    BlockRegs<HEAD_DIM, KV> regs[DEPTH];
+    const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
+    BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
 
-    // Up to 64 physical block numbers are fetched with one vector load (lane i holds the i-th) and
-    // handed to the scalar unit with readlane; inside a chunk the loop is a software pipeline with
-    // DEPTH tiles in flight and no data-dependent branch around any load.
+    // Blocks are consumed in groups of two.  Inside a chunk of 64 blocks (32 groups) the loop is a
+    // software pipeline with DEPTH groups in flight and no data-dependent branch around any load;
+    // block numbers reach the scalar unit by readlane from the vector fetched above.
     for (int cb = 0; cb < nmine; cb += 64) {
-        const int nc = min(64, nmine - cb);
-        int idv = 0;
-        if (lane < nc) idv = bt[(cb + lane) * nwaves];
+        if (cb > 0) {
+            idv = 0;
+            if (cb + lane < nmine) idv = bt[blk0 + wave + (cb + lane) * nwaves];
+        }
+        const int nc = min(64, nmine - cb);          // blocks in this chunk
+        const int ng = (nc + 1) >> 1;                // groups in this chunk
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
-            const int id = __builtin_amdgcn_readlane(idv, u);
-            loader.issue(regs[u], (size_t)id * a.H_k + g, u < nc);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int id = __builtin_amdgcn_readlane(idv, 2 * u + h);
+                loader.issue(regs[u][h], id * a.H_k + g, 2 * u + h < nc);
+            }
             __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
         }
-        for (int i = 0; i < nc; i += DEPTH) {
+        for (int i = 0; i < ng; i += DEPTH) {
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
-                const int ii = i + u;
-                const int nx = ii + DEPTH;
-                const int id = __builtin_amdgcn_readlane(idv, min(nx, 63));
-                if (ii < nc) {
-                    const int visible = t - ((blk0 + wave + (cb + ii) * nwaves) * kBlock + 4 * grp);
-                    BlockOps<HEAD_DIM> ops;
-                    convert_block<HEAD_DIM, KV>(ops, regs[u], visible);
-                    tile_update<HEAD_DIM, KV>(ops, qop, m, l, acc, visible, a.scale_log2e);
+                const int gi = i + u;                // group index within the chunk
+                if (gi < ng) {
+                    // tokens of this lane in blocks A and B of the group, relative to the context end
+                    const int baseA = (blk0 + wave + (cb + 2 * gi) * nwaves) * kBlock;   // uniform
+                    const int visA = t - baseA - 4 * grp;
+                    const int visB = (2 * gi + 1 < nc) ? visA - nwaves * kBlock : 0;
+                    const bool tail = (2 * gi + 1 >= nc) || (baseA + (nwaves + 1) * kBlock > t);
+                    group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], qop, m, l, acc, tail, visA,
+                                               visB, visA, visB, a.scale_log2e);
                 }
-                // refill only after the stage's registers are dead, so the load can land in place
+                // refill only after the stage's registers are dead, so the loads can land in place
                 __builtin_amdgcn_sched_barrier(0);
-                loader.issue(regs[u], (size_t)id * a.H_k + g, nx < nc);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int nb = 2 * (gi + DEPTH) + h;
+                    const int id = __builtin_amdgcn_readlane(idv, min(nb, 63));
+                    loader.issue(regs[u][h], id * a.H_k + g, nb < nc);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -134,11 +161,11 @@ paged_decode_kernel(const DecodeArgs a)
         for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + hh]);
         float L = 0.0f, O = 0.0f;
         for (int w = 0; w < nwaves; ++w) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[w * 16 + hh] - M);  // idle waves: exp2(-inf) = 0
+            const float f = __builtin_amdgcn_exp2f(sm_m[w * 16 + hh] - M);  // idle waves: 0
             L += sm_l[w * 16 + hh] * f;
             O += sm_acc[(w * a.G + hh) * HEAD_DIM + dim] * f;
         }
-        const float o = O / L * out_unscale<KV>();
+        const float o = O / L;                           // the common power of two of O and L cancels
         const size_t row = (size_t)seq * a.H_q + g * a.G + hh;
         if (a.direct) {
             a.out[row * HEAD_DIM + dim] = (half_t)o;
@@ -146,7 +173,7 @@ paged_decode_kernel(const DecodeArgs a)
             a.tmp_out[(row * a.max_parts + part) * HEAD_DIM + dim] = o;
             if (dim == 0) {
                 a.max_logits[row * a.max_parts + part] = M * kLn2;
-                a.exp_sums[row * a.max_parts + part] = L;
+                a.exp_sums[row * a.max_parts + part] = L * kPUnshift;
             }
         }
     }
@@ -161,59 +188,44 @@ partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restri
                         int partition_size, int max_parts, half_t* __restrict__ out, int H_q,
                         int num_rows)
 {
-    constexpr int E = HEAD_DIM / 64;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // seq * H_q + head
     if (row >= num_rows) return;
     const int lane = threadIdx.x & 63;
     const int seq = row / H_q;
     const int t = context_lens[seq];
     const int nparts = min((t + partition_size - 1) / partition_size, max_parts);
-    float o[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) o[e] = 0.0f;
-    if (nparts > 0) {
-        const float* ml = max_logits + (size_t)row * max_parts;
-        const float* es = exp_sums + (size_t)row * max_parts;
-        float M = -INFINITY;
-        for (int p = lane; p < nparts; p += 64) M = fmaxf(M, ml[p]);
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) M = fmaxf(M, __shfl_xor(M, s));
-        float W = 0.0f;
-        for (int p = 0; p < nparts; ++p) {
-            const float w = es[p] * __expf(ml[p] - M);
-            W += w;
-#pragma unroll
-            for (int e = 0; e < E; ++e)
-                o[e] += w * tmp_out[((size_t)row * max_parts + p) * HEAD_DIM + lane + 64 * e];
-        }
-        const float inv = 1.0f / W;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] *= inv;
-    }
-#pragma unroll
-    for (int e = 0; e < E; ++e) out[(size_t)row * HEAD_DIM + lane + 64 * e] = (half_t)o[e];
+    merge_row<HEAD_DIM>(max_logits + (size_t)row * max_parts, exp_sums + (size_t)row * max_parts,
+                        tmp_out + (size_t)row * max_parts * HEAD_DIM, nparts,
+                        out + (size_t)row * HEAD_DIM, lane);
 }
 
 // ------------------------------------------------------------------ host side
 
 struct DecodePlan {
-    int tokens_per_group = 256;
-    int waves = 4;
-    int depth = 4;
+    int tokens_per_group = 128;
+    int waves = 1;
+    int depth = 2;          // two-block groups in flight per wavefront
+    int grid_waves = 1024;  // balanced kernel: one wavefront per SIMD of the 256 CUs
 };
 static DecodePlan g_plan;
 
-template <int HEAD_DIM, int KV>
+template <int HEAD_DIM, int KV, bool BIG>
 static void launch_decode_depth(const DecodeArgs& a, int depth, dim3 grid, dim3 block, size_t lds,
                                 hipStream_t stream)
 {
     switch (depth) {
-    case 1: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 1>), grid, block, lds, stream, a); break;
-    case 2: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 2>), grid, block, lds, stream, a); break;
-    case 3: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 3>), grid, block, lds, stream, a); break;
-    case 6: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 6>), grid, block, lds, stream, a); break;
-    default: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 4>), grid, block, lds, stream, a); break;
+    case 1: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, lds, stream, a); break;
+    case 3: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, lds, stream, a); break;
+    default: hipLaunchKernelGGL((paged_decode_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, lds, stream, a); break;
     }
+}
+
+template <int HEAD_DIM, int KV>
+static void launch_decode_pool(const DecodeArgs& a, bool big, int depth, dim3 grid, dim3 block,
+                               size_t lds, hipStream_t stream)
+{
+    if (big) launch_decode_depth<HEAD_DIM, KV, true>(a, depth, grid, block, lds, stream);
+    else launch_decode_depth<HEAD_DIM, KV, false>(a, depth, grid, block, lds, stream);
 }
 
 static size_t decode_lds_bytes(int waves, int G, int head_dim)
@@ -228,12 +240,13 @@ static void launch_decode(const DecodeArgs& a, const coopt_shape* sh, int waves,
     const dim3 grid((unsigned)((long long)sh->num_seqs * sh->num_kv_heads * a.max_parts));
     const dim3 block(64 * waves);
     const size_t lds = decode_lds_bytes(waves, a.G, sh->head_dim);
+    const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
-        if (sh->head_dim == 128) launch_decode_depth<128, COOPT_KV_E4M3>(a, depth, grid, block, lds, stream);
-        else launch_decode_depth<64, COOPT_KV_E4M3>(a, depth, grid, block, lds, stream);
+        if (sh->head_dim == 128) launch_decode_pool<128, COOPT_KV_E4M3>(a, big, depth, grid, block, lds, stream);
+        else launch_decode_pool<64, COOPT_KV_E4M3>(a, big, depth, grid, block, lds, stream);
     } else {
-        if (sh->head_dim == 128) launch_decode_depth<128, COOPT_KV_FP16>(a, depth, grid, block, lds, stream);
-        else launch_decode_depth<64, COOPT_KV_FP16>(a, depth, grid, block, lds, stream);
+        if (sh->head_dim == 128) launch_decode_pool<128, COOPT_KV_FP16>(a, big, depth, grid, block, lds, stream);
+        else launch_decode_pool<64, COOPT_KV_FP16>(a, big, depth, grid, block, lds, stream);
     }
 }
 
@@ -263,10 +276,12 @@ static DecodeArgs make_args(const void* q, const void* k_cache, const void* v_ca
     a.cv = CacheView{(const uint8_t*)k_cache, (const uint8_t*)v_cache, k_scale, v_scale};
     a.block_tables = block_tables;
     a.context_lens = context_lens;
+    a.num_seqs = sh->num_seqs;
     a.H_q = sh->num_q_heads;
     a.H_k = sh->num_kv_heads;
     a.G = sh->num_q_heads / sh->num_kv_heads;
     a.max_blocks = sh->max_blocks_per_seq;
+    a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
     return a;
 }
@@ -290,30 +305,38 @@ static int parts_for(const coopt_shape* sh, int tokens_per_part)
 
 using namespace coopt;
 
-extern "C" int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves, int32_t depth)
+extern "C" int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves, int32_t depth,
+                                     int32_t grid_waves)
 {
     if (tokens_per_group < 0 || tokens_per_group % kBlock != 0) return COOPT_ERR_SHAPE;
     if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return COOPT_ERR_SHAPE;
-    if (depth != 0 && depth != 1 && depth != 2 && depth != 3 && depth != 4 && depth != 6)
-        return COOPT_ERR_SHAPE;
+    if (depth < 0 || depth > 3) return COOPT_ERR_SHAPE;
+    if (grid_waves < 0 || grid_waves > (1 << 20)) return COOPT_ERR_SHAPE;
     if (tokens_per_group) g_plan.tokens_per_group = tokens_per_group;
     if (waves) g_plan.waves = waves;
     if (depth) g_plan.depth = depth;
+    if (grid_waves) g_plan.grid_waves = grid_waves;
     return COOPT_OK;
 }
 
-extern "C" void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves, int32_t* depth)
+extern "C" void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves, int32_t* depth,
+                                      int32_t* grid_waves)
 {
     if (tokens_per_group) *tokens_per_group = g_plan.tokens_per_group;
     if (waves) *waves = g_plan.waves;
     if (depth) *depth = g_plan.depth;
+    if (grid_waves) *grid_waves = g_plan.grid_waves;
+}
+
+static FlatPlan flat_plan()
+{
+    return FlatPlan{g_plan.tokens_per_group, g_plan.waves, g_plan.depth, g_plan.grid_waves};
 }
 
 extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh)
 {
     if (check_shape(sh) != COOPT_OK) return 0;
-    const size_t parts = (size_t)parts_for(sh, g_plan.tokens_per_group);
-    return (size_t)sh->num_seqs * sh->num_q_heads * parts * (sh->head_dim + 2) * sizeof(float);
+    return flat_workspace_bytes(sh, flat_plan());
 }
 
 extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cache,
@@ -331,30 +354,53 @@ extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const 
     hipStream_t stream = (hipStream_t)hip_stream;
     DecodeArgs a = make_args(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
     a.out = (half_t*)out;
-    const int parts = workspace ? parts_for(sh, g_plan.tokens_per_group) : 1;
-    if (parts == 1) {
+    if (!workspace) {
         // one workgroup per (sequence, KV head) covers the whole context and writes `out`
         a.tokens_per_part = sh->max_blocks_per_seq * kBlock;
         a.max_parts = 1;
         a.direct = 1;
-        launch_decode(a, sh, workspace ? g_plan.waves : 8, g_plan.depth, stream);
+        launch_decode(a, sh, 8, g_plan.depth, stream);
         return launch_status();
     }
     if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
-    const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
-    a.tmp_out = (float*)workspace;
-    a.max_logits = a.tmp_out + rows * parts * sh->head_dim;
-    a.exp_sums = a.max_logits + rows * parts;
-    a.tokens_per_part = g_plan.tokens_per_group;
-    a.max_parts = parts;
-    a.direct = 0;
-    launch_decode(a, sh, g_plan.waves, g_plan.depth, stream);
-    st = launch_status();
+    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                           workspace, sh, flat_plan(), stream);
     if (st != COOPT_OK) return st;
-    launch_reduce(a.tmp_out, a.max_logits, a.exp_sums, context_lens, a.tokens_per_part, parts, out,
-                  sh, stream);
-    return launch_status();
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
+}
+
+extern "C" int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
+                                            const float* k_scale, const float* v_scale,
+                                            const int32_t* block_tables,
+                                            const int32_t* context_lens, void* workspace,
+                                            size_t workspace_bytes, const coopt_shape* sh,
+                                            void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
+    if (st != COOPT_OK) return st;
+    if (!workspace) return COOPT_ERR_NULL;
+    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    return launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                             workspace, sh, flat_plan(), (hipStream_t)hip_stream);
+}
+
+extern "C" int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* workspace,
+                                            size_t workspace_bytes, void* out,
+                                            const coopt_shape* sh, void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    if (!context_lens || !workspace || !out) return COOPT_ERR_NULL;
+    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    return launch_flat_merge(context_lens, const_cast<void*>(workspace), out, sh, flat_plan(),
+                             (hipStream_t)hip_stream);
 }
 
 extern "C" int coopt_paged_gqa_decode_partitioned(

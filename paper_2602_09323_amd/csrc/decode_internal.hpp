@@ -1,0 +1,31 @@
+// Host-side glue between the decode entry points (decode.hip) and the load-balanced kernel
+// (decode_flat.hip).
+#pragma once
+
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace coopt {
+
+struct FlatPlan {
+    int tokens_per_group;   // minimum share of a workgroup, in tokens (32 per two-block group)
+    int waves;              // wavefronts per workgroup
+    int depth;              // two-block groups in flight per wavefront
+    int grid_waves;         // wavefronts in the whole grid
+    int min_share_groups() const { return std::max(1, tokens_per_group / (2 * kBlock)); }
+};
+
+size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan);
+
+// Enqueue the balanced split kernel (attention -> partial results in the workspace) and the merge
+// kernel (partials -> fp16 output rows).  Both derive the same schedule from the context lengths
+// and the plan, so the plan must not change between them.  Each returns a coopt_status.
+int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                      const float* v_scale, const int32_t* block_tables,
+                      const int32_t* context_lens, void* workspace, const coopt_shape* sh,
+                      const FlatPlan& plan, hipStream_t stream);
+int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
+                      const FlatPlan& plan, hipStream_t stream);
+
+}  // namespace coopt

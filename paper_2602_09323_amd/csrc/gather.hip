@@ -23,8 +23,9 @@ gather_cached_kv_kernel(const uint8_t* __restrict__ k_cache, const uint8_t* __re
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int dim = lane * E + e;
-        const size_t ki = (tile * kBlock + off) * HEAD_DIM + dim;
-        const size_t vi = (tile * HEAD_DIM + dim) * kBlock + off;
+        constexpr int ES = (KV == COOPT_KV_E4M3) ? 1 : 2;
+        const size_t ki = tile * (kBlock * HEAD_DIM) + k_tile_index<ES>(off, dim);
+        const size_t vi = tile * (kBlock * HEAD_DIM) + v_tile_index<ES>(off, dim);
         half_t kv, vv;
         if constexpr (KV == COOPT_KV_E4M3) {
             const float ks = k_scale[tile * kBlock + off], vs = v_scale[tile * kBlock + off];

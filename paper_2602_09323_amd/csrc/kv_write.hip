@@ -2,8 +2,8 @@
 //
 // One wavefront owns one (token, KV head) row: the 64 lanes hold the row's d elements (d/64 per
 // lane), a butterfly max gives the row's absmax, and each lane encodes and stores its own
-// elements.  K rows land as one contiguous d-byte run; V rows are scattered with stride 16
-// because the V tile keeps the token index innermost.  Write volume is a few hundred bytes per
+// elements.  Both tiles are stored in matrix-core operand order (see attn_tile.hpp), so a row is
+// scattered in 16-byte (K) and 1-byte (V) pieces.  Write volume is a few hundred bytes per
 // row, against kilobytes per token read by attention, so this kernel is latency-, not
 // bandwidth-bound and is kept simple.
 #include "common.hpp"
@@ -61,11 +61,11 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
     const size_t tile = (size_t)(blk * H_k + head);
 
     float x[E], y[E];
-    // ---- K: [NB][H_k][B][d]
+    // ---- K tile [d/16][16 tokens][16]: the lane's E dims are neighbours inside one 16-byte chunk
 #pragma unroll
     for (int e = 0; e < E; ++e) x[e] = (float)k[(size_t)row * HEAD_DIM + lane * E + e];
     float scale = scale_row<E>(x, y);
-    uint8_t* kdst = k_cache + (tile * kBlock + off) * HEAD_DIM + lane * E;
+    uint8_t* kdst = k_cache + tile * (kBlock * HEAD_DIM) + k_tile_index<1>(off, lane * E);
     if constexpr (E == 2) {
         *reinterpret_cast<uint16_t*>(kdst) = (uint16_t)encode_pair(y[0], y[1]);
     } else {
@@ -73,17 +73,17 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
     }
     if (lane == 0) k_scale[tile * kBlock + off] = scale;
 
-    // ---- V: [NB][H_k][d][B]
+    // ---- V tile: token index innermost, one byte per (dim, token)
 #pragma unroll
     for (int e = 0; e < E; ++e) x[e] = (float)v[(size_t)row * HEAD_DIM + lane * E + e];
     scale = scale_row<E>(x, y);
-    uint8_t* vdst = v_cache + (tile * HEAD_DIM + lane * E) * kBlock + off;
+    uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
     if constexpr (E == 2) {
         const uint32_t c = encode_pair(y[0], y[1]);
-        vdst[0] = (uint8_t)(c & 0xffu);
-        vdst[kBlock] = (uint8_t)(c >> 8);
+        vtile[v_tile_index<1>(off, lane * E)] = (uint8_t)(c & 0xffu);
+        vtile[v_tile_index<1>(off, lane * E + 1)] = (uint8_t)(c >> 8);
     } else {
-        *vdst = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
+        vtile[v_tile_index<1>(off, lane)] = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
     }
     if (lane == 0) v_scale[tile * kBlock + off] = scale;
 }
@@ -107,8 +107,8 @@ kv_write_fp16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict_
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int dim = lane * E + e;
-        k_cache[(tile * kBlock + off) * HEAD_DIM + dim] = k[(size_t)row * HEAD_DIM + dim];
-        v_cache[(tile * HEAD_DIM + dim) * kBlock + off] = v[(size_t)row * HEAD_DIM + dim];
+        k_cache[tile * (kBlock * HEAD_DIM) + k_tile_index<2>(off, dim)] = k[(size_t)row * HEAD_DIM + dim];
+        v_cache[tile * (kBlock * HEAD_DIM) + v_tile_index<2>(off, dim)] = v[(size_t)row * HEAD_DIM + dim];
     }
 }
 

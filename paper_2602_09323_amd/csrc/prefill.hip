@@ -20,12 +20,13 @@ struct PrefillArgs {
     half_t* out;
     int32_t H_q, H_k, G;
     int32_t max_blocks;
+    int32_t pool_tiles;
     float scale_log2e;
 };
 
 constexpr int kPrefillWaves = 4;
 
-template <int HEAD_DIM, int KV, int NR, int DEPTH>
+template <int HEAD_DIM, int KV, int NR, int DEPTH, bool BIG>
 __global__ void __launch_bounds__(64 * kPrefillWaves)
 prefill_chunk_kernel(const PrefillArgs a)
 {
@@ -48,7 +49,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     half8_t qop[NR][HEAD_DIM / 32];
     int limit[NR];          // tokens visible to column n of tile r
     int row0[NR], head[NR];
-    int max_limit = 0;
+    int max_limit = 0, min_row = 0x7fffffff;
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         const int tile = min(first_tile + r, total_tiles - 1);   // surplus tiles repeat the last
@@ -59,6 +60,7 @@ prefill_chunk_kernel(const PrefillArgs a)
         row0[r] = i0;
         limit[r] = t_ctx + row + 1;
         max_limit = max(max_limit, t_ctx + min(i0 + 15, C - 1) + 1);
+        min_row = min(min_row, i0);
         load_q_operand<HEAD_DIM, KV>(qop[r], a.q + ((size_t)(qs + row) * a.H_q + head[r]) * HEAD_DIM,
                                      true, grp);
     }
@@ -75,36 +77,49 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const TileLoader<HEAD_DIM, KV> loader(a.cv, n, grp);
-    BlockRegs<HEAD_DIM, KV> regs[DEPTH];
+    const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
+    BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
+    const int full_limit = min(t, t_ctx + min_row + 1);   // tokens visible to every column
     for (int cb = 0; cb < nblk; cb += 64) {          // 64 block numbers per vector load
         const int nc = min(64, nblk - cb);
+        const int ng = (nc + 1) >> 1;
         int idv = 0;
         if (lane < nc) idv = bt[cb + lane];
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
-            const int id = __builtin_amdgcn_readlane(idv, u);
-            loader.issue(regs[u], (size_t)id * a.H_k + g, u < nc);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int id = __builtin_amdgcn_readlane(idv, 2 * u + h);
+                loader.issue(regs[u][h], id * a.H_k + g, 2 * u + h < nc);
+            }
             __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
         }
-        for (int i = 0; i < nc; i += DEPTH) {
+        for (int i = 0; i < ng; i += DEPTH) {
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
-                const int ii = i + u;
-                const int nx = ii + DEPTH;
-                const int id = __builtin_amdgcn_readlane(idv, min(nx, 63));
-                const int tok_lane = (cb + ii) * kBlock + 4 * grp;
-                if (ii < nc) {
-                    BlockOps<HEAD_DIM> ops;
-                    convert_block<HEAD_DIM, KV>(ops, regs[u], t - tok_lane);
+                const int gi = i + u;
+                if (gi < ng) {
+                    const int baseA = (cb + 2 * gi) * kBlock;           // uniform
+                    const int tokA = baseA + 4 * grp;
+                    const bool hasB = 2 * gi + 1 < nc;
+                    const int cacheA = t - tokA, cacheB = hasB ? cacheA - kBlock : 0;
+                    const bool tail = !(hasB && baseA + 2 * kBlock <= full_limit);
 #pragma unroll
-                    for (int r = 0; r < NR; ++r)
-                        tile_update<HEAD_DIM, KV>(ops, qop[r], m[r], l[r], acc[r],
-                                                  limit[r] - tok_lane, a.scale_log2e);
+                    for (int r = 0; r < NR; ++r) {
+                        const int visA = limit[r] - tokA;
+                        group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], qop[r], m[r], l[r], acc[r],
+                                                   tail, visA, hasB ? visA - kBlock : 0, cacheA, cacheB,
+                                                   a.scale_log2e);
+                    }
                 }
-                // refill only after the stage's registers are dead, so the load can land in place
+                // refill only after the stage's registers are dead, so the loads can land in place
                 __builtin_amdgcn_sched_barrier(0);
-                loader.issue(regs[u], (size_t)id * a.H_k + g, nx < nc);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int nb = 2 * (gi + DEPTH) + h;
+                    const int id = __builtin_amdgcn_readlane(idv, min(nb, 63));
+                    loader.issue(regs[u][h], id * a.H_k + g, nb < nc);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -115,7 +130,7 @@ prefill_chunk_kernel(const PrefillArgs a)
         float L = l[r];
         L += __shfl_xor(L, 16);
         L += __shfl_xor(L, 32);
-        const float inv = out_unscale<KV>() / L;
+        const float inv = 1.0f / L;                       // the common power of two of acc and l cancels
         const int row = row0[r] + n;
         if (first_tile + r < total_tiles && row < C) {
             half_t* dst = a.out + ((size_t)(qs + row) * a.H_q + head[r]) * HEAD_DIM + 4 * grp;
@@ -162,24 +177,25 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     a.H_k = sh->num_kv_heads;
     a.G = sh->num_q_heads / sh->num_kv_heads;
     a.max_blocks = sh->max_blocks_per_seq;
+    a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
 
-    constexpr int NR = 2, DEPTH = 2;
+    constexpr int NR = 2, DEPTH = 1;
     const int tiles = a.G * ((max_chunk_len + 15) / 16);
     const dim3 grid((unsigned)((tiles + kPrefillWaves * NR - 1) / (kPrefillWaves * NR)),
                     (unsigned)(sh->num_seqs * sh->num_kv_heads));
     const dim3 block(64 * kPrefillWaves);
     hipStream_t stream = (hipStream_t)hip_stream;
+#define COOPT_PREFILL(D, KV, BIG) \
+    hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, NR, DEPTH, BIG>), grid, block, 0, stream, a)
+    const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
-        if (sh->head_dim == 128)
-            hipLaunchKernelGGL((prefill_chunk_kernel<128, COOPT_KV_E4M3, NR, DEPTH>), grid, block, 0, stream, a);
-        else
-            hipLaunchKernelGGL((prefill_chunk_kernel<64, COOPT_KV_E4M3, NR, DEPTH>), grid, block, 0, stream, a);
+        if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E4M3, true); else COOPT_PREFILL(128, COOPT_KV_E4M3, false); }
+        else { if (big) COOPT_PREFILL(64, COOPT_KV_E4M3, true); else COOPT_PREFILL(64, COOPT_KV_E4M3, false); }
     } else {
-        if (sh->head_dim == 128)
-            hipLaunchKernelGGL((prefill_chunk_kernel<128, COOPT_KV_FP16, NR, DEPTH>), grid, block, 0, stream, a);
-        else
-            hipLaunchKernelGGL((prefill_chunk_kernel<64, COOPT_KV_FP16, NR, DEPTH>), grid, block, 0, stream, a);
+        if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_FP16, true); else COOPT_PREFILL(128, COOPT_KV_FP16, false); }
+        else { if (big) COOPT_PREFILL(64, COOPT_KV_FP16, true); else COOPT_PREFILL(64, COOPT_KV_FP16, false); }
     }
+#undef COOPT_PREFILL
     return launch_status();
 }

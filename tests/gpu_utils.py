@@ -27,8 +27,8 @@ def cache_to_dev(cache):
 def alloc_dev_cache(w, fill_byte=0):
     """Device cache in the boundary layouts, every byte preset to fill_byte."""
     es = 1 if w.kv_dtype == "e4m3" else 2
-    k_cache = torch.full((w.NB, w.H_k, w.B, w.d * es), fill_byte, dtype=torch.uint8, device="cuda")
-    v_cache = torch.full((w.NB, w.H_k, w.d, w.B * es), fill_byte, dtype=torch.uint8, device="cuda")
+    k_cache = torch.full((w.NB, w.H_k, w.B * w.d * es), fill_byte, dtype=torch.uint8, device="cuda")
+    v_cache = torch.full((w.NB, w.H_k, w.B * w.d * es), fill_byte, dtype=torch.uint8, device="cuda")
     if w.kv_dtype == "e4m3":
         k_scale = torch.full((w.NB, w.H_k, w.B * 4), fill_byte, dtype=torch.uint8, device="cuda")
         v_scale = torch.full((w.NB, w.H_k, w.B * 4), fill_byte, dtype=torch.uint8, device="cuda")

@@ -8,25 +8,58 @@ def e4m3_table() -> np.ndarray:
     return torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
 
 
+def k_tile_index(d, E, B=16):
+    """Element offsets [tok, dim] inside a K tile: 16-byte chunks of a token's row, chunk-major
+    ([d/E][B][E]); E = elements per 16 bytes.  Restated from the public header, not from the oracle."""
+    tok, dim = np.meshgrid(np.arange(B), np.arange(d), indexing="ij")
+    return ((dim // E) * B + tok) * E + dim % E
+
+
+def v_tile_index(d, E, B=16):
+    """Element offsets [tok, dim] inside a V tile ([d/(4E)][B/4][16][E/4][4], tokens innermost)."""
+    tok, dim = np.meshgrid(np.arange(B), np.arange(d), indexing="ij")
+    W, c, n = E // 4, dim // 16, dim % 16
+    return ((((c // W) * (B // 4) + tok // 4) * 16 + n) * W + c % W) * 4 + tok % 4
+
+
+def _E(w):
+    return 16 if w.kv_dtype == "e4m3" else 8
+
+
+def k_logical(w, k_cache):
+    """[NB, H_k, B, d] copy of the K cache in plain (token, dim) order."""
+    return k_cache.reshape(w.NB, w.H_k, w.B * w.d)[:, :, k_tile_index(w.d, _E(w), w.B)]
+
+
+def v_logical(w, v_cache):
+    """[NB, H_k, B, d] copy of the V cache in plain (token, dim) order."""
+    return v_cache.reshape(w.NB, w.H_k, w.B * w.d)[:, :, v_tile_index(w.d, _E(w), w.B)]
+
+
+def k_store_logical(w, k_cache, logical):
+    k_cache.reshape(w.NB, w.H_k, w.B * w.d)[:, :, k_tile_index(w.d, _E(w), w.B)] = logical
+
+
+def v_store_logical(w, v_cache, logical):
+    v_cache.reshape(w.NB, w.H_k, w.B * w.d)[:, :, v_tile_index(w.d, _E(w), w.B)] = logical
+
+
 def alloc_cache(w, fill_byte=None):
-    """Empty paged cache for workload ``w`` in the boundary layouts (numpy, host)."""
+    """Empty paged cache for workload ``w`` (numpy, host): tiles of B*d elements per (block, head)
+    in the boundary's tile order, scales [NB, H_k, B]."""
+    dt = np.uint8 if w.kv_dtype == "e4m3" else np.float16
+    k_cache = np.zeros((w.NB, w.H_k, w.B * w.d), dtype=dt)
+    v_cache = np.zeros((w.NB, w.H_k, w.B * w.d), dtype=dt)
+    k_scale = v_scale = None
     if w.kv_dtype == "e4m3":
-        k_cache = np.zeros((w.NB, w.H_k, w.B, w.d), dtype=np.uint8)
-        v_cache = np.zeros((w.NB, w.H_k, w.d, w.B), dtype=np.uint8)
         k_scale = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32)
         v_scale = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32)
-        if fill_byte is not None:
-            k_cache[...] = fill_byte
-            v_cache[...] = fill_byte
+    if fill_byte is not None:
+        k_cache.view(np.uint8)[...] = fill_byte
+        v_cache.view(np.uint8)[...] = fill_byte
+        if k_scale is not None:
             k_scale[...] = np.float32(np.nan)
             v_scale[...] = np.float32(np.nan)
-    else:
-        k_cache = np.zeros((w.NB, w.H_k, w.B, w.d), dtype=np.float16)
-        v_cache = np.zeros((w.NB, w.H_k, w.d, w.B), dtype=np.float16)
-        k_scale = v_scale = None
-        if fill_byte is not None:
-            k_cache.view(np.uint8)[...] = fill_byte
-            v_cache.view(np.uint8)[...] = fill_byte
     return k_cache, v_cache, k_scale, v_scale
 
 
@@ -51,17 +84,18 @@ def oracle_fill(oracle, w, idx=None, cache=None):
 def gather_dequant(w, cache, s):
     """Contiguous dequantised K, V [t, H_k, d] float64 of sequence s, by direct indexing."""
     k_cache, v_cache, k_scale, v_scale = cache
+    kl, vl = k_logical(w, k_cache), v_logical(w, v_cache)
     t = int(w.context_lens[s])
     K = np.zeros((t, w.H_k, w.d)); V = np.zeros((t, w.H_k, w.d))
     table = e4m3_table()
     for j in range(t):
         pb = int(w.block_tables[s, j // w.B]); off = j % w.B
         if w.kv_dtype == "e4m3":
-            K[j] = table[k_cache[pb, :, off, :]] * k_scale[pb, :, off].astype(np.float64)[:, None]
-            V[j] = table[v_cache[pb, :, :, off]] * v_scale[pb, :, off].astype(np.float64)[:, None]
+            K[j] = table[kl[pb, :, off, :]] * k_scale[pb, :, off].astype(np.float64)[:, None]
+            V[j] = table[vl[pb, :, off, :]] * v_scale[pb, :, off].astype(np.float64)[:, None]
         else:
-            K[j] = k_cache[pb, :, off, :].astype(np.float64)
-            V[j] = v_cache[pb, :, :, off].astype(np.float64)
+            K[j] = kl[pb, :, off, :].astype(np.float64)
+            V[j] = vl[pb, :, off, :].astype(np.float64)
     return K, V
 
 

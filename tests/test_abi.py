@@ -86,5 +86,6 @@ def test_null_pointers_and_bad_arguments(lib):
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, None, one, one, 8, ctypes.byref(sh), None) == -1
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 5, 0, 4, one, one, ctypes.byref(sh), None) == -2
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 0, 0, 999, one, one, ctypes.byref(sh), None) == -2
-    assert lib.coopt_set_decode_plan(100, 0, 0) == -2 and lib.coopt_set_decode_plan(0, 3, 0) == -2
-    assert lib.coopt_set_decode_plan(0, 0, 5) == -2 and lib.coopt_set_decode_plan(0, 0, 0) == 0
+    assert lib.coopt_set_decode_plan(100, 0, 0, 0) == -2 and lib.coopt_set_decode_plan(0, 3, 0, 0) == -2
+    assert lib.coopt_set_decode_plan(0, 0, 4, 0) == -2 and lib.coopt_set_decode_plan(0, 0, 0, -1) == -2
+    assert lib.coopt_set_decode_plan(0, 0, 0, 0) == 0

@@ -22,9 +22,9 @@ def _oracle_decode(oracle, w, cache, q=None, lens=None, tables=None):
 
 @pytest.fixture(autouse=True)
 def _default_plan():
-    coopt.set_decode_plan(256, 4, 4)
+    saved = coopt.get_decode_plan()
     yield
-    coopt.set_decode_plan(256, 4, 4)
+    coopt.set_decode_plan(*saved)
 
 
 def test_tiny_config(oracle_mod):
@@ -50,8 +50,10 @@ def test_ragged_lengths_and_group_sizes(oracle_mod, kv_dtype, H_q, H_k, d):
         assert_close(got, ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} split={split}")
 
 
-@pytest.mark.parametrize("plan", [(16, 1, 1), (64, 2, 2), (128, 1, 3), (128, 8, 4), (512, 4, 6),
-                                  (1024, 8, 2), (256, 4, 4)])
+@pytest.mark.parametrize("plan", [(32, 1, 1, 64), (32, 1, 2, 2048), (64, 2, 2, 512),
+                                  (128, 1, 3, 2048), (128, 8, 2, 2048), (512, 4, 3, 256),
+                                  (1024, 8, 2, 2048), (256, 4, 1, 24), (128, 1, 2, 7),
+                                  (32, 2, 2, 6), (128, 1, 2, 2048)])
 def test_every_launch_plan_gives_the_same_answer(oracle_mod, plan):
     lens = [300, 1, 1025, 47, 640]
     w = workloads.make_custom("plan", seed=32, S=len(lens), H_q=10, H_k=2, d=128, B=16, NB=160,

@@ -16,8 +16,9 @@ def _compare_caches(w, host, devc, what):
     for name, a, b in zip(names, host, got):
         if a is None:
             continue
-        au = a.view(np.uint8) if a.dtype == np.uint8 else a.view(np.uint32 if a.dtype == np.float32 else np.uint16)
-        bu = b.view(au.dtype)
+        au = (a.view(np.uint8) if a.dtype == np.uint8 else
+              a.view(np.uint32 if a.dtype == np.float32 else np.uint16)).reshape(-1)
+        bu = b.view(au.dtype).reshape(-1)
         bad = np.nonzero(au != bu)
         assert bad[0].size == 0, f"{what}: {name} differs at {bad[0].size} places, first {tuple(x[0] for x in bad)}"
 

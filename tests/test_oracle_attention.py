@@ -11,7 +11,8 @@ import torch
 from hypothesis import given, settings, strategies as st
 
 import workloads
-from helpers import alloc_cache, gather_dequant, oracle_fill, softmax_attention
+from helpers import (alloc_cache, gather_dequant, k_logical, k_store_logical, oracle_fill,
+                     softmax_attention, v_logical, v_store_logical)
 
 
 def _decode(oracle, w, cache, q=None, lens=None, tables=None):
@@ -22,7 +23,7 @@ def _decode(oracle, w, cache, q=None, lens=None, tables=None):
 
 
 @settings(max_examples=25, deadline=None)
-@given(S=st.integers(1, 3), H_k=st.integers(1, 3), G=st.integers(1, 4), d=st.sampled_from([8, 64]),
+@given(S=st.integers(1, 3), H_k=st.integers(1, 3), G=st.integers(1, 4), d=st.sampled_from([64, 128]),
        seed=st.integers(0, 10_000), data=st.data())
 def test_decode_equals_contiguous_attention(oracle_mod, S, H_k, G, d, seed, data):
     lens = [data.draw(st.integers(1, 50)) for _ in range(S)]
@@ -134,8 +135,12 @@ def test_invalid_tokens_and_blocks_never_read(oracle_mod):
     used = np.zeros((w.NB, w.B), bool)
     used.reshape(-1)[w.slots] = True
     unused_scale = np.broadcast_to(~used[:, None, :], k_scale.shape)
-    k_cache[np.broadcast_to(~used[:, None, :, None], k_cache.shape)] = 0x7F
-    v_cache[np.broadcast_to(~used[:, None, None, :], v_cache.shape)] = 0x7F
+    kl, vl = k_logical(w, k_cache), v_logical(w, v_cache)
+    unused = np.broadcast_to(~used[:, None, :, None], kl.shape)
+    kl[unused] = 0x7F
+    vl[unused] = 0x7F
+    k_store_logical(w, k_cache, kl)
+    v_store_logical(w, v_cache, vl)
     k_scale[unused_scale] = np.nan
     v_scale[unused_scale] = np.nan
     tables = w.block_tables.copy()

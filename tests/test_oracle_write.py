@@ -6,18 +6,19 @@ import numpy as np
 import pytest
 
 import workloads
-from helpers import alloc_cache, e4m3_table, oracle_fill
+from helpers import alloc_cache, e4m3_table, k_logical, k_tile_index, oracle_fill, v_logical, v_tile_index
 
 
 def _one_row(oracle, row_k, row_v=None, B=16):
     d = row_k.shape[0]
     k = np.ascontiguousarray(row_k.reshape(1, 1, d).astype(np.float16))
     v = np.ascontiguousarray((row_k if row_v is None else row_v).reshape(1, 1, d).astype(np.float16))
-    k_cache = np.zeros((1, 1, B, d), np.uint8); v_cache = np.zeros((1, 1, d, B), np.uint8)
+    k_cache = np.zeros((1, 1, B * d), np.uint8); v_cache = np.zeros((1, 1, B * d), np.uint8)
     k_scale = np.zeros((1, 1, B), np.float32); v_scale = np.zeros((1, 1, B), np.float32)
     oracle.kv_cache_write_fp8(k, v, np.array([3], np.int64), k_cache, v_cache, k_scale, v_scale,
                               H_k=1, d=d, B=B)
-    return k_cache[0, 0, 3], v_cache[0, 0, :, 3], k_scale[0, 0, 3], v_scale[0, 0, 3]
+    return (k_cache[0, 0, k_tile_index(d, 16, B)[3]], v_cache[0, 0, v_tile_index(d, 16, B)[3]],
+            k_scale[0, 0, 3], v_scale[0, 0, 3])
 
 
 def test_amax_element_maps_to_448(oracle_mod):
@@ -99,12 +100,13 @@ def test_skip_rule_and_untouched_slots(oracle_mod):
                                   H_k=w.H_k, d=w.d, B=w.B)
     written = np.zeros(w.NB * w.B, bool); written[slots[~skip]] = True
     wr = written.reshape(w.NB, w.B)
+    k_cache, v_cache = k_logical(w, k_cache), v_logical(w, v_cache)
     for blk in range(w.NB):
         for off in range(w.B):
             if wr[blk, off]:
                 assert not np.isnan(k_scale[blk, :, off]).any()
             else:
-                assert np.all(k_cache[blk, :, off, :] == 0xA5) and np.all(v_cache[blk, :, :, off] == 0xA5)
+                assert np.all(k_cache[blk, :, off, :] == 0xA5) and np.all(v_cache[blk, :, off, :] == 0xA5)
                 assert np.isnan(k_scale[blk, :, off]).all() and np.isnan(v_scale[blk, :, off]).all()
 
 
@@ -117,6 +119,7 @@ def test_slot_and_block_indexing_brute_force(oracle_mod):
     for i in order:
         oracle_fill(oracle_mod, w, idx=np.array([i]), cache=cache)
     k_cache, v_cache, k_scale, v_scale = cache
+    k_cache, v_cache = k_logical(w, k_cache), v_logical(w, v_cache)
     rows = {}
     for s in range(w.S):
         for j in range(int(w.context_lens[s])):
@@ -127,7 +130,7 @@ def test_slot_and_block_indexing_brute_force(oracle_mod):
         for g in range(w.H_k):
             kc, vc, ks, vs = _one_row(oracle_mod, w.k_ctx[i, g], w.v_ctx[i, g])
             assert np.array_equal(k_cache[pb, g, off, :], kc)
-            assert np.array_equal(v_cache[pb, g, :, off], vc)
+            assert np.array_equal(v_cache[pb, g, off, :], vc)
             assert k_scale[pb, g, off] == ks and v_scale[pb, g, off] == vs
 
 
@@ -135,9 +138,10 @@ def test_fp16_write_is_a_pure_scatter(oracle_mod):
     w = workloads.make_custom("f16", seed=7, S=2, H_q=4, H_k=4, d=64, B=16, NB=8,
                               context_lens=[17, 30], kv_dtype="fp16")
     k_cache, v_cache, _, _ = oracle_fill(oracle_mod, w)
+    k_cache, v_cache = k_logical(w, k_cache), v_logical(w, v_cache)
     for s in range(w.S):
         for j in range(int(w.context_lens[s])):
             i = int(w.seq_start[s]) + j
             pb = int(w.block_tables[s, j // w.B]); off = j % w.B
             assert np.array_equal(k_cache[pb, :, off, :].view(np.uint16), w.k_ctx[i].view(np.uint16))
-            assert np.array_equal(v_cache[pb, :, :, off].view(np.uint16), w.v_ctx[i].view(np.uint16))
+            assert np.array_equal(v_cache[pb, :, off, :].view(np.uint16), w.v_ctx[i].view(np.uint16))
