@@ -59,7 +59,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3],
                     help="workload (1 = LLaMa-13B GQA FP8 decode, the headline configuration)")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
-    ap.add_argument("--plan", type=str, default="", help="tokens_per_group,waves,depth (tuning)")
+    ap.add_argument("--plan", type=str, default="",
+                    help="decode plan fields in header order, comma separated (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -83,7 +84,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.plan:
-        coopt.set_decode_plan(*[int(x) for x in args.plan.split(",")])
+        names = [f for f, _ in coopt.DecodePlan._fields_]
+        coopt.set_decode_plan(**dict(zip(names, [int(x) for x in args.plan.split(",")])))
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -186,7 +188,7 @@ def main():
 
     # ---- dominant kernel alone (the balanced split kernel of the decode call): the same rotation
     # over pools, launches back to back on the stream, one event pair around them.
-    tokens_per_group, plan_waves, plan_depth, plan_grid = coopt.get_decode_plan()
+    plan = coopt.get_decode_plan()
 
     def kern(i):
         kc, vc, ks, vs = pools[i % layers]
@@ -213,8 +215,7 @@ def main():
         "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
                    "head_dim": w.d, "block_size": w.B, "context_tokens": ab["tokens"],
                    "kv_pools_rotated": layers,
-                   "decode_plan": {"tokens_per_group": tokens_per_group, "waves": plan_waves,
-                                   "depth": plan_depth, "grid_waves": plan_grid}, "step": "kv_cache_write + paged_gqa_decode, one layer",
+                   "decode_plan": plan, "step": "kv_cache_write + paged_gqa_decode, one layer",
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),

@@ -146,20 +146,25 @@ size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
 
 /*
  * Launch plan (tuning knobs, process-wide, not thread-safe against concurrent decode calls).
- * coopt_paged_gqa_decode with a workspace cuts the flattened work of the batch into equal shares,
+ * coopt_paged_gqa_decode with a workspace flattens the batch's work and cuts it into equal shares,
  * one per workgroup: `grid_waves` wavefronts in the whole grid, `waves_per_group` (1, 2, 4 or 8)
  * per workgroup, a share never smaller than `tokens_per_group` tokens (a positive multiple of 32).
  * coopt_paged_gqa_decode_partitioned uses waves_per_group per partition.  In both, every wavefront
- * keeps `pipeline_depth` (1, 2 or 3) two-block groups of the cache in flight.  Zero keeps the
- * current value.  Returns COOPT_ERR_SHAPE on a bad value and then changes nothing.  Changing
- * tokens_per_group changes coopt_decode_workspace_bytes.
+ * keeps `pipeline_depth` (1, 2 or 3) two-block groups of the cache in flight.
+ * coopt_set_decode_plan validates every field and returns COOPT_ERR_SHAPE (changing nothing) if
+ * one is out of range; tokens_per_group changes coopt_decode_workspace_bytes.
  */
-int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves_per_group,
-                          int32_t pipeline_depth, int32_t grid_waves);
+typedef struct coopt_decode_plan {
+    int32_t tokens_per_group;
+    int32_t waves_per_group;
+    int32_t pipeline_depth;
+    int32_t grid_waves;
+} coopt_decode_plan;
 
-/* Reads the current plan into the four host integers (any may be NULL). */
-void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves_per_group,
-                           int32_t* pipeline_depth, int32_t* grid_waves);
+int coopt_set_decode_plan(const coopt_decode_plan* plan);
+
+/* Copies the current plan into *plan (host memory). */
+void coopt_get_decode_plan(coopt_decode_plan* plan);
 
 /*
  * Partitioned decode for long contexts (the "partitioned parallel" reduction of the paper's

@@ -30,6 +30,12 @@ class CooptError(RuntimeError):
     pass
 
 
+class DecodePlan(ctypes.Structure):
+    """Mirror of ``coopt_decode_plan``."""
+    _fields_ = [("tokens_per_group", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
+                ("pipeline_depth", ctypes.c_int32), ("grid_waves", ctypes.c_int32)]
+
+
 class Shape(ctypes.Structure):
     """Mirror of ``coopt_shape``."""
     _fields_ = [("num_seqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
@@ -60,9 +66,8 @@ def load_library():
         lib.coopt_paged_gqa_decode_merge.argtypes = [vp, vp, ctypes.c_size_t, vp, shp, vp]
         lib.coopt_decode_workspace_bytes.argtypes = [shp]
         lib.coopt_decode_workspace_bytes.restype = ctypes.c_size_t
-        lib.coopt_set_decode_plan.argtypes = [i32, i32, i32, i32]
-        i32p = ctypes.POINTER(ctypes.c_int32)
-        lib.coopt_get_decode_plan.argtypes = [i32p, i32p, i32p, i32p]
+        lib.coopt_set_decode_plan.argtypes = [ctypes.POINTER(DecodePlan)]
+        lib.coopt_get_decode_plan.argtypes = [ctypes.POINTER(DecodePlan)]
         lib.coopt_get_decode_plan.restype = None
         lib.coopt_paged_gqa_decode_partitioned.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, shp, vp]
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
@@ -115,18 +120,22 @@ def decode_workspace_bytes(shape: Shape) -> int:
     return int(load_library().coopt_decode_workspace_bytes(ctypes.byref(shape)))
 
 
-def set_decode_plan(tokens_per_group: int = 0, waves_per_group: int = 0,
-                    pipeline_depth: int = 0, grid_waves: int = 0) -> None:
-    _check(load_library().coopt_set_decode_plan(tokens_per_group, waves_per_group, pipeline_depth,
-                                                grid_waves), "coopt_set_decode_plan")
+def get_decode_plan() -> dict:
+    """The plan currently in force, as a dict of the fields of ``coopt_decode_plan``."""
+    p = DecodePlan()
+    load_library().coopt_get_decode_plan(ctypes.byref(p))
+    return {name: int(getattr(p, name)) for name, _ in DecodePlan._fields_}
 
 
-def get_decode_plan():
-    """(tokens_per_group, waves_per_group, pipeline_depth, grid_waves) currently in force."""
-    t, w, d, g = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
-    load_library().coopt_get_decode_plan(ctypes.byref(t), ctypes.byref(w), ctypes.byref(d),
-                                         ctypes.byref(g))
-    return t.value, w.value, d.value, g.value
+def set_decode_plan(**fields) -> None:
+    """Update the named fields of the plan (see ``coopt_decode_plan``); the others keep their value."""
+    cur = get_decode_plan()
+    for k in fields:
+        if k not in cur:
+            raise KeyError(k)
+    cur.update(fields)
+    p = DecodePlan(*[cur[name] for name, _ in DecodePlan._fields_])
+    _check(load_library().coopt_set_decode_plan(ctypes.byref(p)), "coopt_set_decode_plan")
 
 
 def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, out,

@@ -201,13 +201,8 @@ partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restri
 
 // ------------------------------------------------------------------ host side
 
-struct DecodePlan {
-    int tokens_per_group = 128;
-    int waves = 1;
-    int depth = 2;          // two-block groups in flight per wavefront
-    int grid_waves = 1024;  // balanced kernel: one wavefront per SIMD of the 256 CUs
-};
-static DecodePlan g_plan;
+// tokens_per_group, waves per workgroup, depth, grid waves (one wavefront per SIMD of the 256 CUs)
+static coopt_decode_plan g_plan = {128, 1, 2, 1024};
 
 template <int HEAD_DIM, int KV, bool BIG>
 static void launch_decode_depth(const DecodeArgs& a, int depth, dim3 grid, dim3 block, size_t lds,
@@ -305,32 +300,27 @@ static int parts_for(const coopt_shape* sh, int tokens_per_part)
 
 using namespace coopt;
 
-extern "C" int coopt_set_decode_plan(int32_t tokens_per_group, int32_t waves, int32_t depth,
-                                     int32_t grid_waves)
+extern "C" int coopt_set_decode_plan(const coopt_decode_plan* p)
 {
-    if (tokens_per_group < 0 || tokens_per_group % kBlock != 0) return COOPT_ERR_SHAPE;
-    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return COOPT_ERR_SHAPE;
-    if (depth < 0 || depth > 3) return COOPT_ERR_SHAPE;
-    if (grid_waves < 0 || grid_waves > (1 << 20)) return COOPT_ERR_SHAPE;
-    if (tokens_per_group) g_plan.tokens_per_group = tokens_per_group;
-    if (waves) g_plan.waves = waves;
-    if (depth) g_plan.depth = depth;
-    if (grid_waves) g_plan.grid_waves = grid_waves;
+    if (!p) return COOPT_ERR_NULL;
+    if (p->tokens_per_group <= 0 || p->tokens_per_group % (2 * kBlock) != 0) return COOPT_ERR_SHAPE;
+    const int w = p->waves_per_group;
+    if (w != 1 && w != 2 && w != 4 && w != 8) return COOPT_ERR_SHAPE;
+    if (p->pipeline_depth < 1 || p->pipeline_depth > 3) return COOPT_ERR_SHAPE;
+    if (p->grid_waves <= 0 || p->grid_waves > (1 << 20)) return COOPT_ERR_SHAPE;
+    g_plan = *p;
     return COOPT_OK;
 }
 
-extern "C" void coopt_get_decode_plan(int32_t* tokens_per_group, int32_t* waves, int32_t* depth,
-                                      int32_t* grid_waves)
+extern "C" void coopt_get_decode_plan(coopt_decode_plan* p)
 {
-    if (tokens_per_group) *tokens_per_group = g_plan.tokens_per_group;
-    if (waves) *waves = g_plan.waves;
-    if (depth) *depth = g_plan.depth;
-    if (grid_waves) *grid_waves = g_plan.grid_waves;
+    if (p) *p = g_plan;
 }
 
 static FlatPlan flat_plan()
 {
-    return FlatPlan{g_plan.tokens_per_group, g_plan.waves, g_plan.depth, g_plan.grid_waves};
+    return FlatPlan{g_plan.tokens_per_group, g_plan.waves_per_group, g_plan.pipeline_depth,
+                    g_plan.grid_waves};
 }
 
 extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh)
@@ -359,7 +349,7 @@ extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const 
         a.tokens_per_part = sh->max_blocks_per_seq * kBlock;
         a.max_parts = 1;
         a.direct = 1;
-        launch_decode(a, sh, 8, g_plan.depth, stream);
+        launch_decode(a, sh, 8, g_plan.pipeline_depth, stream);
         return launch_status();
     }
     if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
@@ -425,7 +415,7 @@ extern "C" int coopt_paged_gqa_decode_partitioned(
     a.tokens_per_part = partition_size;
     a.max_parts = max_parts;
     a.direct = 0;
-    launch_decode(a, sh, g_plan.waves, g_plan.depth, (hipStream_t)hip_stream);
+    launch_decode(a, sh, g_plan.waves_per_group, g_plan.pipeline_depth, (hipStream_t)hip_stream);
     return launch_status();
 }
 

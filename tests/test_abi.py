@@ -35,10 +35,16 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(binding.EXPORTS) == names
 
 
-def test_shape_struct_matches_header():
+def _struct_fields(name):
+    body = re.search(r"typedef struct %s \{(.*?)\}" % name, open(HEADER).read(), flags=re.S).group(1)
+    return re.findall(r"^\s+(?:int32_t|float)\s+(\w+);", body, flags=re.M)
+
+
+def test_structs_match_header():
     assert ctypes.sizeof(coopt.Shape) == 9 * 4
-    fields = re.findall(r"^\s+(?:int32_t|float)\s+(\w+);", open(HEADER).read(), flags=re.M)
-    assert [f[0] for f in coopt.Shape._fields_] == fields
+    assert [f[0] for f in coopt.Shape._fields_] == _struct_fields("coopt_shape")
+    assert ctypes.sizeof(coopt.DecodePlan) == 4 * 4
+    assert [f[0] for f in coopt.DecodePlan._fields_] == _struct_fields("coopt_decode_plan")
 
 
 def test_status_strings(lib):
@@ -86,6 +92,12 @@ def test_null_pointers_and_bad_arguments(lib):
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, None, one, one, 8, ctypes.byref(sh), None) == -1
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 5, 0, 4, one, one, ctypes.byref(sh), None) == -2
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 0, 0, 999, one, one, ctypes.byref(sh), None) == -2
-    assert lib.coopt_set_decode_plan(100, 0, 0, 0) == -2 and lib.coopt_set_decode_plan(0, 3, 0, 0) == -2
-    assert lib.coopt_set_decode_plan(0, 0, 4, 0) == -2 and lib.coopt_set_decode_plan(0, 0, 0, -1) == -2
-    assert lib.coopt_set_decode_plan(0, 0, 0, 0) == 0
+    good = dict(coopt.get_decode_plan())
+    for bad in (dict(tokens_per_group=100), dict(tokens_per_group=0), dict(waves_per_group=3),
+                dict(pipeline_depth=4), dict(pipeline_depth=0), dict(grid_waves=0),
+                dict(grid_waves=-5)):
+        with pytest.raises(coopt.CooptError):
+            coopt.set_decode_plan(**bad)
+        assert coopt.get_decode_plan() == good        # a refused plan changes nothing
+    coopt.set_decode_plan(**good)
+    assert lib.coopt_set_decode_plan(None) == -1

@@ -24,7 +24,7 @@ def _oracle_decode(oracle, w, cache, q=None, lens=None, tables=None):
 def _default_plan():
     saved = coopt.get_decode_plan()
     yield
-    coopt.set_decode_plan(*saved)
+    coopt.set_decode_plan(**saved)
 
 
 def test_tiny_config(oracle_mod):
@@ -50,18 +50,24 @@ def test_ragged_lengths_and_group_sizes(oracle_mod, kv_dtype, H_q, H_k, d):
         assert_close(got, ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} split={split}")
 
 
+def _plan(tokens, waves, depth, grid):
+    return dict(tokens_per_group=tokens, waves_per_group=waves, pipeline_depth=depth,
+                grid_waves=grid)
+
+
 @pytest.mark.parametrize("plan", [(32, 1, 1, 64), (32, 1, 2, 2048), (64, 2, 2, 512),
                                   (128, 1, 3, 2048), (128, 8, 2, 2048), (512, 4, 3, 256),
                                   (1024, 8, 2, 2048), (256, 4, 1, 24), (128, 1, 2, 7),
-                                  (32, 2, 2, 6), (128, 1, 2, 2048)])
+                                  (32, 2, 2, 6), (128, 1, 2, 1024)])
 def test_every_launch_plan_gives_the_same_answer(oracle_mod, plan):
     lens = [300, 1, 1025, 47, 640]
     w = workloads.make_custom("plan", seed=32, S=len(lens), H_q=10, H_k=2, d=128, B=16, NB=160,
                               context_lens=lens, max_blocks=80)
     cache = oracle_fill(oracle_mod, w)
     ref = _oracle_decode(oracle_mod, w, cache)
-    coopt.set_decode_plan(*plan)
-    got = hip_decode(w, cache_to_dev(cache), split=True)
+    coopt.set_decode_plan(**_plan(*plan))
+    dcache = cache_to_dev(cache)
+    got = hip_decode(w, dcache, split=True)
     assert_close(got, ref, f"plan {plan}")
 
 
@@ -117,6 +123,43 @@ def test_maximum_length_fills_the_block_table(oracle_mod):
     ref = _oracle_decode(oracle_mod, w, cache)
     for split in (False, True):
         assert_close(hip_decode(w, cache_to_dev(cache), split=split), ref, "full table")
+
+
+@pytest.mark.parametrize("S", [65, 150, 300])
+def test_many_short_sequences(oracle_mod, S):
+    """More than 64 sequences (the schedule scans the lengths in tiles of 64), many of them
+    shorter than one share, some empty."""
+    rng = np.random.default_rng(S)
+    lens = rng.integers(1, 200, size=S)
+    lens[rng.integers(0, S, size=S // 10)] = 0
+    lens[S // 2] = 700
+    w = workloads.make_custom("many", seed=38, S=S, H_q=8, H_k=2, d=128, B=16, NB=2600,
+                              context_lens=np.maximum(lens, 1), max_blocks=44)
+    cache = oracle_fill(oracle_mod, w)
+    lens = lens.astype(np.int32)
+    ref = _oracle_decode(oracle_mod, w, cache, lens=lens)
+    dcache = cache_to_dev(cache)
+    for plan in [(128, 1, 2, 1024), (32, 1, 1, 4096), (256, 4, 2, 64), (64, 1, 2, 96)]:
+        coopt.set_decode_plan(**_plan(*plan))
+        got = hip_decode(w, dcache, lens=lens, split=True)
+        assert np.all(got[lens == 0] == 0)
+        assert_close(got, ref, f"S={S} plan={plan}")
+
+
+def test_split_and_merge_as_separate_calls(oracle_mod):
+    w = workloads.make_custom("sm", seed=39, S=5, H_q=10, H_k=2, d=128, B=16, NB=160,
+                              context_lens=[300, 1, 1025, 47, 640], max_blocks=80)
+    cache = oracle_fill(oracle_mod, w)
+    ref = _oracle_decode(oracle_mod, w, cache)
+    shape = shape_of(w)
+    dcache = cache_to_dev(cache)
+    ws = torch.empty(coopt.decode_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
+    dlen = dev(w.context_lens)
+    coopt.paged_gqa_decode_split(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables), dlen, ws, shape)
+    coopt.paged_gqa_decode_merge(dlen, ws, out, shape)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy().astype(np.float64), ref, "split+merge")
 
 
 def test_decode_step_end_to_end_on_device(oracle_mod):
