@@ -229,7 +229,7 @@ def main():
         if pmc and not args.plan:
             traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
         achieved = alg / (kern_us * 1e-6) / 1e9
-        result["roofline"] = {"bound": "hbm", "kernel": "flat_decode_kernel (coopt_paged_gqa_decode_split)",
+        result["roofline"] = {"bound": "hbm", "kernel": "flat_stream_kernel (coopt_paged_gqa_decode_split)",
                               "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                               "algorithmic_bytes_per_launch": int(alg),

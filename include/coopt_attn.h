@@ -146,11 +146,13 @@ size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
 
 /*
  * Launch plan (tuning knobs, process-wide, not thread-safe against concurrent decode calls).
- * coopt_paged_gqa_decode with a workspace flattens the batch's work and cuts it into equal shares,
- * one per workgroup: `grid_waves` wavefronts in the whole grid, `waves_per_group` (1, 2, 4 or 8)
- * per workgroup, a share never smaller than `tokens_per_group` tokens (a positive multiple of 32).
- * coopt_paged_gqa_decode_partitioned uses waves_per_group per partition.  In both, every wavefront
- * keeps `pipeline_depth` (1, 2 or 3) two-block groups of the cache in flight.
+ * coopt_paged_gqa_decode with a workspace flattens the batch's work and cuts it into shares that
+ * differ by at most one two-block group, one share per single-wavefront workgroup: at most
+ * `grid_waves` wavefronts in the whole grid, a share never smaller than `tokens_per_group` tokens
+ * (a positive multiple of 32) unless the whole batch is.  coopt_paged_gqa_decode_partitioned runs
+ * `waves_per_group` (1, 2, 4 or 8) wavefronts per partition; the balanced kernel ignores that
+ * field.  In both, every wavefront keeps `pipeline_depth` (1, 2 or 3) two-block groups of the
+ * cache in flight.
  * coopt_set_decode_plan validates every field and returns COOPT_ERR_SHAPE (changing nothing) if
  * one is out of range; tokens_per_group changes coopt_decode_workspace_bytes.
  */

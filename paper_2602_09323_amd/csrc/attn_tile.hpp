@@ -176,6 +176,23 @@ __device__ __forceinline__ void load_q_operand(half8_t (&qop)[HEAD_DIM / 32], co
     }
 }
 
+// The same operand through a buffer descriptor over the G query rows of one (sequence, KV head)
+// pair: no branch around the loads, lanes of absent heads (n >= G) fall outside the descriptor and
+// read zeros, and `valid` = false (wave-uniform) turns the whole load into zeros.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void load_q_operand_rows(half8_t (&qop)[HEAD_DIM / 32],
+                                                    const half_t* pair_rows, int G, bool valid,
+                                                    int n, int grp)
+{
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half_t*>(pair_rows), 0, valid ? G * HEAD_DIM * 2 : 0, 0x00020000);
+#pragma unroll
+    for (int jj = 0; jj < HEAD_DIM / 32; ++jj)
+        qop[jj] = __builtin_bit_cast(
+            half8_t, __builtin_amdgcn_raw_buffer_load_b128(
+                         rq, 2 * (n * HEAD_DIM + q_dim_offset<HEAD_DIM, KV>(jj, grp)), 0, 0));
+}
+
 // K operand number jj (8 dims of token n) of a loaded tile.
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ half8_t k_operand(const BlockRegs<HEAD_DIM, KV>& r, int jj)

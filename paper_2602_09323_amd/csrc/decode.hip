@@ -319,8 +319,7 @@ extern "C" void coopt_get_decode_plan(coopt_decode_plan* p)
 
 static FlatPlan flat_plan()
 {
-    return FlatPlan{g_plan.tokens_per_group, g_plan.waves_per_group, g_plan.pipeline_depth,
-                    g_plan.grid_waves};
+    return FlatPlan{g_plan.tokens_per_group, g_plan.pipeline_depth, g_plan.grid_waves};
 }
 
 extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh)

@@ -2,18 +2,18 @@
 // coopt_paged_gqa_decode when a workspace is given (Opt-KV Eq. 6, Opt-GQA Eq. 7-8, Opt-Pa Eq. 9-10).
 //
 // Decode is a stream of ~2 KB tiles read once, so the kernel is organised around keeping as many
-// tile loads in flight as early as possible and ending all workgroups at the same time:
+// tile loads in flight as early as possible and ending all wavefronts at the same time:
 //
 //   * The work of the whole batch is flattened into one sequence of two-block groups, ordered
-//     [sequence][KV head][group], and cut into equal contiguous shares, one per workgroup
-//     (share = max(min_share, ceil(total / workgroups))).  Context lengths live on the device, so
-//     every workgroup derives the schedule itself: one vector load of the lengths and a wave scan.
-//     There are no empty or short workgroups, and consecutive workgroup ids (which land on
-//     different XCDs) carry equal work.
-//   * A share may straddle the boundary between two (sequence, KV head) pairs.  It is processed as
-//     segments, one per pair; a segment's groups go round-robin to the waves of the workgroup,
-//     each wave runs the software-pipelined group loop over its own, and the waves are merged
-//     through LDS into ONE partial (m, l, o) per segment.
+//     [sequence][KV head][group], and cut into contiguous shares that differ by at most one group,
+//     one share per single-wave workgroup.  Context lengths live on the device, so every workgroup
+//     derives the schedule itself: one vector load of the lengths and a wave scan.  There are no
+//     empty or short workgroups, and consecutive workgroup ids (which land on different XCDs)
+//     carry equal work.
+//   * A share may straddle the boundary between (sequence, KV head) pairs; the part in one pair is
+//     a segment.  The software pipeline runs across segment boundaries: tiles of the next pair are
+//     in flight while the current pair's last groups are consumed, and a segment ends with ONE
+//     partial (m, l, o) stored straight from the accumulator registers.
 //   * Partial j of a pair is written by workgroup first_wg(pair) + j, and the pair's first
 //     workgroup also records how many partials the pair gets; the merge kernel combines them into
 //     the fp16 output rows.
@@ -116,154 +116,155 @@ struct FlatArgs {
     float scale_log2e;
 };
 
-__device__ __forceinline__ int flat_share(int total, int num_groups, int min_share)
-{
-    return max(min_share, (total + num_groups - 1) / num_groups);
-}
+// How the flattened groups are cut into contiguous shares: `nwg` workgroups, the first `r` with
+// q + 1 groups and the rest with q, so no two shares differ by more than one group.  q is at least
+// the plan's minimum share unless the whole batch is smaller than that.
+struct FlatCut {
+    int nwg, q, r;
+    __host__ __device__ FlatCut(int total, int grid, int min_share)
+    {
+        nwg = max(1, min(grid, total / max(min_share, 1)));
+        q = total / nwg;
+        r = total - q * nwg;
+    }
+    __host__ __device__ int begin(int wg) const { return wg * q + min(wg, r); }
+    __host__ __device__ int wg_of(int x) const
+    {
+        const int xr = r * (q + 1);
+        return x < xr ? x / (q + 1) : r + (x - xr) / max(q, 1);
+    }
+};
 
+// One wave per workgroup; the wave's share is ONE stream of groups that runs across the
+// boundaries between (sequence, KV head) pairs.  The loads of the next pair's first groups are in
+// flight while the last groups of the current pair are being consumed, and the pair's partial is
+// stored from the accumulator registers in between.  The block numbers of up to 32 groups come from
+// one gathered vector load (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
 template <int HEAD_DIM, int KV, int DEPTH, bool BIG>
-__global__ void __launch_bounds__(512)
-flat_decode_kernel(const FlatArgs a)
+__global__ void __launch_bounds__(64)
+flat_stream_kernel(const FlatArgs a)
 {
-    extern __shared__ float smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = wave_uniform((int)(threadIdx.x >> 6));
-    const int nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x;
     const int n = lane & 15, grp = lane >> 4;
 
     const FlatSchedule sched(a.context_lens, a.num_seqs, a.H_k, lane);
     const int total = sched.total();
-    const int share = flat_share(total, gridDim.x, a.min_share);
-    const int x_begin = blockIdx.x * share;
-    if (x_begin >= total) return;
-    const int x_end = min(total, x_begin + share);
+    if (total == 0) return;
+    const FlatCut cut(total, gridDim.x, a.min_share);
+    if ((int)blockIdx.x >= cut.nwg) return;
+    const int x_begin = cut.begin(blockIdx.x), x_end = cut.begin(blockIdx.x + 1);
 
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
     BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
+    half8_t q_cur[HEAD_DIM / 32], q_nxt[HEAD_DIM / 32];
+    float m = -INFINITY, l = 0.0f;
+    floatx4 acc[HEAD_DIM / 16];
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int x = x_begin; x < x_end;) {
-        // ---- segment: the part of this workgroup's share that lies in one (sequence, KV head)
-        int seq, seq_first, t;
-        sched.locate(x, seq, seq_first, t);
-        const int nb = (t + kBlock - 1) / kBlock;
-        const int ng = (nb + 1) >> 1;
-        const int g = (x - seq_first) / ng;
-        const int gi0 = x - seq_first - g * ng;            // first group of the segment in the pair
-        const int seg = min(x_end - x, ng - gi0);          // groups in the segment
-        const int pair_first = seq_first + g * ng;
-        const int slot = blockIdx.x - pair_first / share;
-        if (slot == 0 && threadIdx.x == 0)              // the pair's first workgroup counts its partials
-            a.counts[seq * a.H_k + g] = (pair_first + ng - 1) / share - pair_first / share + 1;
-        x += seg;
+    for (int xc = x_begin; xc < x_end; xc += 32) {
+        const int nc = min(32, x_end - xc);                 // groups in this chunk
+        // ---- per-lane description of entry j = lane / 2, block h = lane & 1
+        const int xl = xc + (lane >> 1);
+        int seq_l = 0, first_l = 0, t_l = 0;
+        for (int xs = xc; xs < xc + nc;) {
+            int s, first, t;
+            sched.locate(xs, s, first, t);
+            const int span_end = first + a.H_k * groups_of(t);     // > xs: the owner has groups
+            if (xl >= xs && xl < span_end) { seq_l = s; first_l = first; t_l = t; }
+            xs = span_end;
+        }
+        const int nb_l = (t_l + kBlock - 1) / kBlock;
+        const int ng_l = max((nb_l + 1) >> 1, 1);
+        const int g_l = (xl - first_l) / ng_l;
+        const int gi_l = xl - first_l - g_l * ng_l;
+        const int b_l = 2 * gi_l + (lane & 1);
+        const bool in_chunk = (lane >> 1) < nc;
+        int tile_l = -1;
+        if (in_chunk && b_l < nb_l) tile_l = a.block_tables[(size_t)seq_l * a.max_blocks + b_l] * a.H_k + g_l;
+        // entries that end a segment: last group of their pair, or last group of the share
+        const unsigned long long last_mask = __builtin_amdgcn_ballot_w64(
+            in_chunk && (lane & 1) == 0 && (gi_l == ng_l - 1 || xl == x_end - 1));
 
-        // this wave's groups: gi0 + wave + i * nwaves, i < nmine
-        const int nmine = wave < seg ? (seg - wave + nwaves - 1) / nwaves : 0;
-        const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks;
-
-        half8_t qop[HEAD_DIM / 32];
-        load_q_operand<HEAD_DIM, KV>(qop, a.q + ((size_t)seq * a.H_q + g * a.G + n) * HEAD_DIM,
-                                     n < a.G, grp);
-        float m = -INFINITY, l = 0.0f;
-        floatx4 acc[HEAD_DIM / 16];
-#pragma unroll
-        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-        // 32 groups (64 block numbers, lane 2i+h = block h of the wave's i-th group) per vector
-        // load; inside such a chunk the loop is a software pipeline with DEPTH groups in flight and
-        // no data-dependent branch around any load.
-        for (int cg = 0; cg < nmine; cg += 32) {
-            const int ncg = min(32, nmine - cg);                    // groups in this chunk
-            int idv = 0;
-            {
-                const int b = 2 * (gi0 + wave + (cg + (lane >> 1)) * nwaves) + (lane & 1);
-                if ((lane >> 1) < ncg && b < nb) idv = bt[b];
-            }
-            auto block_of = [&](int gi, int h) {                     // logical block, gi within chunk
-                return 2 * (gi0 + wave + (cg + gi) * nwaves) + h;
-            };
-#pragma unroll
-            for (int u = 0; u < DEPTH; ++u) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int id = __builtin_amdgcn_readlane(idv, 2 * u + h);
-                    loader.issue(regs[u][h], id * a.H_k + g, u < ncg && block_of(u, h) < nb);
-                }
-                __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
-            }
-            for (int i = 0; i < ncg; i += DEPTH) {
-#pragma unroll
-                for (int u = 0; u < DEPTH; ++u) {
-                    const int gi = i + u;
-                    if (gi < ncg) {
-                        const int baseA = block_of(gi, 0) * kBlock;          // wave-uniform
-                        const int visA = t - baseA - 4 * grp;
-                        group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], qop, m, l, acc,
-                                                   baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
-                                                   visA - kBlock, a.scale_log2e);
-                    }
-                    // refill only after the stage's registers are dead, so the loads land in place
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int gn = gi + DEPTH;
-                        const int id = __builtin_amdgcn_readlane(idv, min(2 * gn + h, 63));
-                        loader.issue(regs[u][h], id * a.H_k + g, gn < ncg && block_of(gn, h) < nb);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
+        auto q_rows = [&](int e) {         // q rows of the pair that entry e belongs to
+            const int s = __builtin_amdgcn_readlane(seq_l, 2 * e), g = __builtin_amdgcn_readlane(g_l, 2 * e);
+            return a.q + ((size_t)s * a.H_q + g * a.G) * HEAD_DIM;
+        };
+        // first entry of the segment after the one that contains entry e (nc if there is none)
+        auto next_segment = [&](int e) {
+            const unsigned long long rest = e < 32 ? last_mask >> (2 * e) : 0ull;
+            return rest ? e + (__builtin_ctzll(rest) >> 1) + 1 : nc;
+        };
+        load_q_operand_rows<HEAD_DIM, KV>(q_cur, q_rows(0), a.G, true, n, grp);
+        {
+            const int e1 = next_segment(0);
+            load_q_operand_rows<HEAD_DIM, KV>(q_nxt, q_rows(min(e1, nc - 1)), a.G, e1 < nc, n, grp);
         }
 
-        // ---- one partial per segment
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const size_t row0 = (size_t)seq * a.H_q + g * a.G;
-        if (nwaves == 1) {
-            // straight from the accumulator registers: lane (n, grp) owns dims 16c+4grp..+3 of head n
-            if (n < a.G) {
-                const float inv = 1.0f / l;
-                float* dst = a.tmp_out + ((row0 + n) * a.max_slots + slot) * HEAD_DIM + 4 * grp;
+        auto issue_entry = [&](BlockRegs<HEAD_DIM, KV> (&r)[2], int e) {
+            const int ec = min(e, 31);
+            const int tA = __builtin_amdgcn_readlane(tile_l, 2 * ec);
+            const int tB = __builtin_amdgcn_readlane(tile_l, 2 * ec + 1);
+            loader.issue(r[0], max(tA, 0), e < nc && tA >= 0);
+            loader.issue(r[1], max(tB, 0), e < nc && tB >= 0);
+        };
 #pragma unroll
-                for (int c = 0; c < HEAD_DIM / 16; ++c)
-                    *reinterpret_cast<floatx4*>(dst + 16 * c) = acc[c] * inv;
-                if (grp == 0) {
-                    a.max_logits[(row0 + n) * a.max_slots + slot] = m * kLn2;
-                    a.exp_sums[(row0 + n) * a.max_slots + slot] = l * kPUnshift;
-                }
-            }
-        } else {
-            // smem: acc [nwaves][G][HEAD_DIM], then m [nwaves][16], then l [nwaves][16]
-            float* sm_acc = smem;
-            float* sm_m = smem + nwaves * a.G * HEAD_DIM;
-            float* sm_l = sm_m + nwaves * 16;
-            if (n < a.G) {
+        for (int u = 0; u < DEPTH; ++u) {
+            issue_entry(regs[u], u);
+            __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
+        }
+        for (int j = 0; j < nc; j += DEPTH) {
 #pragma unroll
-                for (int c = 0; c < HEAD_DIM / 16; ++c)
-                    *reinterpret_cast<floatx4*>(sm_acc + ((wave * a.G + n) * HEAD_DIM + 16 * c + 4 * grp)) =
-                        acc[c];
-            }
-            if (grp == 0) {
-                sm_m[wave * 16 + n] = m;
-                sm_l[wave * 16 + n] = l;
-            }
-            __syncthreads();
-            for (int idx = threadIdx.x; idx < a.G * HEAD_DIM; idx += blockDim.x) {
-                const int hh = idx / HEAD_DIM, dim = idx - hh * HEAD_DIM;
-                float M = -INFINITY;
-                for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + hh]);
-                float L = 0.0f, O = 0.0f;
-                for (int w = 0; w < nwaves; ++w) {
-                    const float f = __builtin_amdgcn_exp2f(sm_m[w * 16 + hh] - M);   // idle waves: 0
-                    L += sm_l[w * 16 + hh] * f;
-                    O += sm_acc[(w * a.G + hh) * HEAD_DIM + dim] * f;
+            for (int u = 0; u < DEPTH; ++u) {
+                const int e = j + u;
+                if (e < nc) {
+                    const int t = __builtin_amdgcn_readlane(t_l, 2 * e);
+                    const int gi = __builtin_amdgcn_readlane(gi_l, 2 * e);
+                    const int baseA = 2 * gi * kBlock;
+                    const int visA = t - baseA - 4 * grp;
+                    group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], q_cur, m, l, acc,
+                                               baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
+                                               visA - kBlock, a.scale_log2e);
+                    if ((last_mask >> (2 * e)) & 1) {
+                        // ---- the segment's partial, straight from the accumulator registers:
+                        // lane (n, grp) owns dims 16c+4grp..+3 of head n
+                        const int seq = __builtin_amdgcn_readlane(seq_l, 2 * e);
+                        const int g = __builtin_amdgcn_readlane(g_l, 2 * e);
+                        const int ng = (((t + kBlock - 1) / kBlock) + 1) >> 1;
+                        const int pair_first = xc + e - gi;
+                        const int slot = blockIdx.x - cut.wg_of(pair_first);
+                        if (slot == 0 && lane == 0)      // the pair's first workgroup counts its partials
+                            a.counts[seq * a.H_k + g] = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+                        l += __shfl_xor(l, 16);
+                        l += __shfl_xor(l, 32);
+                        if (n < a.G) {
+                            const size_t row = (size_t)seq * a.H_q + g * a.G + n;
+                            const float inv = 1.0f / l;
+                            float* dst = a.tmp_out + (row * a.max_slots + slot) * HEAD_DIM + 4 * grp;
+#pragma unroll
+                            for (int c = 0; c < HEAD_DIM / 16; ++c)
+                                *reinterpret_cast<floatx4*>(dst + 16 * c) = acc[c] * inv;
+                            if (grp == 0) {
+                                a.max_logits[row * a.max_slots + slot] = m * kLn2;
+                                a.exp_sums[row * a.max_slots + slot] = l * kPUnshift;
+                            }
+                        }
+                        m = -INFINITY;
+                        l = 0.0f;
+#pragma unroll
+                        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        // the next segment's q is already here; fetch the one after it
+#pragma unroll
+                        for (int jj = 0; jj < HEAD_DIM / 32; ++jj) q_cur[jj] = q_nxt[jj];
+                        const int e2 = next_segment(e + 1);
+                        load_q_operand_rows<HEAD_DIM, KV>(q_nxt, q_rows(min(e2, nc - 1)), a.G, e2 < nc, n, grp);
+                    }
                 }
-                a.tmp_out[((row0 + hh) * a.max_slots + slot) * HEAD_DIM + dim] = O / L;
-                if (dim == 0) {
-                    a.max_logits[(row0 + hh) * a.max_slots + slot] = M * kLn2;
-                    a.exp_sums[(row0 + hh) * a.max_slots + slot] = L * kPUnshift;
-                }
+                // refill only after the stage's registers are dead, so the loads land in place
+                __builtin_amdgcn_sched_barrier(0);
+                issue_entry(regs[u], e + DEPTH);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __syncthreads();       // LDS is reused by the next segment
         }
     }
 }
@@ -350,22 +351,21 @@ flat_merge_kernel(const FlatArgs a)
 }
 
 template <int HEAD_DIM, int KV, bool BIG>
-static void launch_flat_depth(const FlatArgs& a, int depth, dim3 grid, dim3 block, size_t lds,
-                              hipStream_t stream)
+static void launch_flat_depth(const FlatArgs& a, int depth, dim3 grid, hipStream_t stream)
 {
+    const dim3 block(64);
     switch (depth) {
-    case 1: hipLaunchKernelGGL((flat_decode_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, lds, stream, a); break;
-    case 3: hipLaunchKernelGGL((flat_decode_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, lds, stream, a); break;
-    default: hipLaunchKernelGGL((flat_decode_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, lds, stream, a); break;
+    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, 0, stream, a); break;
+    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, 0, stream, a); break;
     }
 }
 
 template <int HEAD_DIM, int KV>
-static void launch_flat_pool(const FlatArgs& a, bool big, int depth, dim3 grid, dim3 block,
-                             size_t lds, hipStream_t stream)
+static void launch_flat_pool(const FlatArgs& a, bool big, int depth, dim3 grid, hipStream_t stream)
 {
-    if (big) launch_flat_depth<HEAD_DIM, KV, true>(a, depth, grid, block, lds, stream);
-    else launch_flat_depth<HEAD_DIM, KV, false>(a, depth, grid, block, lds, stream);
+    if (big) launch_flat_depth<HEAD_DIM, KV, true>(a, depth, grid, stream);
+    else launch_flat_depth<HEAD_DIM, KV, false>(a, depth, grid, stream);
 }
 
 int flat_max_slots(const coopt_shape* sh, const FlatPlan& plan)
@@ -382,19 +382,14 @@ size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan)
            (size_t)sh->num_seqs * sh->num_kv_heads * sizeof(int32_t);
 }
 
-static int flat_grid_groups(const coopt_shape* sh, const FlatPlan& plan, int& waves)
+// Workgroups (= wavefronts) to launch: the plan's grid, but never more than the work's upper bound
+// at the minimum share.
+static int flat_grid_groups(const coopt_shape* sh, const FlatPlan& plan)
 {
-    const int G = sh->num_q_heads / sh->num_kv_heads;
-    waves = plan.waves;
-    while (waves > 1 && ((size_t)waves * G * sh->head_dim + 2 * waves * 16) * sizeof(float) > 48 * 1024)
-        waves /= 2;
-    // enough workgroups to give every wave slot of the chip one wave, but never more than the
-    // work's upper bound at the minimum share
     const int min_share = plan.min_share_groups();
     const long long max_total =
         (long long)sh->num_seqs * sh->num_kv_heads * ((sh->max_blocks_per_seq + 1) / 2);
-    long long groups = plan.grid_waves / waves;
-    groups = std::min(groups, (max_total + min_share - 1) / min_share);
+    const long long groups = std::min((long long)plan.grid_waves, (max_total + min_share - 1) / min_share);
     return (int)std::max(groups, 1LL);
 }
 
@@ -428,17 +423,14 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
     a.cv = CacheView{(const uint8_t*)k_cache, (const uint8_t*)v_cache, k_scale, v_scale};
     a.block_tables = block_tables;
     a.context_lens = context_lens;
-    int waves;
-    const int groups = flat_grid_groups(sh, plan, waves);
-    const dim3 grid((unsigned)groups), block(64 * waves);
-    const size_t lds = waves > 1 ? ((size_t)waves * a.G * sh->head_dim + 2 * waves * 16) * sizeof(float) : 0;
+    const dim3 grid((unsigned)flat_grid_groups(sh, plan));
     const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
-        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan.depth, grid, block, lds, stream);
-        else launch_flat_pool<64, COOPT_KV_E4M3>(a, big, plan.depth, grid, block, lds, stream);
+        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan.depth, grid, stream);
+        else launch_flat_pool<64, COOPT_KV_E4M3>(a, big, plan.depth, grid, stream);
     } else {
-        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_FP16>(a, big, plan.depth, grid, block, lds, stream);
-        else launch_flat_pool<64, COOPT_KV_FP16>(a, big, plan.depth, grid, block, lds, stream);
+        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_FP16>(a, big, plan.depth, grid, stream);
+        else launch_flat_pool<64, COOPT_KV_FP16>(a, big, plan.depth, grid, stream);
     }
     return launch_status();
 }

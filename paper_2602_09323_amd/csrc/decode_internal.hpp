@@ -10,9 +10,8 @@ namespace coopt {
 
 struct FlatPlan {
     int tokens_per_group;   // minimum share of a workgroup, in tokens (32 per two-block group)
-    int waves;              // wavefronts per workgroup
     int depth;              // two-block groups in flight per wavefront
-    int grid_waves;         // wavefronts in the whole grid
+    int grid_waves;         // wavefronts (= single-wave workgroups) in the whole grid
     int min_share_groups() const { return std::max(1, tokens_per_group / (2 * kBlock)); }
 };
 

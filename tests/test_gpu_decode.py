@@ -58,7 +58,8 @@ def _plan(tokens, waves, depth, grid):
 @pytest.mark.parametrize("plan", [(32, 1, 1, 64), (32, 1, 2, 2048), (64, 2, 2, 512),
                                   (128, 1, 3, 2048), (128, 8, 2, 2048), (512, 4, 3, 256),
                                   (1024, 8, 2, 2048), (256, 4, 1, 24), (128, 1, 2, 7),
-                                  (32, 2, 2, 6), (128, 1, 2, 1024)])
+                                  (32, 2, 2, 6), (128, 1, 2, 1024), (128, 1, 2, 2), (128, 1, 3, 3),
+                                  (2048, 1, 1, 1024)])
 def test_every_launch_plan_gives_the_same_answer(oracle_mod, plan):
     lens = [300, 1, 1025, 47, 640]
     w = workloads.make_custom("plan", seed=32, S=len(lens), H_q=10, H_k=2, d=128, B=16, NB=160,
