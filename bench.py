@@ -31,9 +31,9 @@ HBM_PEAK_GBS = 8000.0
 # 256 MiB device copy: FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  The summaries
 # with the commands are under profiles/; the figures belong to the default decode plan.
 PMC_TRAFFIC = {
-    "llama13b_gqa_fp8_decode": {"fetch_kib": 37907.6, "fetch_scale": 2.0,
-                                "write_kib": 3389.6, "write_scale": 1.0,
-                                "source": "profiles/flat_decode_kernel_llama13b_gqa_fp8_decode.md"},
+    "llama13b_gqa_fp8_decode": {"fetch_kib": 37957.3, "fetch_scale": 2.0,
+                                "write_kib": 3372.2, "write_scale": 1.0,
+                                "source": "profiles/flat_stream_kernel_llama13b_gqa_fp8_decode.md"},
 }
 
 

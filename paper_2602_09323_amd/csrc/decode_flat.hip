@@ -5,15 +5,17 @@
 // tile loads in flight as early as possible and ending all wavefronts at the same time:
 //
 //   * The work of the whole batch is flattened into one sequence of two-block groups, ordered
-//     [sequence][KV head][group], and cut into contiguous shares that differ by at most one group,
-//     one share per single-wave workgroup.  Context lengths live on the device, so every workgroup
-//     derives the schedule itself: one vector load of the lengths and a wave scan.  There are no
-//     empty or short workgroups, and consecutive workgroup ids (which land on different XCDs)
-//     carry equal work.
+//     [sequence][KV head][group], and cut into contiguous shares, one per single-wave workgroup.
+//     The cut is made on a cost axis that charges a few group times for every (sequence, KV head)
+//     pair that ends inside a share; shares differ by at most one cost unit.  Context lengths live
+//     on the device, so every workgroup derives the schedule itself: one vector load of the
+//     lengths and wave scans.  There are no empty or short workgroups, and consecutive workgroup
+//     ids (which land on different XCDs) carry equal work.
 //   * A share may straddle the boundary between (sequence, KV head) pairs; the part in one pair is
 //     a segment.  The software pipeline runs across segment boundaries: tiles of the next pair are
-//     in flight while the current pair's last groups are consumed, and a segment ends with ONE
-//     partial (m, l, o) stored straight from the accumulator registers.
+//     in flight while the current pair's last groups are consumed, the next pair's q operand waits
+//     in LDS, and a segment that ends mid-share parks its partial (m, l, o) in LDS so that no store
+//     sits between the tile loads; partials go to memory when the share is done.
 //   * Partial j of a pair is written by workgroup first_wg(pair) + j, and the pair's first
 //     workgroup also records how many partials the pair gets; the merge kernel combines them into
 //     the fp16 output rows.
@@ -44,29 +46,40 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     return v;
 }
 
-// The flattened schedule, derived identically by every wavefront that needs it.
+// The flattened schedule, derived identically by every wavefront that needs it.  Two axes run
+// side by side over [sequence][KV head][group]: the REAL one counts groups; the COST one also gives
+// every (sequence, KV head) pair `extra` units in front of its groups, the price (in group times)
+// of ending a pair inside a share: the masked last group and the hand-over to the next pair.
+// Shares are cut on the cost axis, so a wave that crosses a pair boundary gets fewer groups.
 struct FlatSchedule {
     const int32_t* lens;
-    int S, H_k, lane;
+    int S, H_k, extra, lane;
     // cache of the first 64 sequences (the whole batch when S <= 64)
-    int t0, incl0, total0;
+    int t0, incl0, total0, cincl0, ctotal0;
 
-    __device__ __forceinline__ FlatSchedule(const int32_t* context_lens, int num_seqs, int kv_heads,
-                                            int lane_id)
-        : lens(context_lens), S(num_seqs), H_k(kv_heads), lane(lane_id)
+    __device__ __forceinline__ int real_weight(int t) const { return H_k * groups_of(t); }
+    __device__ __forceinline__ int cost_weight(int t) const
     {
-        t0 = lane < S ? lens[lane] : 0;
-        incl0 = wave_inclusive_scan(H_k * groups_of(t0));
-        total0 = __builtin_amdgcn_readlane(incl0, 63);
+        return t > 0 ? H_k * (groups_of(t) + extra) : 0;
     }
 
-    // Groups (times KV heads) of the whole batch.
-    __device__ __forceinline__ int total() const
+    __device__ __forceinline__ FlatSchedule(const int32_t* context_lens, int num_seqs, int kv_heads,
+                                            int pair_extra, int lane_id)
+        : lens(context_lens), S(num_seqs), H_k(kv_heads), extra(pair_extra), lane(lane_id)
     {
-        int sum = total0;
+        t0 = lane < S ? lens[lane] : 0;
+        incl0 = wave_inclusive_scan(real_weight(t0));
+        total0 = __builtin_amdgcn_readlane(incl0, 63);
+        cincl0 = wave_inclusive_scan(cost_weight(t0));
+        ctotal0 = __builtin_amdgcn_readlane(cincl0, 63);
+    }
+
+    // Length of the cost axis for the whole batch.
+    __device__ __forceinline__ int cost_total() const
+    {
+        int sum = ctotal0;
         for (int base = 64; base < S; base += 64) {
-            const int t = base + lane < S ? lens[base + lane] : 0;
-            int v = H_k * groups_of(t);
+            int v = cost_weight(base + lane < S ? lens[base + lane] : 0);
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
             sum += wave_uniform(v);      // equal in all lanes; tell the compiler so
@@ -74,27 +87,49 @@ struct FlatSchedule {
         return sum;
     }
 
-    // Sequence that owns flattened group x (x < total): its index, the flattened index of its
-    // first group, and its context length.  All results are wave-uniform.
-    __device__ __forceinline__ void locate(int x, int& seq, int& first, int& t) const
+    // Sequence that owns position x of the real axis (COST = false) or of the cost axis (COST =
+    // true), x below that axis' total: its index, the positions of its first unit on both axes, and
+    // its context length.  All results are wave-uniform.
+    template <bool COST>
+    __device__ __forceinline__ void locate(int x, int& seq, int& first, int& cfirst, int& t) const
     {
-        int carry = 0, tl = t0, incl = incl0, tile_total = total0;
+        int carry = 0, ccarry = 0, tl = t0, incl = incl0, cincl = cincl0;
+        int tile_total = total0, ctile_total = ctotal0;
         for (int base = 0;; base += 64) {
             if (base > 0) {
                 tl = base + lane < S ? lens[base + lane] : 0;
-                incl = wave_inclusive_scan(H_k * groups_of(tl));
+                incl = wave_inclusive_scan(real_weight(tl));
                 tile_total = __builtin_amdgcn_readlane(incl, 63);
+                cincl = wave_inclusive_scan(cost_weight(tl));
+                ctile_total = __builtin_amdgcn_readlane(cincl, 63);
             }
-            if (x < carry + tile_total || base + 64 >= S) {
-                const unsigned long long before = __builtin_amdgcn_ballot_w64(carry + incl <= x);
+            const bool here = COST ? x < ccarry + ctile_total : x < carry + tile_total;
+            if (here || base + 64 >= S) {
+                const unsigned long long before =
+                    __builtin_amdgcn_ballot_w64(COST ? ccarry + cincl <= x : carry + incl <= x);
                 const int idx = min(__builtin_popcountll(before), 63);
                 seq = min(base + idx, S - 1);
                 t = __builtin_amdgcn_readlane(tl, idx);
-                first = carry + __builtin_amdgcn_readlane(incl - H_k * groups_of(tl), idx);
+                first = carry + __builtin_amdgcn_readlane(incl - real_weight(tl), idx);
+                cfirst = ccarry + __builtin_amdgcn_readlane(cincl - cost_weight(tl), idx);
                 return;
             }
             carry += tile_total;
+            ccarry += ctile_total;
         }
+    }
+
+    // Number of groups whose cost-axis position is below v (0 <= v <= cost_total): the real-axis
+    // position at which a share that begins at v begins.
+    __device__ __forceinline__ int real_before(int v, int ctotal) const
+    {
+        int seq, first, cfirst, t;
+        locate<true>(min(v, ctotal - 1), seq, first, cfirst, t);
+        const int ng = groups_of(t);
+        const int r = v - cfirst;                     // v = ctotal lands past the last pair
+        const int g = min(r / (ng + extra), H_k);
+        const int gi = min(max(r - g * (ng + extra) - extra, 0), ng);
+        return first + min(g * ng + gi, H_k * ng);
     }
 };
 
@@ -111,7 +146,8 @@ struct FlatArgs {
     int32_t num_seqs, H_q, H_k, G;
     int32_t max_blocks;
     int32_t max_slots;
-    int32_t min_share;    // groups per workgroup, lower bound
+    int32_t min_share;    // cost units (groups plus pair extras) per workgroup, lower bound
+    int32_t pair_extra;   // cost units charged to a share for every pair that ends inside it
     int32_t pool_tiles;   // num_blocks * H_k
     float scale_log2e;
 };
@@ -135,6 +171,66 @@ struct FlatCut {
     }
 };
 
+// Where one partial goes: first output row of its (sequence, KV head) pair, slot among the pair's
+// partials, and -- for the pair's first workgroup only (count_at >= 0) -- where to leave the
+// number of partials of the pair.  All wave-uniform.
+struct PartialSlot {
+    int row0, slot, count_at, count;
+};
+
+// Lane (n, grp) owns dims 16c + 4grp .. +3 of head n: o[c].  m in natural-log units.
+template <int HEAD_DIM>
+__device__ __forceinline__ void store_partial(const FlatArgs& a, const PartialSlot& ps,
+                                              const floatx4 (&o)[HEAD_DIM / 16], float m_ln, float l,
+                                              int lane)
+{
+    const int n = lane & 15, grp = lane >> 4;
+    if (ps.count_at >= 0 && lane == 0) a.counts[ps.count_at] = ps.count;
+    if (n < a.G) {
+        const size_t at = (size_t)(ps.row0 + n) * a.max_slots + ps.slot;
+        float* dst = a.tmp_out + at * HEAD_DIM + 4 * grp;
+#pragma unroll
+        for (int c = 0; c < HEAD_DIM / 16; ++c) *reinterpret_cast<floatx4*>(dst + 16 * c) = o[c];
+        if (grp == 0) {
+            a.max_logits[at] = m_ln;
+            a.exp_sums[at] = l;
+        }
+    }
+}
+
+// The same for a partial parked in LDS (each lane reads back what it wrote itself).
+template <int HEAD_DIM>
+__device__ __forceinline__ void store_parked(const FlatArgs& a, const PartialSlot& ps,
+                                             const unsigned char* park, int lane)
+{
+    floatx4 o[HEAD_DIM / 16];
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c)
+        o[c] = *reinterpret_cast<const floatx4*>(park + 16 * (64 * c + lane));
+    const float m_ln = *reinterpret_cast<const float*>(park + HEAD_DIM / 16 * 1024 + 4 * lane);
+    const float l = *reinterpret_cast<const float*>(park + HEAD_DIM / 16 * 1024 + 256 + 4 * lane);
+    store_partial<HEAD_DIM>(a, ps, o, m_ln, l, lane);
+}
+
+// Stage the q^T operand of one (sequence, KV head) pair in LDS with loads that write LDS directly:
+// operand jj of lane i lands at stage + 1024 * jj + 16 * i.  Lanes of absent heads (n >= G) repeat
+// the last head; their columns are never stored.  The compiler does not track these loads, so the
+// reader waits on the vector-memory counter itself.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void stage_q_operand(unsigned char* stage, const half_t* pair_rows, int G,
+                                                int n, int grp)
+{
+#if defined(__HIP_DEVICE_COMPILE__)      // the host pass rejects the cast to the LDS address space
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<half_t*>(pair_rows), 0, G * HEAD_DIM * 2, 0x00020000);
+#pragma unroll
+    for (int jj = 0; jj < HEAD_DIM / 32; ++jj)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rq, (__attribute__((address_space(3))) void*)(stage + 1024 * jj), 16,
+            2 * (min(n, G - 1) * HEAD_DIM + q_dim_offset<HEAD_DIM, KV>(jj, grp)), 0, 0, 0);
+#endif
+}
+
 // One wave per workgroup; the wave's share is ONE stream of groups that runs across the
 // boundaries between (sequence, KV head) pairs.  The loads of the next pair's first groups are in
 // flight while the last groups of the current pair are being consumed, and the pair's partial is
@@ -144,19 +240,34 @@ template <int HEAD_DIM, int KV, int DEPTH, bool BIG>
 __global__ void __launch_bounds__(64)
 flat_stream_kernel(const FlatArgs a)
 {
+    // vector-memory loads per group: two blocks of K and V chunks plus, for FP8, their scales
+    constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (KV == COOPT_KV_E4M3 ? 2 : 0));
+    // s_waitcnt immediates (gfx9 layout: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+    constexpr int kWaitStaged = (kGroupLoads & 15) | (7 << 4) | (15 << 8) | ((kGroupLoads >> 4) << 14);
+    constexpr int kWaitLds = 15 | (7 << 4) | (0 << 8) | (3 << 14);
+    static_assert(kGroupLoads < 64, "vmcnt is a 6-bit counter");
     const int lane = threadIdx.x;
     const int n = lane & 15, grp = lane >> 4;
 
-    const FlatSchedule sched(a.context_lens, a.num_seqs, a.H_k, lane);
-    const int total = sched.total();
-    if (total == 0) return;
-    const FlatCut cut(total, gridDim.x, a.min_share);
+    const FlatSchedule sched(a.context_lens, a.num_seqs, a.H_k, a.pair_extra, lane);
+    const int ctotal = sched.cost_total();
+    if (ctotal == 0) return;
+    const FlatCut cut(ctotal, gridDim.x, a.min_share);          // shares of the cost axis
     if ((int)blockIdx.x >= cut.nwg) return;
-    const int x_begin = cut.begin(blockIdx.x), x_end = cut.begin(blockIdx.x + 1);
+    const int x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
+    const int x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
+    if (x_begin >= x_end) return;           // a share that lies inside one pair's extra units
 
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
     BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
-    half8_t q_cur[HEAD_DIM / 32], q_nxt[HEAD_DIM / 32];
+    // q operand of the pair in progress; the next pair's is staged in LDS by loads that write LDS
+    // directly, so taking it over is an LDS read and never waits on a register in flight.
+    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // HEAD_DIM / 32 KiB
+    constexpr int kParkAcc = HEAD_DIM / 16 * 1024;               // parked o, then m and l per lane
+    unsigned char* park = q_stage + HEAD_DIM / 32 * 1024;
+    PartialSlot parked;
+    parked.row0 = -1;
+    half8_t q_cur[HEAD_DIM / 32];
     float m = -INFINITY, l = 0.0f;
     floatx4 acc[HEAD_DIM / 16];
 #pragma unroll
@@ -166,12 +277,12 @@ flat_stream_kernel(const FlatArgs a)
         const int nc = min(32, x_end - xc);                 // groups in this chunk
         // ---- per-lane description of entry j = lane / 2, block h = lane & 1
         const int xl = xc + (lane >> 1);
-        int seq_l = 0, first_l = 0, t_l = 0;
+        int seq_l = 0, first_l = 0, cfirst_l = 0, t_l = 0;
         for (int xs = xc; xs < xc + nc;) {
-            int s, first, t;
-            sched.locate(xs, s, first, t);
+            int s, first, cfirst, t;
+            sched.template locate<false>(xs, s, first, cfirst, t);
             const int span_end = first + a.H_k * groups_of(t);     // > xs: the owner has groups
-            if (xl >= xs && xl < span_end) { seq_l = s; first_l = first; t_l = t; }
+            if (xl >= xs && xl < span_end) { seq_l = s; first_l = first; cfirst_l = cfirst; t_l = t; }
             xs = span_end;
         }
         const int nb_l = (t_l + kBlock - 1) / kBlock;
@@ -196,10 +307,7 @@ flat_stream_kernel(const FlatArgs a)
             return rest ? e + (__builtin_ctzll(rest) >> 1) + 1 : nc;
         };
         load_q_operand_rows<HEAD_DIM, KV>(q_cur, q_rows(0), a.G, true, n, grp);
-        {
-            const int e1 = next_segment(0);
-            load_q_operand_rows<HEAD_DIM, KV>(q_nxt, q_rows(min(e1, nc - 1)), a.G, e1 < nc, n, grp);
-        }
+        stage_q_operand<HEAD_DIM, KV>(q_stage, q_rows(min(next_segment(0), nc - 1)), a.G, n, grp);
 
         auto issue_entry = [&](BlockRegs<HEAD_DIM, KV> (&r)[2], int e) {
             const int ec = min(e, 31);
@@ -226,38 +334,54 @@ flat_stream_kernel(const FlatArgs a)
                                                baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
                                                visA - kBlock, a.scale_log2e);
                     if ((last_mask >> (2 * e)) & 1) {
-                        // ---- the segment's partial, straight from the accumulator registers:
-                        // lane (n, grp) owns dims 16c+4grp..+3 of head n
+                        // ---- the segment ends: its partial is (m, l, acc / l)
                         const int seq = __builtin_amdgcn_readlane(seq_l, 2 * e);
                         const int g = __builtin_amdgcn_readlane(g_l, 2 * e);
                         const int ng = (((t + kBlock - 1) / kBlock) + 1) >> 1;
-                        const int pair_first = xc + e - gi;
-                        const int slot = blockIdx.x - cut.wg_of(pair_first);
-                        if (slot == 0 && lane == 0)      // the pair's first workgroup counts its partials
-                            a.counts[seq * a.H_k + g] = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+                        // cost-axis position of the pair's first group
+                        const int pair_first = __builtin_amdgcn_readlane(cfirst_l, 2 * e) +
+                                               g * (ng + a.pair_extra) + a.pair_extra;
+                        PartialSlot ps;
+                        ps.row0 = seq * a.H_q + g * a.G;
+                        ps.slot = blockIdx.x - cut.wg_of(pair_first);
+                        // the pair's first workgroup also counts the pair's partials
+                        ps.count_at = ps.slot == 0 ? seq * a.H_k + g : -1;
+                        ps.count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
                         l += __shfl_xor(l, 16);
                         l += __shfl_xor(l, 32);
-                        if (n < a.G) {
-                            const size_t row = (size_t)seq * a.H_q + g * a.G + n;
-                            const float inv = 1.0f / l;
-                            float* dst = a.tmp_out + (row * a.max_slots + slot) * HEAD_DIM + 4 * grp;
+                        const float inv = 1.0f / l;
+                        if (xc + e == x_end - 1) {
+                            // end of the share: nothing runs behind these stores
+#pragma unroll
+                            for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= inv;
+                            store_partial<HEAD_DIM>(a, ps, acc, m * kLn2, l * kPUnshift, lane);
+                            if (parked.row0 >= 0) store_parked<HEAD_DIM>(a, parked, park, lane);
+                        } else {
+                            // Mid-stream: vector-memory stores here would sit between the tile
+                            // loads in the in-order counter and stall the next group on their
+                            // completion, so the partial is parked in LDS and stored at the end.
+                            if (parked.row0 >= 0) store_parked<HEAD_DIM>(a, parked, park, lane);
 #pragma unroll
                             for (int c = 0; c < HEAD_DIM / 16; ++c)
-                                *reinterpret_cast<floatx4*>(dst + 16 * c) = acc[c] * inv;
-                            if (grp == 0) {
-                                a.max_logits[row * a.max_slots + slot] = m * kLn2;
-                                a.exp_sums[row * a.max_slots + slot] = l * kPUnshift;
-                            }
+                                *reinterpret_cast<floatx4*>(park + 16 * (64 * c + lane)) = acc[c] * inv;
+                            *reinterpret_cast<float*>(park + kParkAcc + 4 * lane) = m * kLn2;
+                            *reinterpret_cast<float*>(park + kParkAcc + 256 + 4 * lane) = l * kPUnshift;
+                            parked = ps;
+                            m = -INFINITY;
+                            l = 0.0f;
+#pragma unroll
+                            for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+                            // The next segment's q was staged at least one refill (kGroupLoads
+                            // tile loads, which complete in issue order behind it) ago.  The
+                            // compiler does not track loads that write LDS, hence the explicit waits.
+                            __builtin_amdgcn_s_waitcnt(kWaitStaged);
+#pragma unroll
+                            for (int jj = 0; jj < HEAD_DIM / 32; ++jj)
+                                q_cur[jj] = *reinterpret_cast<const half8_t*>(q_stage + 1024 * jj + 16 * lane);
+                            __builtin_amdgcn_s_waitcnt(kWaitLds);      // read before it is restaged
+                            const int e2 = next_segment(e + 1);
+                            if (e2 < nc) stage_q_operand<HEAD_DIM, KV>(q_stage, q_rows(e2), a.G, n, grp);
                         }
-                        m = -INFINITY;
-                        l = 0.0f;
-#pragma unroll
-                        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-                        // the next segment's q is already here; fetch the one after it
-#pragma unroll
-                        for (int jj = 0; jj < HEAD_DIM / 32; ++jj) q_cur[jj] = q_nxt[jj];
-                        const int e2 = next_segment(e + 1);
-                        load_q_operand_rows<HEAD_DIM, KV>(q_nxt, q_rows(min(e2, nc - 1)), a.G, e2 < nc, n, grp);
                     }
                 }
                 // refill only after the stage's registers are dead, so the loads land in place
@@ -354,10 +478,12 @@ template <int HEAD_DIM, int KV, bool BIG>
 static void launch_flat_depth(const FlatArgs& a, int depth, dim3 grid, hipStream_t stream)
 {
     const dim3 block(64);
+    // staging area of one q operand + one parked partial (o, m, l per lane)
+    const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512;
     switch (depth) {
-    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, lds, stream, a); break;
+    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, lds, stream, a); break;
+    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, lds, stream, a); break;
     }
 }
 
@@ -382,13 +508,24 @@ size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan)
            (size_t)sh->num_seqs * sh->num_kv_heads * sizeof(int32_t);
 }
 
+// Cost units charged per (sequence, KV head) pair that ends inside a share, in group times: on
+// MI355X the masked last group of a pair and the hand-over to the next pair together take about
+// as long as two ordinary groups.
+constexpr int kPairExtra = 2;
+
+// Upper bound of the cost axis' length (the kernels index it with 32-bit integers).
+static long long flat_max_cost(const coopt_shape* sh)
+{
+    return (long long)sh->num_seqs * sh->num_kv_heads *
+           ((sh->max_blocks_per_seq + 1) / 2 + kPairExtra);
+}
+
 // Workgroups (= wavefronts) to launch: the plan's grid, but never more than the work's upper bound
 // at the minimum share.
 static int flat_grid_groups(const coopt_shape* sh, const FlatPlan& plan)
 {
     const int min_share = plan.min_share_groups();
-    const long long max_total =
-        (long long)sh->num_seqs * sh->num_kv_heads * ((sh->max_blocks_per_seq + 1) / 2);
+    const long long max_total = flat_max_cost(sh);
     const long long groups = std::min((long long)plan.grid_waves, (max_total + min_share - 1) / min_share);
     return (int)std::max(groups, 1LL);
 }
@@ -403,6 +540,7 @@ static FlatArgs flat_args(const coopt_shape* sh, const FlatPlan& plan, void* wor
     a.max_blocks = sh->max_blocks_per_seq;
     a.max_slots = flat_max_slots(sh, plan);
     a.min_share = plan.min_share_groups();
+    a.pair_extra = kPairExtra;
     a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
     const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
@@ -418,6 +556,7 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
                       const int32_t* context_lens, void* workspace, const coopt_shape* sh,
                       const FlatPlan& plan, hipStream_t stream)
 {
+    if (flat_max_cost(sh) > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     FlatArgs a = flat_args(sh, plan, workspace);
     a.q = (const half_t*)q;
     a.cv = CacheView{(const uint8_t*)k_cache, (const uint8_t*)v_cache, k_scale, v_scale};
