@@ -2,6 +2,8 @@
 """Benchmark of the paged FP8 GQA decode step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--layers L]
+    python bench.py --config 3 --path partitioned     (fixed 512-token partitions + reduce)
+    python bench.py --config 4 --steps 20             (chunked prefill, priced against the MFMA peak)
 
 A "step" is one pass of the whole hot path for one layer over one synthetic batch: the cache
 write of one new token per sequence (quantise-on-write) followed by paged grouped-query decode
@@ -25,6 +27,7 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this script (FETCH_SIZE
 # and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain
@@ -56,8 +59,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3],
-                    help="workload (1 = LLaMa-13B GQA FP8 decode, the headline configuration)")
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4],
+                    help="workload (1 = LLaMa-13B GQA FP8 decode, the headline configuration; "
+                         "4 = chunked prefill)")
+    ap.add_argument("--path", choices=["balanced", "partitioned"], default="balanced",
+                    help="decode through coopt_paged_gqa_decode (balanced split + merge) or through "
+                         "coopt_paged_gqa_decode_partitioned + coopt_paged_gqa_reduce with the "
+                         "workload's partition size (512 if it names none)")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
     ap.add_argument("--plan", type=str, default="",
                     help="decode plan fields in header order, comma separated (tuning)")
@@ -97,6 +105,8 @@ def main():
         return
 
     w = workloads.make(args.config)
+    if args.config == 4:
+        return bench_prefill(args, w, coopt, torch, dev)
     ab = algorithmic_bytes(w)
     e4m3 = w.kv_dtype == "e4m3"
     shape = coopt.Shape(w.S, w.H_q, w.H_k, w.d, w.B, w.NB, w.max_blocks,
@@ -131,13 +141,31 @@ def main():
         pools.append((kc, vc, ks, vs))
     torch.cuda.synchronize()
 
+    partitioned = args.path == "partitioned"
+    if partitioned:
+        P = w.partition_size or 512
+        max_parts = (w.max_blocks * w.B + P - 1) // P
+        tmp_out = torch.empty((w.S, w.H_q, max_parts, w.d), dtype=torch.float32, device=dev)
+        max_logits = torch.empty((w.S, w.H_q, max_parts), dtype=torch.float32, device=dev)
+        exp_sums = torch.empty_like(max_logits)
+
+    def attend(i, reduce=True):
+        kc, vc, ks, vs = pools[i % layers]
+        if not partitioned:
+            coopt.paged_gqa_decode(q, kc, vc, ks, vs, bt, lens, out, ws, shape)
+            return
+        coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens, P, tmp_out, max_logits,
+                                           exp_sums, max_parts, shape)
+        if reduce:
+            coopt.paged_gqa_reduce(tmp_out, max_logits, exp_sums, lens, P, max_parts, out, shape)
+
     def step(i):
         kc, vc, ks, vs = pools[i % layers]
         if e4m3:
             coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
         else:
             coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
-        coopt.paged_gqa_decode(q, kc, vc, ks, vs, bt, lens, out, ws, shape)
+        attend(i)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
@@ -191,6 +219,8 @@ def main():
     plan = coopt.get_decode_plan()
 
     def kern(i):
+        if partitioned:
+            return attend(i, reduce=False)
         kc, vc, ks, vs = pools[i % layers]
         coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape)
     kern_us = timed(kern, args.steps) * 1e3
@@ -201,7 +231,11 @@ def main():
 
     def kern_empty(i):
         kc, vc, ks, vs = pools[i % layers]
-        coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape)
+        if partitioned:
+            coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens_zero, P, tmp_out,
+                                               max_logits, exp_sums, max_parts, shape)
+        else:
+            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape)
     floor_us = timed(kern_empty, min(args.steps, 200)) * 1e3
 
     kv_gbs = ab["kv"] / (step_ms * 1e-3) / 1e9
@@ -215,7 +249,10 @@ def main():
         "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
                    "head_dim": w.d, "block_size": w.B, "context_tokens": ab["tokens"],
                    "kv_pools_rotated": layers,
-                   "decode_plan": plan, "step": "kv_cache_write + paged_gqa_decode, one layer",
+                   "decode_plan": plan,
+                   "step": ("kv_cache_write + paged_gqa_decode_partitioned (P=%d) + paged_gqa_reduce, "
+                            "one layer" % P) if partitioned else
+                           "kv_cache_write + paged_gqa_decode, one layer",
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),
@@ -226,10 +263,12 @@ def main():
         alg = ab["kv"] + ab["q_out"] // 2 + ab["tables"]
         pmc = PMC_TRAFFIC.get(w.name)
         traffic = None
-        if pmc and not args.plan:
+        if pmc and not args.plan and not partitioned:
             traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
         achieved = alg / (kern_us * 1e-6) / 1e9
-        result["roofline"] = {"bound": "hbm", "kernel": "flat_stream_kernel (coopt_paged_gqa_decode_split)",
+        result["roofline"] = {"bound": "hbm",
+                              "kernel": "paged_decode_kernel (coopt_paged_gqa_decode_partitioned)"
+                              if partitioned else "flat_stream_kernel (coopt_paged_gqa_decode_split)",
                               "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                               "algorithmic_bytes_per_launch": int(alg),
@@ -241,6 +280,116 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, ab)
     print(json.dumps(result), flush=True)
+
+
+def bench_prefill(args, w, coopt, torch, dev):
+    """Config 4: a step = cache write of every sequence's chunk (quantise-on-write) + causal
+    attention of the chunk rows over history and chunk.  A dense contraction: the dominant kernel
+    is priced against the fp16 matrix-core peak."""
+    shape = coopt.Shape(w.S, w.H_q, w.H_k, w.d, w.B, w.NB, w.max_blocks, coopt.COOPT_KV_E4M3,
+                        float(np.float32(w.softmax_scale)))
+    C = w.new_per_seq
+    layers = args.layers or 4
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    hist, new = w.history_index(), w.new_index()
+    k_hist, v_hist = to_dev(w.k_ctx[hist].view(np.uint16)), to_dev(w.v_ctx[hist].view(np.uint16))
+    s_hist = to_dev(w.slots[hist])
+    k_new, v_new = to_dev(w.k_ctx[new].view(np.uint16)), to_dev(w.v_ctx[new].view(np.uint16))
+    s_new = to_dev(w.slots[new])
+    q, bt, lens, qs = (to_dev(w.q.view(np.uint16)), to_dev(w.block_tables), to_dev(w.context_lens),
+                       to_dev(w.query_start))
+    n_rows = int(w.query_start[-1])
+    out = torch.zeros((n_rows, w.H_q, w.d), dtype=torch.float16, device=dev)
+    pools = []
+    for _ in range(layers):
+        kc = torch.zeros((w.NB, w.H_k, w.B * w.d), dtype=torch.uint8, device=dev)
+        vc = torch.zeros_like(kc)
+        ks = torch.zeros((w.NB, w.H_k, w.B), dtype=torch.float32, device=dev)
+        vs = torch.zeros_like(ks)
+        coopt.kv_cache_write_fp8(k_hist, v_hist, s_hist, kc, vc, ks, vs, shape)
+        pools.append((kc, vc, ks, vs))
+    torch.cuda.synchronize()
+
+    def attend(i):
+        coopt.paged_gqa_prefill_chunk(q, *pools[i % layers], bt, lens, qs, n_rows, C, out, shape)
+
+    def step(i):
+        coopt.kv_cache_write_fp8(k_new, v_new, s_new, *pools[i % layers], shape)
+        attend(i)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, count):                 # launches of ~1 ms: eager is fine
+        e0.record()
+        for i in range(count):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    steps = min(args.steps, 200)
+    t0 = time.perf_counter()
+    step_ms = timed(step, steps)
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    kern_ms = timed(attend, steps)
+    # 2 products of 2*d flops per (row, query head, visible token)
+    pairs = sum(C * (int(t) - C) + C * (C + 1) // 2 for t in w.context_lens)
+    flops = 4.0 * w.d * w.H_q * pairs
+    result = {
+        "metric": "chunked prefill attention over the paged FP8 cache: TFLOP/s per step",
+        "value": round(flops / step_ms / 1e9, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": round(step_ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3 cache, f16 MFMA, f32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
+                   "head_dim": w.d, "block_size": w.B, "history_tokens": int(w.context_lens[0]) - C,
+                   "chunk_tokens": C, "kv_pools_rotated": layers,
+                   "step": "kv_cache_write of the chunk + paged_gqa_prefill_chunk, one layer",
+                   "launch": "eager"},
+        "wall_ms_timed_region": round(wall_ms, 2),
+        "roofline": {"bound": "mfma", "kernel": "prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk)",
+                     "achieved": round(flops / kern_ms / 1e9, 1), "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(flops / kern_ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4),
+                     "traffic": None, "algorithmic_flops_per_launch": flops,
+                     "kernel_ms_mean": round(kern_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline_prefill(w, flops)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline_prefill(w, flops):
+    """The oracle on a sample of chunk rows of the first sequence (every query head), scaled by
+    flops to the whole step."""
+    import oracle
+    oracle.build()
+    C = w.new_per_seq
+    n_tok = int(w.seq_start[1])
+    kc = np.zeros((w.NB, w.H_k, w.B, w.d), dtype=np.uint8)
+    vc = np.zeros((w.NB, w.H_k, w.d, w.B), dtype=np.uint8)
+    ks = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32)
+    vs = np.zeros_like(ks)
+    idx = np.arange(n_tok)
+    oracle.kv_cache_write_fp8(np.ascontiguousarray(w.k_ctx[idx]), np.ascontiguousarray(w.v_ctx[idx]),
+                              np.ascontiguousarray(w.slots[idx]), kc, vc, ks, vs, H_k=w.H_k, d=w.d, B=w.B)
+    rows = np.arange(0, C, 8, dtype=np.int32)               # 64 rows of sequence 0
+    t0 = time.perf_counter()
+    oracle.paged_gqa_prefill_chunk(w.q, kc, vc, ks, vs, w.block_tables, w.context_lens, w.query_start,
+                                   H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B,
+                                   softmax_scale=w.softmax_scale, rows=rows)
+    sec = time.perf_counter() - t0
+    t_ctx = int(w.context_lens[0]) - C
+    sample_flops = 4.0 * w.d * w.H_q * sum(t_ctx + int(r) + 1 for r in rows)
+    return {"value": round(sample_flops / sec / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(sec, 3),
+            "sample": f"{len(rows)} of {C} chunk rows of sequence 0, all {w.H_q} query heads, "
+                      f"attention only ({sample_flops / flops:.2%} of the step's flops)"}
 
 
 def cpu_baseline(w, ab):

@@ -98,6 +98,33 @@ struct TileLoader {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, kRsrcFlags);
     }
 
+    // Single pieces of a tile, for kernels that split a tile's loads between wavefronts:
+    // piece = 0 .. NL-1 of K or of V (16 bytes per lane each), or the lane group's 4 scales.
+    // `tile` must be wave-uniform; valid = false returns zeros.
+    __device__ __forceinline__ u32x4 load_piece(const uint8_t* pool, int tile, int piece, bool valid) const
+    {
+        if constexpr (BIG) {
+            const __amdgpu_buffer_rsrc_t r =
+                rsrc(pool + (size_t)(uint32_t)tile * kTileBytes, valid ? kTileBytes : 0);
+            return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off + 1024 * piece, 0, kAuxStream);
+        } else {
+            const __amdgpu_buffer_rsrc_t r = rsrc(pool, valid ? kv_pool_bytes : 0);
+            return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off + 1024 * piece, tile * kTileBytes, kAuxStream);
+        }
+    }
+    __device__ __forceinline__ floatx4 load_scales(const float* pool, int tile, bool valid) const
+    {
+        if constexpr (BIG) {
+            const __amdgpu_buffer_rsrc_t r =
+                rsrc(pool + (size_t)(uint32_t)tile * kBlock, valid ? kBlock * 4 : 0);
+            return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, s_off, 0, 0));
+        } else {
+            const __amdgpu_buffer_rsrc_t r = rsrc(pool, valid ? scale_pool_bytes : 0);
+            return __builtin_bit_cast(
+                floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, s_off, tile * (kBlock * 4), 0));
+        }
+    }
+
     // `tile` (= physical block * H_k + KV head) must be wave-uniform.
     __device__ __forceinline__ void issue(BlockRegs<HEAD_DIM, KV>& r, int tile, bool valid) const
     {

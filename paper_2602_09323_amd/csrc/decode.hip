@@ -15,7 +15,6 @@
 // The per-block arithmetic (two MFMA products around an in-register softmax) is in attn_tile.hpp.
 #include "attn_tile.hpp"
 #include "decode_internal.hpp"
-#include "partials.hpp"
 
 namespace coopt {
 
@@ -179,24 +178,71 @@ paged_decode_kernel(const DecodeArgs a)
     }
 }
 
-// One wavefront per (sequence, query head): M = max_p m_p, w_p = l_p exp(m_p - M),
-// out = sum_p w_p o_p / sum_p w_p.  Lane i owns dims i and i+64.
+// One workgroup of 4 wavefronts per (sequence, query head) row: M = max_p m_p,
+// w_p = l_p exp(m_p - M), out = sum_p w_p o_p / sum_p w_p.  Every wave derives M and the weights
+// (a row has few partials); the partial rows are dealt to the waves, read with independent
+// 16-byte loads (HEAD_DIM/4 lanes per row, so one wave-wide load covers 2 or 4 partials), and the
+// four waves' sums meet in LDS.  A slot beyond the row's partial count is replaced by partial 0
+// with weight 0, so memory nobody wrote is never read.
 template <int HEAD_DIM>
 __global__ void __launch_bounds__(256)
 partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restrict__ max_logits,
                         const float* __restrict__ exp_sums, const int32_t* __restrict__ context_lens,
-                        int partition_size, int max_parts, half_t* __restrict__ out, int H_q,
-                        int num_rows)
+                        int partition_size, int max_parts, half_t* __restrict__ out, int H_q)
 {
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // seq * H_q + head
-    if (row >= num_rows) return;
+    constexpr int LPR = HEAD_DIM / 4;          // lanes per partial row
+    constexpr int PPW = 64 / LPR;              // partial rows per wave-wide load
+    __shared__ float sm[4][HEAD_DIM];
+    const int row = blockIdx.x;                // seq * H_q + head
     const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub = lane / LPR, piece = lane % LPR;
     const int seq = row / H_q;
     const int t = context_lens[seq];
     const int nparts = min((t + partition_size - 1) / partition_size, max_parts);
-    merge_row<HEAD_DIM>(max_logits + (size_t)row * max_parts, exp_sums + (size_t)row * max_parts,
-                        tmp_out + (size_t)row * max_parts * HEAD_DIM, nparts,
-                        out + (size_t)row * HEAD_DIM, lane);
+    half_t* out_row = out + (size_t)row * HEAD_DIM;
+    if (nparts <= 0) {                         // the whole workgroup takes this branch together
+        if (threadIdx.x < HEAD_DIM) out_row[threadIdx.x] = (half_t)0.0f;
+        return;
+    }
+    const float* ml = max_logits + (size_t)row * max_parts;
+    const float* es = exp_sums + (size_t)row * max_parts;
+    const float* po = tmp_out + (size_t)row * max_parts * HEAD_DIM + 4 * piece;
+
+    float M = -INFINITY;
+    for (int p = lane; p < nparts; p += 64) M = fmaxf(M, ml[p]);
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) M = fmaxf(M, __shfl_xor(M, s));
+    floatx4 o = {0.f, 0.f, 0.f, 0.f};
+    float W = 0.0f;
+    for (int base = 0; base < nparts; base += 64) {
+        const int p = base + lane;
+        const float wv = p < nparts ? es[p] * __expf(ml[p] - M) : 0.0f;   // weight of partial base+lane
+        W += wv;
+        const int cnt = min(64, nparts - base);
+#pragma unroll
+        for (int i = 0; i < 64 / (4 * PPW); ++i) {
+            const int j = (i * 4 + wave) * PPW + sub;                      // < 64
+            const float wj = __shfl(wv, j);
+            const bool ok = j < cnt;
+            const floatx4 x = *reinterpret_cast<const floatx4*>(po + (size_t)(base + (ok ? j : 0)) * HEAD_DIM);
+            o += x * (ok ? wj : 0.0f);
+        }
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) W += __shfl_xor(W, s);
+#pragma unroll
+    for (int s = LPR; s < 64; s <<= 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] += __shfl_xor(o[i], s);
+    }
+    if (sub == 0) *reinterpret_cast<floatx4*>(&sm[wave][4 * piece]) = o;
+    __syncthreads();
+    if (threadIdx.x < HEAD_DIM) {
+        const int dim = threadIdx.x;
+        const float v = sm[0][dim] + sm[1][dim] + sm[2][dim] + sm[3][dim];
+        out_row[dim] = (half_t)(v / W);
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -250,15 +296,15 @@ static void launch_reduce(const float* tmp_out, const float* max_logits, const f
                           void* out, const coopt_shape* sh, hipStream_t stream)
 {
     const int rows = sh->num_seqs * sh->num_q_heads;
-    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    const dim3 grid((unsigned)rows), block(256);
     if (sh->head_dim == 128)
         hipLaunchKernelGGL(partition_reduce_kernel<128>, grid, block, 0, stream, tmp_out, max_logits,
                            exp_sums, context_lens, partition_size, max_parts, (half_t*)out,
-                           sh->num_q_heads, rows);
+                           sh->num_q_heads);
     else
         hipLaunchKernelGGL(partition_reduce_kernel<64>, grid, block, 0, stream, tmp_out, max_logits,
                            exp_sums, context_lens, partition_size, max_parts, (half_t*)out,
-                           sh->num_q_heads, rows);
+                           sh->num_q_heads);
 }
 
 static DecodeArgs make_args(const void* q, const void* k_cache, const void* v_cache,

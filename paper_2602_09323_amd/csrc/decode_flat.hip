@@ -23,7 +23,6 @@
 // The per-group arithmetic is in attn_tile.hpp.
 #include "attn_tile.hpp"
 #include "decode_internal.hpp"
-#include "partials.hpp"
 
 namespace coopt {
 

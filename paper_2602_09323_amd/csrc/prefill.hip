@@ -2,11 +2,23 @@
 // against history + chunk, both already in the cache (each row is Background Eq. 1 over its
 // visible prefix, with the grouping of Opt-GQA Eq. 7 and the valid-block rule of Opt-Pa Eq. 9).
 //
-// Query length > 1 makes this a dense contraction, so the matrix cores are used at full width:
-// a score tile has 16 query rows of ONE query head as its columns (column n = chunk row i0+n), and
-// a wavefront carries NR such tiles against every K/V tile it loads, so each cache byte fetched
-// and converted once feeds 16*NR query rows.  The per-block arithmetic is in attn_tile.hpp; the
-// only difference from decode is that the visible-token limit is per column (causal).
+// Query length > 1 makes this a dense contraction, so the matrix cores are used at full width and
+// every cache byte is fetched and converted once per WORKGROUP:
+//   * A score tile has 16 query rows of ONE query head as its columns (column n = chunk row
+//     i0+n).  A wavefront carries NR such tiles, a workgroup of 4 wavefronts 4*NR of them (128 rows
+//     at NR = 2), all of the same (sequence, KV head) pair.
+//   * The pair's K/V stream, two 16-token blocks (a group) at a time, through a double-buffered
+//     LDS stage in matrix-core operand order, already converted to fp16: wave 0 brings block A's K,
+//     wave 1 block B's K, waves 2 and 3 the V pieces of both blocks (and zero the V entries and
+//     scales of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
+//     All four then read their operands back with 16-byte LDS loads, conflict-free, and run the
+//     online-softmax update of attn_tile.hpp's arithmetic on each of their tiles.  One barrier
+//     per group; the global loads of group i+2 are in flight while group i is consumed.
+//   * Workgroup ids are dealt to the 8 XCDs round-robin, so the mapping puts all workgroups of a
+//     pair on ONE XCD: the pair's 2 MB of cache are fetched from HBM once and re-read from that
+//     XCD's L2 by the pair's other workgroups.
+// The only difference from decode in the arithmetic is that the visible-token limit is per column
+// (causal).
 #include "attn_tile.hpp"
 
 namespace coopt {
@@ -21,20 +33,116 @@ struct PrefillArgs {
     int32_t H_q, H_k, G;
     int32_t max_blocks;
     int32_t pool_tiles;
+    int32_t num_pairs;        // num_seqs * H_k
+    int32_t wgs_per_pair;
     float scale_log2e;
 };
 
 constexpr int kPrefillWaves = 4;
 
-template <int HEAD_DIM, int KV, int NR, int DEPTH, bool BIG>
-__global__ void __launch_bounds__(64 * kPrefillWaves)
+// Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
+template <int HEAD_DIM>
+struct PrefillStage {
+    static constexpr int kKOps = HEAD_DIM / 32;        // S^T MFMAs per block
+    static constexpr int kVOps = HEAD_DIM / 16;        // O^T MFMAs per group
+    static constexpr int kK = 0;                        // [2 blocks][kKOps][64 lanes] 8 halves
+    static constexpr int kV = 2 * kKOps * 1024;         // [kVOps][64 lanes] 4 halves of A, 4 of B
+    static constexpr int kS = kV + kVOps * 1024;        // 16 floats each: k_scale*c A, B; v_scale A, B
+    static constexpr int kBytes = kS + 256;
+};
+
+// One online-softmax step of a 16-column tile against a group whose operands are ready, in two
+// parts so that the caller can issue the score products of all its tiles before the first
+// softmax (the matrix pipe then works on the next tile's scores and on this tile's P.V while the
+// vector ALU does the exponentials).
+//   kA/kB = K operands of blocks A/B, vop = V operands of the group, ksc = k_scale * softmax_scale
+//   * log2(e) and vs = v_scale of this lane's 4 tokens per block.  tail / visA / visB as in
+//   group_update (attn_tile.hpp); absent tokens are already zero in vop and vs.
+template <int HEAD_DIM>
+__device__ __forceinline__ void tile_scores(const half8_t (&kA)[HEAD_DIM / 32],
+                                            const half8_t (&kB)[HEAD_DIM / 32],
+                                            const half8_t (&qop)[HEAD_DIM / 32], floatx4& sA,
+                                            floatx4& sB)
+{
+    sA = floatx4{0.f, 0.f, 0.f, 0.f};
+    sB = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) {
+        sA = mfma_16x16x32(kA[jj], qop[jj], sA);
+        sB = mfma_16x16x32(kB[jj], qop[jj], sB);
+    }
+}
+
+template <int HEAD_DIM>
+__device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
+                                                const half8_t (&vop)[HEAD_DIM / 16], floatx4 kscA,
+                                                floatx4 kscB, floatx4 vsA, floatx4 vsB, float& m,
+                                                float& l, floatx4 (&acc)[HEAD_DIM / 16], bool tail,
+                                                int visA, int visB)
+{
+    float z[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        z[i] = sA[i] * kscA[i];
+        z[4 + i] = sB[i] * kscB[i];
+    }
+    if (tail) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);          // min drops a NaN score
+            z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
+        }
+    }
+    const float bm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                           fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+    if (__builtin_amdgcn_ballot_w64(bm > m + kRescaleSlack) != 0) {   // wave-uniform, rare
+        float nm = fmaxf(bm, __shfl_xor(bm, 16));
+        nm = fmaxf(nm, __shfl_xor(nm, 32));
+        nm = fmaxf(nm, m);
+        const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = -inf at the start gives 0
+        l *= alpha;
+#pragma unroll
+        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
+        m = nm;
+    }
+    const float mm = m - kPShift;
+    float p[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(z[i] - mm);             // invisible: exp2(-inf) = 0
+        l += p[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        p[i] *= vsA[i];
+        p[4 + i] *= vsB[i];
+    }
+    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
+                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
+}
+
+template <int HEAD_DIM, int KV, int NR, bool BIG>
+__global__ void __launch_bounds__(64 * kPrefillWaves, 2)
 prefill_chunk_kernel(const PrefillArgs a)
 {
+    using St = PrefillStage<HEAD_DIM>;
+    constexpr bool FP8 = KV == COOPT_KV_E4M3;
+    constexpr int NL = BlockRegs<HEAD_DIM, KV>::NL;   // 16-byte pieces per lane of a K (or V) tile
+    constexpr int NLH = (NL + 1) / 2;                 // V pieces per V wave
+    constexpr int NP = NL > 2 * NLH ? NL : 2 * NLH;   // producer registers per wave
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];     // two stages
+
     const int lane = threadIdx.x & 63;
     const int wave = wave_uniform((int)(threadIdx.x >> 6));
     const int n = lane & 15, grp = lane >> 4;
-    const int seq = blockIdx.y / a.H_k;
-    const int g = blockIdx.y - seq * a.H_k;
+    // all workgroups of a (sequence, KV head) pair on one XCD (ids go round-robin over 8 XCDs)
+    const int k8 = blockIdx.x >> 3;
+    const int pair = (k8 / a.wgs_per_pair) * 8 + (blockIdx.x & 7);
+    if (pair >= a.num_pairs) return;
+    const int seq = pair / a.H_k;
+    const int g = pair - seq * a.H_k;
 
     const int qs = a.query_start[seq];
     const int C = a.query_start[seq + 1] - qs;
@@ -43,13 +151,15 @@ prefill_chunk_kernel(const PrefillArgs a)
     if (C <= 0) return;
     const int tiles_per_head = (C + 15) / 16;
     const int total_tiles = a.G * tiles_per_head;
-    const int first_tile = (blockIdx.x * kPrefillWaves + wave) * NR;
-    if (first_tile >= total_tiles) return;          // no barrier below: a wave may leave alone
+    const int wg_first_tile = (k8 % a.wgs_per_pair) * (kPrefillWaves * NR);
+    if (wg_first_tile >= total_tiles) return;          // the whole workgroup leaves together
+    const int first_tile = wg_first_tile + wave * NR;
+    const bool active = first_tile < total_tiles;      // a wave without tiles still produces
 
     half8_t qop[NR][HEAD_DIM / 32];
     int limit[NR];          // tokens visible to column n of tile r
     int row0[NR], head[NR];
-    int max_limit = 0, min_row = 0x7fffffff;
+    int my_max = 0, min_row = 0x7fffffff;
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         const int tile = min(first_tile + r, total_tiles - 1);   // surplus tiles repeat the last
@@ -59,12 +169,21 @@ prefill_chunk_kernel(const PrefillArgs a)
         head[r] = g * a.G + hh;
         row0[r] = i0;
         limit[r] = t_ctx + row + 1;
-        max_limit = max(max_limit, t_ctx + min(i0 + 15, C - 1) + 1);
+        my_max = max(my_max, t_ctx + min(i0 + 15, C - 1) + 1);
         min_row = min(min_row, i0);
         load_q_operand<HEAD_DIM, KV>(qop[r], a.q + ((size_t)(qs + row) * a.H_q + head[r]) * HEAD_DIM,
                                      true, grp);
     }
-    const int nblk = (max_limit + kBlock - 1) / kBlock;
+    if (!active) my_max = 0;
+    // the workgroup streams as far as its longest column needs
+    int wg_max = 0;
+    for (int i = 0; i < kPrefillWaves * NR; ++i) {
+        const int tile = min(wg_first_tile + i, total_tiles - 1);
+        const int i0 = (tile % tiles_per_head) * 16;
+        wg_max = max(wg_max, t_ctx + min(i0 + 15, C - 1) + 1);
+    }
+    const int nblk = (wg_max + kBlock - 1) / kBlock;
+    const int num_groups = (nblk + 1) >> 1;
     const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks;
 
     float m[NR], l[NR];
@@ -77,54 +196,151 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // ---- block numbers: 64 per vector load, the chunk in use and the one after it
+    int cur_chunk = 0;
+    int idv_cur = lane < nblk ? bt[lane] : 0;
+    int idv_nxt = 64 + lane < nblk ? bt[64 + lane] : 0;
+
+    // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
-    BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
-    const int full_limit = min(t, t_ctx + min_row + 1);   // tokens visible to every column
-    for (int cb = 0; cb < nblk; cb += 64) {          // 64 block numbers per vector load
-        const int nc = min(64, nblk - cb);
-        const int ng = (nc + 1) >> 1;
-        int idv = 0;
-        if (lane < nc) idv = bt[cb + lane];
-#pragma unroll
-        for (int u = 0; u < DEPTH; ++u) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int id = __builtin_amdgcn_readlane(idv, 2 * u + h);
-                loader.issue(regs[u][h], id * a.H_k + g, 2 * u + h < nc);
-            }
-            __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
+    u32x4 pr[NP];
+    floatx4 psc = {0.f, 0.f, 0.f, 0.f};
+    const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
+    const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
+    auto produce_issue = [&](int p) {
+        const int c = (2 * p) >> 6;
+        if (c != cur_chunk) {                              // groups are produced in order
+            idv_cur = idv_nxt;
+            cur_chunk = c;
+            idv_nxt = 64 * (c + 1) + lane < nblk ? bt[64 * (c + 1) + lane] : 0;
         }
-        for (int i = 0; i < ng; i += DEPTH) {
+        const bool okA = 2 * p < nblk, okB = 2 * p + 1 < nblk;
+        const int tA = __builtin_amdgcn_readlane(idv_cur, (2 * p) & 63) * a.H_k + g;
+        const int tB = __builtin_amdgcn_readlane(idv_cur, (2 * p + 1) & 63) * a.H_k + g;
+        if (wave < 2) {
+            const int tk = wave == 0 ? tA : tB;
+            const bool ok = wave == 0 ? okA : okB;
 #pragma unroll
-            for (int u = 0; u < DEPTH; ++u) {
-                const int gi = i + u;
-                if (gi < ng) {
-                    const int baseA = (cb + 2 * gi) * kBlock;           // uniform
-                    const int tokA = baseA + 4 * grp;
-                    const bool hasB = 2 * gi + 1 < nc;
-                    const int cacheA = t - tokA, cacheB = hasB ? cacheA - kBlock : 0;
-                    const bool tail = !(hasB && baseA + 2 * kBlock <= full_limit);
+            for (int j = 0; j < NL; ++j) pr[j] = loader.load_piece(a.cv.k_cache, tk, j, ok);
+            if constexpr (FP8) psc = loader.load_scales(a.cv.k_scale, tk, ok);
+        } else {
 #pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        const int visA = limit[r] - tokA;
-                        group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], qop[r], m[r], l[r], acc[r],
-                                                   tail, visA, hasB ? visA - kBlock : 0, cacheA, cacheB,
-                                                   a.scale_log2e);
+            for (int jj = 0; jj < NLH; ++jj) {
+                if (jj < vcnt) {
+                    pr[2 * jj] = loader.load_piece(a.cv.v_cache, tA, vj0 + jj, okA);
+                    pr[2 * jj + 1] = loader.load_piece(a.cv.v_cache, tB, vj0 + jj, okB);
+                }
+            }
+            if constexpr (FP8)
+                psc = loader.load_scales(a.cv.v_scale, wave == 2 ? tA : tB, wave == 2 ? okA : okB);
+        }
+    };
+    auto produce_store = [&](int p, unsigned char* st) {
+        if (wave < 2) {
+            unsigned char* kdst = st + St::kK + wave * (St::kKOps * 1024) + 16 * lane;
+#pragma unroll
+            for (int j = 0; j < NL; ++j) {
+                if constexpr (FP8) {
+                    *reinterpret_cast<half8_t*>(kdst + (2 * j) * 1024) = e4m3x8_to_half8(pr[j].x, pr[j].y);
+                    *reinterpret_cast<half8_t*>(kdst + (2 * j + 1) * 1024) = e4m3x8_to_half8(pr[j].z, pr[j].w);
+                } else {
+                    *reinterpret_cast<u32x4*>(kdst + j * 1024) = pr[j];
+                }
+            }
+            if constexpr (FP8) {
+                if (n == 0)
+                    *reinterpret_cast<floatx4*>(st + St::kS + 64 * wave + 16 * grp) = psc * a.scale_log2e;
+            }
+        } else {
+            // this lane's 4 tokens of block A start at 32p + 4grp, of block B 16 later
+            const int cacheA = t - (32 * p + 4 * grp), cacheB = cacheA - kBlock;
+            uint32_t a0, a1, b0, b1;
+            token_masks<KV>(cacheA, a0, a1);
+            token_masks<KV>(cacheB, b0, b1);
+#pragma unroll
+            for (int jj = 0; jj < NLH; ++jj) {
+                if (jj < vcnt) {
+                    if constexpr (FP8) {
+                        const u32x4 wa = pr[2 * jj] & a0, wb = pr[2 * jj + 1] & b0;
+#pragma unroll
+                        for (int cc = 0; cc < 4; ++cc) {
+                            const half4_t va = e4m3x4_to_half4(wa[cc]), vb = e4m3x4_to_half4(wb[cc]);
+                            *reinterpret_cast<half8_t*>(st + St::kV + (4 * (vj0 + jj) + cc) * 1024 + 16 * lane) =
+                                half8_t{va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
+                        }
+                    } else {
+                        const u32x4 wa = pr[2 * jj] & u32x4{a0, a1, a0, a1};
+                        const u32x4 wb = pr[2 * jj + 1] & u32x4{b0, b1, b0, b1};
+                        *reinterpret_cast<u32x4*>(st + St::kV + (2 * (vj0 + jj)) * 1024 + 16 * lane) =
+                            u32x4{wa.x, wa.y, wb.x, wb.y};
+                        *reinterpret_cast<u32x4*>(st + St::kV + (2 * (vj0 + jj) + 1) * 1024 + 16 * lane) =
+                            u32x4{wa.z, wa.w, wb.z, wb.w};
                     }
                 }
-                // refill only after the stage's registers are dead, so the loads can land in place
-                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (FP8) {
+                const int cache = wave == 2 ? cacheA : cacheB;
+                floatx4 vs;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int nb = 2 * (gi + DEPTH) + h;
-                    const int id = __builtin_amdgcn_readlane(idv, min(nb, 63));
-                    loader.issue(regs[u][h], id * a.H_k + g, nb < nc);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 4; ++i) vs[i] = (i < cache) ? psc[i] : 0.0f;   // a stale scale
+                if (n == 0) *reinterpret_cast<floatx4*>(st + St::kS + 64 * wave + 16 * grp) = vs;
             }
         }
+    };
+
+    // ---- consumer side
+    const int full_limit = min(t, t_ctx + min_row + 1);   // tokens visible to every column of mine
+    auto consume = [&](const unsigned char* st, int gi) {
+        half8_t kA[St::kKOps], kB[St::kKOps], vop[St::kVOps];
+#pragma unroll
+        for (int jj = 0; jj < St::kKOps; ++jj) {
+            kA[jj] = *reinterpret_cast<const half8_t*>(st + St::kK + jj * 1024 + 16 * lane);
+            kB[jj] = *reinterpret_cast<const half8_t*>(st + St::kK + (St::kKOps + jj) * 1024 + 16 * lane);
+        }
+#pragma unroll
+        for (int c = 0; c < St::kVOps; ++c)
+            vop[c] = *reinterpret_cast<const half8_t*>(st + St::kV + c * 1024 + 16 * lane);
+        floatx4 kscA, kscB, vsA, vsB;
+        if constexpr (FP8) {
+            kscA = *reinterpret_cast<const floatx4*>(st + St::kS + 16 * grp);
+            kscB = *reinterpret_cast<const floatx4*>(st + St::kS + 64 + 16 * grp);
+            vsA = *reinterpret_cast<const floatx4*>(st + St::kS + 128 + 16 * grp);
+            vsB = *reinterpret_cast<const floatx4*>(st + St::kS + 192 + 16 * grp);
+        } else {
+            kscA = kscB = floatx4{a.scale_log2e, a.scale_log2e, a.scale_log2e, a.scale_log2e};
+            vsA = vsB = floatx4{1.f, 1.f, 1.f, 1.f};
+        }
+        const int baseA = 2 * gi * kBlock;
+        const int tokA = baseA + 4 * grp;
+        const bool hasB = 2 * gi + 1 < nblk;
+        const bool tail = !(hasB && baseA + 2 * kBlock <= full_limit);
+        floatx4 sA[NR], sB[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) tile_scores<HEAD_DIM>(kA, kB, qop[r], sA[r], sB[r]);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const int visA = limit[r] - tokA;
+            tile_softmax_pv<HEAD_DIM>(sA[r], sB[r], vop, kscA, kscB, vsA, vsB, m[r], l[r], acc[r],
+                                      tail, visA, hasB ? visA - kBlock : 0);
+        }
+    };
+
+    auto stage = [&](int gi) { return lds + (gi & 1) * St::kBytes; };
+    produce_issue(0);
+    produce_store(0, stage(0));
+    if (num_groups > 1) produce_issue(1);
+    __syncthreads();
+    for (int gi = 0; gi < num_groups; ++gi) {
+        if (2 * gi * kBlock < my_max) consume(stage(gi), gi);
+        if (gi + 1 < num_groups) {
+            produce_store(gi + 1, stage(gi + 1));
+            if (gi + 2 < num_groups) produce_issue(gi + 2);
+        }
+        // group gi+1 is complete in its stage, and nobody still reads group gi's
+        __syncthreads();
     }
 
+    if (!active) return;
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         float L = l[r];
@@ -164,7 +380,6 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !query_start || !out)
         return COOPT_ERR_NULL;
     if (sh->kv_dtype == COOPT_KV_E4M3 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
-    if ((long long)sh->num_seqs * sh->num_kv_heads > 65535) return COOPT_ERR_SHAPE;
 
     PrefillArgs a{};
     a.q = (const half_t*)q;
@@ -180,14 +395,17 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
 
-    constexpr int NR = 2, DEPTH = 1;
+    constexpr int NR = 2;
     const int tiles = a.G * ((max_chunk_len + 15) / 16);
-    const dim3 grid((unsigned)((tiles + kPrefillWaves * NR - 1) / (kPrefillWaves * NR)),
-                    (unsigned)(sh->num_seqs * sh->num_kv_heads));
-    const dim3 block(64 * kPrefillWaves);
+    a.num_pairs = sh->num_seqs * sh->num_kv_heads;
+    a.wgs_per_pair = (tiles + kPrefillWaves * NR - 1) / (kPrefillWaves * NR);
+    const long long wgs = (long long)((a.num_pairs + 7) / 8) * 8 * a.wgs_per_pair;
+    if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    const dim3 grid((unsigned)wgs), block(64 * kPrefillWaves);
+    const size_t lds = 2 * (size_t)(sh->head_dim == 128 ? PrefillStage<128>::kBytes : PrefillStage<64>::kBytes);
     hipStream_t stream = (hipStream_t)hip_stream;
 #define COOPT_PREFILL(D, KV, BIG) \
-    hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, NR, DEPTH, BIG>), grid, block, 0, stream, a)
+    hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, NR, BIG>), grid, block, lds, stream, a)
     const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E4M3, true); else COOPT_PREFILL(128, COOPT_KV_E4M3, false); }
