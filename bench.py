@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
     ap.add_argument("--plan", type=str, default="",
                     help="decode plan fields in header order, comma separated (tuning)")
+    ap.add_argument("--write", choices=["fused", "separate"], default="fused",
+                    help="the step's cache write inside the decode launch (coopt_paged_gqa_decode_step) "
+                         "or as its own kernel before coopt_paged_gqa_decode (balanced path only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -159,8 +162,13 @@ def main():
         if reduce:
             coopt.paged_gqa_reduce(tmp_out, max_logits, exp_sums, lens, P, max_parts, out, shape)
 
+    fused = args.write == "fused" and not partitioned
+
     def step(i):
         kc, vc, ks, vs = pools[i % layers]
+        if fused:
+            coopt.paged_gqa_decode_step(k_new, v_new, s_new, q, kc, vc, ks, vs, bt, lens, out, ws, shape)
+            return
         if e4m3:
             coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
         else:
@@ -252,7 +260,8 @@ def main():
                    "decode_plan": plan,
                    "step": ("kv_cache_write + paged_gqa_decode_partitioned (P=%d) + paged_gqa_reduce, "
                             "one layer" % P) if partitioned else
-                           "kv_cache_write + paged_gqa_decode, one layer",
+                           ("paged_gqa_decode_step (cache write fused into the decode launch), one layer"
+                            if fused else "kv_cache_write + paged_gqa_decode, one layer"),
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),

@@ -140,6 +140,30 @@ int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* worksp
                                  size_t workspace_bytes, void* out, const coopt_shape* shape,
                                  void* hip_stream);
 
+/*
+ * One decode step in two launches instead of three: Opt-KV's write of each sequence's new token
+ * (Eq. 5, Alg. 1 phase 1) fused with the attention of Opt-GQA / Opt-Pa (Eq. 6-10).  The result is
+ * that of coopt_kv_cache_write_fp8 / _fp16 with num_tokens = num_seqs followed by
+ * coopt_paged_gqa_decode with a workspace: the same bytes end up in the cache, and `out` agrees
+ * within the attention tolerance (the new token enters as one more partial, computed from the
+ * values just quantised, while the other workgroups of the same launch read the older tokens).
+ *   k, v          device, fp16 [num_seqs][num_kv_heads][head_dim]: token s is the LAST token of
+ *                 sequence s, i.e. position context_lens[s]-1
+ *   slot_mapping  device, int64 [num_seqs]: its slot, which must be the one block_tables assigns
+ *                 to that position (not checked); negative = write nothing for this sequence and
+ *                 attend to whatever the cache holds at that position, as the two separate calls
+ *                 would
+ *   k_cache .. v_scale   as in coopt_paged_gqa_decode, but written to (scales NULL iff fp16 cache)
+ *   context_lens  INCLUDES the new token; 0 = empty sequence (nothing written, zero output rows)
+ *   workspace     required here; coopt_decode_workspace_bytes(shape) bytes, 16-byte aligned
+ * Errors as for the two separate calls; nothing is launched on error.
+ */
+int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slot_mapping,
+                                const void* q, void* k_cache, void* v_cache, float* k_scale,
+                                float* v_scale, const int32_t* block_tables,
+                                const int32_t* context_lens, void* out, void* workspace,
+                                size_t workspace_bytes, const coopt_shape* shape, void* hip_stream);
+
 /* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under the current decode plan
  * (0 if the shape is unsupported). */
 size_t coopt_decode_workspace_bytes(const coopt_shape* shape);

@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     get_decode_plan,
     kv_cache_write_fp16, kv_cache_write_fp8, lib_path, load_library, paged_gqa_decode,
     paged_gqa_decode_merge, paged_gqa_decode_partitioned, paged_gqa_decode_split,
+    paged_gqa_decode_step,
     paged_gqa_prefill_chunk, paged_gqa_reduce, set_decode_plan,
     status_string)

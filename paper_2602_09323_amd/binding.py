@@ -19,7 +19,7 @@ COOPT_KV_E4M3 = 1
 
 EXPORTS = [
     "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_paged_gqa_decode",
-    "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
+    "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
     "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
     "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
     "coopt_status_string",
@@ -62,6 +62,8 @@ def load_library():
         lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, i64p, i32, vp, vp, vp, vp, shp, vp]
         lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, i64p, i32, vp, vp, shp, vp]
         lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
+        lib.coopt_paged_gqa_decode_step.argtypes = [vp, vp, i64p, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                    ctypes.c_size_t, shp, vp]
         lib.coopt_paged_gqa_decode_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
         lib.coopt_paged_gqa_decode_merge.argtypes = [vp, vp, ctypes.c_size_t, vp, shp, vp]
         lib.coopt_decode_workspace_bytes.argtypes = [shp]
@@ -145,6 +147,15 @@ def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, contex
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
         _ptr(context_lens), _ptr(out), _ptr(workspace), ctypes.c_size_t(nbytes),
         ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode")
+
+
+def paged_gqa_decode_step(k, v, slot_mapping, q, k_cache, v_cache, k_scale, v_scale, block_tables,
+                          context_lens, out, workspace, shape: Shape, stream=None) -> None:
+    _check(load_library().coopt_paged_gqa_decode_step(
+        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
+        _ptr(v_scale), _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(workspace),
+        ctypes.c_size_t(workspace.numel() * workspace.element_size()), ctypes.byref(shape),
+        _stream(stream)), "coopt_paged_gqa_decode_step")
 
 
 def paged_gqa_decode_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcoopt_attn.so")
 SOURCES = ["kv_write.hip", "decode.hip", "decode_flat.hip", "prefill.hip", "gather.hip"]
-HEADERS = [os.path.join(CSRC, h) for h in ("common.hpp", "attn_tile.hpp",
+HEADERS = [os.path.join(CSRC, h) for h in ("common.hpp", "attn_tile.hpp", "kv_quant.hpp",
                                           "decode_internal.hpp")] + [
     os.path.join(ROOT, "include", "coopt_attn.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -405,6 +405,31 @@ extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const 
     return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
 }
 
+extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
+                                           const int64_t* slot_mapping, const void* q,
+                                           void* k_cache, void* v_cache, float* k_scale,
+                                           float* v_scale, const int32_t* block_tables,
+                                           const int32_t* context_lens, void* out, void* workspace,
+                                           size_t workspace_bytes, const coopt_shape* sh,
+                                           void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    if (!k || !v || !slot_mapping) return COOPT_ERR_NULL;
+    st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
+    if (st != COOPT_OK) return st;
+    if (!out || !workspace) return COOPT_ERR_NULL;
+    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const FlatAppend append{k, v, slot_mapping};
+    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                           workspace, sh, flat_plan(), stream, &append);
+    if (st != COOPT_OK) return st;
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
+}
+
 extern "C" int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
                                             const float* k_scale, const float* v_scale,
                                             const int32_t* block_tables,

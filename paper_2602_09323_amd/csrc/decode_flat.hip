@@ -23,6 +23,7 @@
 // The per-group arithmetic is in attn_tile.hpp.
 #include "attn_tile.hpp"
 #include "decode_internal.hpp"
+#include "kv_quant.hpp"
 
 namespace coopt {
 
@@ -52,6 +53,7 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
 // Shares are cut on the cost axis, so a wave that crosses a pair boundary gets fewer groups.
 struct FlatSchedule {
     const int32_t* lens;
+    const int64_t* new_slots;   // fused step only: slot of the token each sequence appends, or NULL
     int S, H_k, extra, lane;
     // cache of the first 64 sequences (the whole batch when S <= 64)
     int t0, incl0, total0, cincl0, ctotal0;
@@ -62,11 +64,21 @@ struct FlatSchedule {
         return t > 0 ? H_k * (groups_of(t) + extra) : 0;
     }
 
-    __device__ __forceinline__ FlatSchedule(const int32_t* context_lens, int num_seqs, int kv_heads,
-                                            int pair_extra, int lane_id)
-        : lens(context_lens), S(num_seqs), H_k(kv_heads), extra(pair_extra), lane(lane_id)
+    // Tokens of sequence s that this launch reads from the cache: all of them, or -- in the fused
+    // step, for a sequence whose new token is being written by this same launch -- all but the last.
+    __device__ __forceinline__ int cached_len(int s) const
     {
-        t0 = lane < S ? lens[lane] : 0;
+        int t = lens[s];
+        if (new_slots && t > 0 && new_slots[s] >= 0) t -= 1;
+        return t;
+    }
+
+    __device__ __forceinline__ FlatSchedule(const int32_t* context_lens, const int64_t* appended,
+                                            int num_seqs, int kv_heads, int pair_extra, int lane_id)
+        : lens(context_lens), new_slots(appended), S(num_seqs), H_k(kv_heads), extra(pair_extra),
+          lane(lane_id)
+    {
+        t0 = lane < S ? cached_len(lane) : 0;
         incl0 = wave_inclusive_scan(real_weight(t0));
         total0 = __builtin_amdgcn_readlane(incl0, 63);
         cincl0 = wave_inclusive_scan(cost_weight(t0));
@@ -78,7 +90,7 @@ struct FlatSchedule {
     {
         int sum = ctotal0;
         for (int base = 64; base < S; base += 64) {
-            int v = cost_weight(base + lane < S ? lens[base + lane] : 0);
+            int v = cost_weight(base + lane < S ? cached_len(base + lane) : 0);
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
             sum += wave_uniform(v);      // equal in all lanes; tell the compiler so
@@ -96,7 +108,7 @@ struct FlatSchedule {
         int tile_total = total0, ctile_total = ctotal0;
         for (int base = 0;; base += 64) {
             if (base > 0) {
-                tl = base + lane < S ? lens[base + lane] : 0;
+                tl = base + lane < S ? cached_len(base + lane) : 0;
                 incl = wave_inclusive_scan(real_weight(tl));
                 tile_total = __builtin_amdgcn_readlane(incl, 63);
                 cincl = wave_inclusive_scan(cost_weight(tl));
@@ -115,6 +127,19 @@ struct FlatSchedule {
             }
             carry += tile_total;
             ccarry += ctile_total;
+        }
+    }
+
+    // Cost-axis position of sequence seq's first unit.
+    __device__ __forceinline__ int cost_first_of(int seq) const
+    {
+        int ccarry = 0;
+        for (int base = 0;; base += 64) {
+            const int tl = base == 0 ? t0 : (base + lane < S ? cached_len(base + lane) : 0);
+            const int cincl = base == 0 ? cincl0 : wave_inclusive_scan(cost_weight(tl));
+            if (seq < base + 64)
+                return ccarry + __builtin_amdgcn_readlane(cincl - cost_weight(tl), seq - base);
+            ccarry += __builtin_amdgcn_readlane(cincl, 63);
         }
     }
 
@@ -148,7 +173,18 @@ struct FlatArgs {
     int32_t min_share;    // cost units (groups plus pair extras) per workgroup, lower bound
     int32_t pair_extra;   // cost units charged to a share for every pair that ends inside it
     int32_t pool_tiles;   // num_blocks * H_k
+    int32_t decode_wgs;   // workgroups that run attention; in the fused step the grid continues
+                          // with one workgroup per (sequence, KV head) that appends the new token
     float scale_log2e;
+    // fused step only (new_slots != NULL): the token every sequence appends, and the cache as
+    // written to
+    const int64_t* new_slots;
+    const half_t* k_new;
+    const half_t* v_new;
+    uint8_t* k_cache_w;
+    uint8_t* v_cache_w;
+    float* k_scale_w;
+    float* v_scale_w;
 };
 
 // How the flattened groups are cut into contiguous shares: `nwg` workgroups, the first `r` with
@@ -230,6 +266,81 @@ __device__ __forceinline__ void stage_q_operand(unsigned char* stage, const half
 #endif
 }
 
+// Fused step: one wavefront per (sequence, KV head) appends the sequence's new token to the cache
+// (Opt-KV Eq. 5 and Alg. 1 phase 1, exactly as the cache-write kernel does) and contributes that
+// token's share of the attention as one more partial of the pair, (m, l, o) = (z, 1, v~), from the
+// values it has just quantised -- the attention workgroups of the same launch read only the tokens
+// that were in the cache before, so nothing in the launch waits for anything else.  It also leaves
+// the pair's partial count (the attention workgroups' partials plus this one).
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void append_and_attend(const FlatArgs& a, const FlatSchedule& sched,
+                                                  const FlatCut& cut, int ctotal, int pair, int lane)
+{
+    constexpr int E = HEAD_DIM / 64;
+    const int seq = pair / a.H_k;
+    const int g = pair - seq * a.H_k;
+    if (seq >= a.num_seqs) return;
+    const int64_t slot = a.new_slots[seq];
+    const bool appends = slot >= 0 && a.context_lens[seq] > 0;
+    // partials the attention workgroups write for this pair
+    const int t_cached = sched.cached_len(seq);
+    const int ng = groups_of(t_cached);
+    int count = 0;
+    if (ng > 0 && ctotal > 0) {
+        const int pair_first = sched.cost_first_of(seq) + g * (ng + a.pair_extra) + a.pair_extra;
+        count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+    }
+    if (lane == 0) a.counts[pair] = count + (appends ? 1 : 0);
+    if (!appends) return;                                       // Eq. 5: filtered token
+
+    const int64_t blk = slot / kBlock;
+    const int off = (int)(slot - blk * kBlock);
+    const size_t tile = (size_t)(blk * a.H_k + g);
+    const half_t* k_row = a.k_new + (size_t)pair * HEAD_DIM;
+    const half_t* v_row = a.v_new + (size_t)pair * HEAD_DIM;
+    float kd[E], vd[E];                                         // the values attention will see
+    if constexpr (KV == COOPT_KV_E4M3) {
+        const QuantRow<HEAD_DIM> qr = quantise_row_to_cache<HEAD_DIM>(
+            k_row, v_row, tile, off, lane, a.k_cache_w, a.v_cache_w, a.k_scale_w, a.v_scale_w);
+        const half2_t kh = e4m3x2_to_half2<false>(qr.k_codes), vh = e4m3x2_to_half2<false>(qr.v_codes);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            kd[e] = (float)kh[e] * qr.k_scale;
+            vd[e] = (float)vh[e] * qr.v_scale;
+        }
+    } else {
+        half_t* kc = reinterpret_cast<half_t*>(a.k_cache_w) + tile * (kBlock * HEAD_DIM);
+        half_t* vc = reinterpret_cast<half_t*>(a.v_cache_w) + tile * (kBlock * HEAD_DIM);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int dim = lane * E + e;
+            const half_t kk = k_row[dim], vv = v_row[dim];
+            kc[k_tile_index<2>(off, dim)] = kk;
+            vc[v_tile_index<2>(off, dim)] = vv;
+            kd[e] = (float)kk;
+            vd[e] = (float)vv;
+        }
+    }
+    const int slot_idx = count;                                 // after the attention partials
+    for (int h = 0; h < a.G; ++h) {
+        const size_t row = (size_t)seq * a.H_q + g * a.G + h;
+        const half_t* q_row = a.q + row * HEAD_DIM + lane * E;
+        float dot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dot += (float)q_row[e] * kd[e];
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) dot += __shfl_xor(dot, s);
+        const size_t at = row * a.max_slots + slot_idx;
+        float* dst = a.tmp_out + at * HEAD_DIM + lane * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dst[e] = vd[e];
+        if (lane == 0) {
+            a.max_logits[at] = dot * a.scale_log2e * kLn2;      // natural-log units
+            a.exp_sums[at] = 1.0f;
+        }
+    }
+}
+
 // One wave per workgroup; the wave's share is ONE stream of groups that runs across the
 // boundaries between (sequence, KV head) pairs.  The loads of the next pair's first groups are in
 // flight while the last groups of the current pair are being consumed, and the pair's partial is
@@ -248,10 +359,14 @@ flat_stream_kernel(const FlatArgs a)
     const int lane = threadIdx.x;
     const int n = lane & 15, grp = lane >> 4;
 
-    const FlatSchedule sched(a.context_lens, a.num_seqs, a.H_k, a.pair_extra, lane);
+    const FlatSchedule sched(a.context_lens, a.new_slots, a.num_seqs, a.H_k, a.pair_extra, lane);
     const int ctotal = sched.cost_total();
+    const FlatCut cut(max(ctotal, 1), a.decode_wgs, a.min_share);   // shares of the cost axis
+    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
+        append_and_attend<HEAD_DIM, KV>(a, sched, cut, ctotal, blockIdx.x - a.decode_wgs, lane);
+        return;
+    }
     if (ctotal == 0) return;
-    const FlatCut cut(ctotal, gridDim.x, a.min_share);          // shares of the cost axis
     if ((int)blockIdx.x >= cut.nwg) return;
     const int x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
     const int x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
@@ -344,7 +459,8 @@ flat_stream_kernel(const FlatArgs a)
                         ps.row0 = seq * a.H_q + g * a.G;
                         ps.slot = blockIdx.x - cut.wg_of(pair_first);
                         // the pair's first workgroup also counts the pair's partials
-                        ps.count_at = ps.slot == 0 ? seq * a.H_k + g : -1;
+                        // (in the fused step the appending workgroups do the counting)
+                        ps.count_at = (ps.slot == 0 && !a.new_slots) ? seq * a.H_k + g : -1;
                         ps.count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
                         l += __shfl_xor(l, 16);
                         l += __shfl_xor(l, 32);
@@ -497,7 +613,8 @@ int flat_max_slots(const coopt_shape* sh, const FlatPlan& plan)
 {
     const int max_groups = (sh->max_blocks_per_seq + 1) / 2;
     const int min_share = plan.min_share_groups();
-    return (max_groups + min_share - 1) / min_share + 1;
+    // a pair's groups span at most this many shares, plus the fused step's partial of the new token
+    return (max_groups + min_share - 1) / min_share + 2;
 }
 
 size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan)
@@ -553,7 +670,7 @@ static FlatArgs flat_args(const coopt_shape* sh, const FlatPlan& plan, void* wor
 int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
                       const float* v_scale, const int32_t* block_tables,
                       const int32_t* context_lens, void* workspace, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream)
+                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append)
 {
     if (flat_max_cost(sh) > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     FlatArgs a = flat_args(sh, plan, workspace);
@@ -561,7 +678,20 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
     a.cv = CacheView{(const uint8_t*)k_cache, (const uint8_t*)v_cache, k_scale, v_scale};
     a.block_tables = block_tables;
     a.context_lens = context_lens;
-    const dim3 grid((unsigned)flat_grid_groups(sh, plan));
+    a.decode_wgs = flat_grid_groups(sh, plan);
+    long long wgs = a.decode_wgs;
+    if (append) {
+        a.new_slots = append->slot_mapping;
+        a.k_new = (const half_t*)append->k;
+        a.v_new = (const half_t*)append->v;
+        a.k_cache_w = (uint8_t*)const_cast<void*>(k_cache);
+        a.v_cache_w = (uint8_t*)const_cast<void*>(v_cache);
+        a.k_scale_w = const_cast<float*>(k_scale);
+        a.v_scale_w = const_cast<float*>(v_scale);
+        wgs += (long long)sh->num_seqs * sh->num_kv_heads;
+    }
+    if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    const dim3 grid((unsigned)wgs);
     const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan.depth, grid, stream);

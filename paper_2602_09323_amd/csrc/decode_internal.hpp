@@ -17,13 +17,22 @@ struct FlatPlan {
 
 size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan);
 
-// Enqueue the balanced split kernel (attention -> partial results in the workspace) and the merge
+// The token every sequence appends in a fused step: fp16 rows [num_seqs][H_k][d] and the slot of
+// each (negative: that sequence appends nothing).
+struct FlatAppend {
+    const void* k;
+    const void* v;
+    const int64_t* slot_mapping;
+};
+
+// Enqueue the balanced split kernel (attention -> partial results in the workspace; with `append`
+// also the cache write of one new token per sequence and that token's partial) and the merge
 // kernel (partials -> fp16 output rows).  Both derive the same schedule from the context lengths
 // and the plan, so the plan must not change between them.  Each returns a coopt_status.
 int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
                       const float* v_scale, const int32_t* block_tables,
                       const int32_t* context_lens, void* workspace, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream);
+                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append = nullptr);
 int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
                       const FlatPlan& plan, hipStream_t stream);
 

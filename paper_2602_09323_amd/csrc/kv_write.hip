@@ -6,41 +6,9 @@
 // scattered in 16-byte (K) and 1-byte (V) pieces.  Write volume is a few hundred bytes per
 // row, against kilobytes per token read by attention, so this kernel is latency-, not
 // bandwidth-bound and is kept simple.
-#include "common.hpp"
+#include "kv_quant.hpp"
 
 namespace coopt {
-
-__device__ __forceinline__ float wave_max(float a)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
-    return a;
-}
-
-// Dynamic per-row scale and the scaled, clamped values (binary32, correctly rounded divisions so
-// that the stored bytes are defined bit for bit).
-template <int E>
-__device__ __forceinline__ float scale_row(const float (&x)[E], float (&y)[E])
-{
-    float amax = 0.0f;
-#pragma unroll
-    for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(x[e]));
-    amax = wave_max(amax);
-    const float scale = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kE4M3Max);
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        float q = __fdiv_rn(x[e], scale);
-        y[e] = fminf(fmaxf(q, -kE4M3Max), kE4M3Max);
-    }
-    return scale;
-}
-
-// binary32 -> OCP E4M3 by the gfx950 convert (round to nearest even; inputs are already in
-// [-448, 448], so the instruction's overflow behaviour never comes into play).
-__device__ __forceinline__ uint32_t encode_pair(float a, float b)
-{
-    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
-}
 
 template <int HEAD_DIM>
 __global__ void __launch_bounds__(256)
@@ -49,7 +17,6 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
                     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache,
                     float* __restrict__ k_scale, float* __restrict__ v_scale)
 {
-    constexpr int E = HEAD_DIM / 64;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // token * H_k + head
     if (row >= num_rows) return;
     const int tok = row / H_k, head = row - tok * H_k;
@@ -60,32 +27,8 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
     const int lane = threadIdx.x & 63;
     const size_t tile = (size_t)(blk * H_k + head);
 
-    float x[E], y[E];
-    // ---- K tile [d/16][16 tokens][16]: the lane's E dims are neighbours inside one 16-byte chunk
-#pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = (float)k[(size_t)row * HEAD_DIM + lane * E + e];
-    float scale = scale_row<E>(x, y);
-    uint8_t* kdst = k_cache + tile * (kBlock * HEAD_DIM) + k_tile_index<1>(off, lane * E);
-    if constexpr (E == 2) {
-        *reinterpret_cast<uint16_t*>(kdst) = (uint16_t)encode_pair(y[0], y[1]);
-    } else {
-        *kdst = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
-    }
-    if (lane == 0) k_scale[tile * kBlock + off] = scale;
-
-    // ---- V tile: token index innermost, one byte per (dim, token)
-#pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = (float)v[(size_t)row * HEAD_DIM + lane * E + e];
-    scale = scale_row<E>(x, y);
-    uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
-    if constexpr (E == 2) {
-        const uint32_t c = encode_pair(y[0], y[1]);
-        vtile[v_tile_index<1>(off, lane * E)] = (uint8_t)(c & 0xffu);
-        vtile[v_tile_index<1>(off, lane * E + 1)] = (uint8_t)(c >> 8);
-    } else {
-        vtile[v_tile_index<1>(off, lane)] = (uint8_t)(encode_pair(y[0], 0.0f) & 0xffu);
-    }
-    if (lane == 0) v_scale[tile * kBlock + off] = scale;
+    quantise_row_to_cache<HEAD_DIM>(k + (size_t)row * HEAD_DIM, v + (size_t)row * HEAD_DIM, tile, off,
+                                    lane, k_cache, v_cache, k_scale, v_scale);
 }
 
 template <int HEAD_DIM>

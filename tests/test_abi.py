@@ -66,26 +66,32 @@ def test_unsupported_shapes_are_refused_without_launch(lib, bad):
     sh = _shape(**bad)
     one = ctypes.c_void_p(16)          # never dereferenced: validation comes first
     assert lib.coopt_kv_cache_write_fp8(one, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -2
-    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, None, 0, ctypes.byref(sh), None) == -2
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, None, ctypes.c_size_t(0), ctypes.byref(sh), None) == -2
     assert lib.coopt_paged_gqa_reduce(one, one, one, one, 16, 1, one, ctypes.byref(sh), None) == -2
     assert lib.coopt_decode_workspace_bytes(ctypes.byref(sh)) == 0
 
 
 def test_null_pointers_and_bad_arguments(lib):
+    # sizes go in as ctypes.c_size_t: a bare Python int is passed as a 32-bit int, and the upper
+    # half of a size_t argument on the stack would be whatever was there
     sh = _shape()
     one = ctypes.c_void_p(16)
     assert lib.coopt_kv_cache_write_fp8(None, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -1
     assert lib.coopt_kv_cache_write_fp8(one, one, one, 1, one, one, None, one, ctypes.byref(sh), None) == -1
     assert lib.coopt_kv_cache_write_fp8(one, one, one, 0, one, one, one, one, ctypes.byref(sh), None) == 0
     assert lib.coopt_kv_cache_write_fp16(one, one, one, 1, one, one, ctypes.byref(sh), None) == -2  # wrong dtype
-    assert lib.coopt_paged_gqa_decode(one, one, one, None, one, one, one, one, None, 0, ctypes.byref(sh), None) == -1
-    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, None, None, 0, ctypes.byref(sh), None) == -1
+    assert lib.coopt_paged_gqa_decode(one, one, one, None, one, one, one, one, None, ctypes.c_size_t(0), ctypes.byref(sh), None) == -1
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, None, None, ctypes.c_size_t(0), ctypes.byref(sh), None) == -1
     # split decode with a workspace that is too small / misaligned
     # (every call below is refused by validation before any launch: pointers are never read)
     sh2 = _shape(max_blocks_per_seq=128)
     need2 = lib.coopt_decode_workspace_bytes(ctypes.byref(sh2))
-    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, one, need2 - 1, ctypes.byref(sh2), None) == -3
-    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, ctypes.c_void_p(8), need2, ctypes.byref(sh2), None) == -3
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2 - 1), ctypes.byref(sh2), None) == -3
+    assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, ctypes.c_void_p(8), ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -3
+    # fused step: the new rows and a workspace are required
+    assert lib.coopt_paged_gqa_decode_step(None, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1
+    assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, None, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1
+    assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2 - 1), ctypes.byref(sh2), None) == -3
     # partitioned: partition size must be a positive multiple of 16; buffers must cover the table
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 24, one, one, one, 8, ctypes.byref(sh), None) == -2
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, one, one, one, 7, ctypes.byref(sh), None) == -3
