@@ -176,7 +176,11 @@ size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
  * (a positive multiple of 32) unless the whole batch is.  coopt_paged_gqa_decode_partitioned runs
  * `waves_per_group` (1, 2, 4 or 8) wavefronts per partition; the balanced kernel ignores that
  * field.  In both, every wavefront keeps `pipeline_depth` (1, 2 or 3) two-block groups of the
- * cache in flight.
+ * cache in flight.  `softmax_reduction` selects how the balanced kernel keeps the softmax
+ * statistics: 0 (default) = a running reference max per lane that is raised only when a score
+ * exceeds it by a margin, sums reduced once at the end; 1 = the mechanism Opt-Pa states (Alg. 3,
+ * Eq. 10): max and sum of every group of blocks reduced through shared memory and the accumulator
+ * rescaled each time -- kept to compare the two on this hardware (pipeline_depth is then 2).
  * coopt_set_decode_plan validates every field and returns COOPT_ERR_SHAPE (changing nothing) if
  * one is out of range; tokens_per_group changes coopt_decode_workspace_bytes.
  */
@@ -185,6 +189,7 @@ typedef struct coopt_decode_plan {
     int32_t waves_per_group;
     int32_t pipeline_depth;
     int32_t grid_waves;
+    int32_t softmax_reduction;
 } coopt_decode_plan;
 
 int coopt_set_decode_plan(const coopt_decode_plan* plan);

@@ -33,7 +33,8 @@ class CooptError(RuntimeError):
 class DecodePlan(ctypes.Structure):
     """Mirror of ``coopt_decode_plan``."""
     _fields_ = [("tokens_per_group", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
-                ("pipeline_depth", ctypes.c_int32), ("grid_waves", ctypes.c_int32)]
+                ("pipeline_depth", ctypes.c_int32), ("grid_waves", ctypes.c_int32),
+                ("softmax_reduction", ctypes.c_int32)]
 
 
 class Shape(ctypes.Structure):

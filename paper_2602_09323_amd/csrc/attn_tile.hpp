@@ -362,4 +362,101 @@ __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRe
     }
 }
 
+// The same step with the softmax statistics reduced the way Opt-Pa states it (Alg. 3, Eq. 10): a
+// max reduction and a sum reduction ("block_sum") over the group's tokens through shared memory,
+// and the accumulator rescaled at every group to the exact running max.  Kept to measure that
+// mechanism against group_update on this machine; the results agree up to rounding.  `red` is
+// 128 floats of LDS private to the wavefront, which must be the only one of its workgroup (the
+// barriers only order this wave's own LDS traffic).  l ends up in the lanes of group 0, so the
+// caller's sum over the four lane groups still gives the column's total.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void group_update_block_reduce(
+    BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B, const half8_t (&qop)[HEAD_DIM / 32],
+    float& m, float& l, floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA, int visB, int cacheA,
+    int cacheB, float scale_log2e, float* red, int lane)
+{
+    const int n = lane & 15;
+    floatx4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) {
+        sA = mfma_16x16x32(k_operand<HEAD_DIM, KV>(A, jj), qop[jj], sA);
+        sB = mfma_16x16x32(k_operand<HEAD_DIM, KV>(B, jj), qop[jj], sB);
+    }
+    float z[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (KV == COOPT_KV_E4M3) {
+            z[i] = sA[i] * (A.ks[i] * scale_log2e);
+            z[4 + i] = sB[i] * (B.ks[i] * scale_log2e);
+        } else {
+            z[i] = sA[i] * scale_log2e;
+            z[4 + i] = sB[i] * scale_log2e;
+        }
+    }
+    if (tail) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);
+            z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
+        }
+        if constexpr (KV == COOPT_KV_E4M3) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                A.vs[i] = (i < cacheA) ? A.vs[i] : 0.0f;
+                B.vs[i] = (i < cacheB) ? B.vs[i] : 0.0f;
+            }
+        }
+        uint32_t a0, a1, b0, b1;
+        token_masks<KV>(cacheA, a0, a1);
+        token_masks<KV>(cacheB, b0, b1);
+#pragma unroll
+        for (int j = 0; j < BlockRegs<HEAD_DIM, KV>::NL; ++j) {
+            if constexpr (KV == COOPT_KV_E4M3) {
+                A.v[j] &= a0;
+                B.v[j] &= b0;
+            } else {
+                A.v[j] &= u32x4{a0, a1, a0, a1};
+                B.v[j] &= u32x4{b0, b1, b0, b1};
+            }
+        }
+    }
+    // ---- max over the group's 32 tokens of column n, through shared memory
+    red[lane] = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
+                      fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+    __syncthreads();
+    const float nm = fmaxf(m, fmaxf(fmaxf(red[n], red[16 + n]), fmaxf(red[32 + n], red[48 + n])));
+    const float alpha = __builtin_amdgcn_exp2f(m - nm);       // m = -inf at the start gives 0
+    m = nm;
+    const float mm = m - kPShift;
+    float p[8], ps = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(z[i] - mm);
+        ps += p[i];
+    }
+    // ---- block_sum: the group's exponential sum of column n, through shared memory
+    red[64 + lane] = ps;
+    __syncthreads();
+    const float bs = (red[64 + n] + red[80 + n]) + (red[96 + n] + red[112 + n]);
+    l = l * alpha + (lane < 16 ? bs : 0.0f);
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
+    if constexpr (KV == COOPT_KV_E4M3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] *= A.vs[i];
+            p[4 + i] *= B.vs[i];
+        }
+    }
+    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
+                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) {
+        const half4_t va = v_operand<HEAD_DIM, KV>(A, c);
+        const half4_t vb = v_operand<HEAD_DIM, KV>(B, c);
+        const half8_t vop = {va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
+        acc[c] = mfma_16x16x32(vop, pop, acc[c]);
+    }
+}
+
 }  // namespace coopt

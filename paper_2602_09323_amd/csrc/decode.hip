@@ -248,7 +248,7 @@ partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restri
 // ------------------------------------------------------------------ host side
 
 // tokens_per_group, waves per workgroup, depth, grid waves (one wavefront per SIMD of the 256 CUs)
-static coopt_decode_plan g_plan = {128, 1, 2, 1024};
+static coopt_decode_plan g_plan = {128, 1, 2, 1024, 0};
 
 template <int HEAD_DIM, int KV, bool BIG>
 static void launch_decode_depth(const DecodeArgs& a, int depth, dim3 grid, dim3 block, size_t lds,
@@ -354,6 +354,7 @@ extern "C" int coopt_set_decode_plan(const coopt_decode_plan* p)
     if (w != 1 && w != 2 && w != 4 && w != 8) return COOPT_ERR_SHAPE;
     if (p->pipeline_depth < 1 || p->pipeline_depth > 3) return COOPT_ERR_SHAPE;
     if (p->grid_waves <= 0 || p->grid_waves > (1 << 20)) return COOPT_ERR_SHAPE;
+    if (p->softmax_reduction != 0 && p->softmax_reduction != 1) return COOPT_ERR_SHAPE;
     g_plan = *p;
     return COOPT_OK;
 }
@@ -365,7 +366,8 @@ extern "C" void coopt_get_decode_plan(coopt_decode_plan* p)
 
 static FlatPlan flat_plan()
 {
-    return FlatPlan{g_plan.tokens_per_group, g_plan.pipeline_depth, g_plan.grid_waves};
+    return FlatPlan{g_plan.tokens_per_group, g_plan.pipeline_depth, g_plan.grid_waves,
+                    g_plan.softmax_reduction};
 }
 
 extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh)

@@ -346,7 +346,7 @@ __device__ __forceinline__ void append_and_attend(const FlatArgs& a, const FlatS
 // flight while the last groups of the current pair are being consumed, and the pair's partial is
 // stored from the accumulator registers in between.  The block numbers of up to 32 groups come from
 // one gathered vector load (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
-template <int HEAD_DIM, int KV, int DEPTH, bool BIG>
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
 __global__ void __launch_bounds__(64)
 flat_stream_kernel(const FlatArgs a)
 {
@@ -379,6 +379,7 @@ flat_stream_kernel(const FlatArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // HEAD_DIM / 32 KiB
     constexpr int kParkAcc = HEAD_DIM / 16 * 1024;               // parked o, then m and l per lane
     unsigned char* park = q_stage + HEAD_DIM / 32 * 1024;
+    float* red = reinterpret_cast<float*>(park + kParkAcc + 512);  // BLOCK_REDUCE: 128 floats
     PartialSlot parked;
     parked.row0 = -1;
     half8_t q_cur[HEAD_DIM / 32];
@@ -444,9 +445,14 @@ flat_stream_kernel(const FlatArgs a)
                     const int gi = __builtin_amdgcn_readlane(gi_l, 2 * e);
                     const int baseA = 2 * gi * kBlock;
                     const int visA = t - baseA - 4 * grp;
-                    group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], q_cur, m, l, acc,
-                                               baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
-                                               visA - kBlock, a.scale_log2e);
+                    if constexpr (BLOCK_REDUCE)
+                        group_update_block_reduce<HEAD_DIM, KV>(
+                            regs[u][0], regs[u][1], q_cur, m, l, acc, baseA + 2 * kBlock > t, visA,
+                            visA - kBlock, visA, visA - kBlock, a.scale_log2e, red, lane);
+                    else
+                        group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], q_cur, m, l, acc,
+                                                   baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
+                                                   visA - kBlock, a.scale_log2e);
                     if ((last_mask >> (2 * e)) & 1) {
                         // ---- the segment ends: its partial is (m, l, acc / l)
                         const int seq = __builtin_amdgcn_readlane(seq_l, 2 * e);
@@ -590,23 +596,28 @@ flat_merge_kernel(const FlatArgs a)
 }
 
 template <int HEAD_DIM, int KV, bool BIG>
-static void launch_flat_depth(const FlatArgs& a, int depth, dim3 grid, hipStream_t stream)
+static void launch_flat_depth(const FlatArgs& a, const FlatPlan& plan, dim3 grid, hipStream_t stream)
 {
     const dim3 block(64);
-    // staging area of one q operand + one parked partial (o, m, l per lane)
-    const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512;
-    switch (depth) {
-    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG>), grid, block, lds, stream, a); break;
-    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG>), grid, block, lds, stream, a); break;
-    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG>), grid, block, lds, stream, a); break;
+    // staging area of one q operand + one parked partial (o, m, l per lane) + reduction scratch
+    const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512 + 512;
+    if (plan.block_reduce) {             // comparison variant: depth 2 only
+        hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG, true>), grid, block, lds, stream, a);
+        return;
+    }
+    switch (plan.depth) {
+    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG, false>), grid, block, lds, stream, a); break;
+    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG, false>), grid, block, lds, stream, a); break;
+    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG, false>), grid, block, lds, stream, a); break;
     }
 }
 
 template <int HEAD_DIM, int KV>
-static void launch_flat_pool(const FlatArgs& a, bool big, int depth, dim3 grid, hipStream_t stream)
+static void launch_flat_pool(const FlatArgs& a, bool big, const FlatPlan& plan, dim3 grid,
+                             hipStream_t stream)
 {
-    if (big) launch_flat_depth<HEAD_DIM, KV, true>(a, depth, grid, stream);
-    else launch_flat_depth<HEAD_DIM, KV, false>(a, depth, grid, stream);
+    if (big) launch_flat_depth<HEAD_DIM, KV, true>(a, plan, grid, stream);
+    else launch_flat_depth<HEAD_DIM, KV, false>(a, plan, grid, stream);
 }
 
 int flat_max_slots(const coopt_shape* sh, const FlatPlan& plan)
@@ -694,11 +705,11 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
     const dim3 grid((unsigned)wgs);
     const bool big = !pool_fits_small(sh);
     if (sh->kv_dtype == COOPT_KV_E4M3) {
-        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan.depth, grid, stream);
-        else launch_flat_pool<64, COOPT_KV_E4M3>(a, big, plan.depth, grid, stream);
+        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan, grid, stream);
+        else launch_flat_pool<64, COOPT_KV_E4M3>(a, big, plan, grid, stream);
     } else {
-        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_FP16>(a, big, plan.depth, grid, stream);
-        else launch_flat_pool<64, COOPT_KV_FP16>(a, big, plan.depth, grid, stream);
+        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_FP16>(a, big, plan, grid, stream);
+        else launch_flat_pool<64, COOPT_KV_FP16>(a, big, plan, grid, stream);
     }
     return launch_status();
 }

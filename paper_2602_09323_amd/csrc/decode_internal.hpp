@@ -12,6 +12,7 @@ struct FlatPlan {
     int tokens_per_group;   // minimum share of a workgroup, in tokens (32 per two-block group)
     int depth;              // two-block groups in flight per wavefront
     int grid_waves;         // wavefronts (= single-wave workgroups) in the whole grid
+    int block_reduce;       // 1: softmax statistics reduced through LDS at every group (comparison)
     int min_share_groups() const { return std::max(1, tokens_per_group / (2 * kBlock)); }
 };
 

@@ -43,7 +43,7 @@ def _struct_fields(name):
 def test_structs_match_header():
     assert ctypes.sizeof(coopt.Shape) == 9 * 4
     assert [f[0] for f in coopt.Shape._fields_] == _struct_fields("coopt_shape")
-    assert ctypes.sizeof(coopt.DecodePlan) == 4 * 4
+    assert ctypes.sizeof(coopt.DecodePlan) == 5 * 4
     assert [f[0] for f in coopt.DecodePlan._fields_] == _struct_fields("coopt_decode_plan")
 
 
@@ -101,7 +101,7 @@ def test_null_pointers_and_bad_arguments(lib):
     good = dict(coopt.get_decode_plan())
     for bad in (dict(tokens_per_group=100), dict(tokens_per_group=0), dict(waves_per_group=3),
                 dict(pipeline_depth=4), dict(pipeline_depth=0), dict(grid_waves=0),
-                dict(grid_waves=-5)):
+                dict(grid_waves=-5), dict(softmax_reduction=2)):
         with pytest.raises(coopt.CooptError):
             coopt.set_decode_plan(**bad)
         assert coopt.get_decode_plan() == good        # a refused plan changes nothing

@@ -48,18 +48,20 @@ def test_ragged_lengths_and_group_sizes(oracle_mod, kv_dtype, H_q, H_k, d):
     for split in (False, True):
         got = hip_decode(w, dcache, split=split)
         assert_close(got, ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} split={split}")
+    coopt.set_decode_plan(softmax_reduction=1)      # Opt-Pa's shared-memory max / block_sum form
+    assert_close(hip_decode(w, dcache, split=True), ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} block reduce")
 
 
-def _plan(tokens, waves, depth, grid):
+def _plan(tokens, waves, depth, grid, reduction=0):
     return dict(tokens_per_group=tokens, waves_per_group=waves, pipeline_depth=depth,
-                grid_waves=grid)
+                grid_waves=grid, softmax_reduction=reduction)
 
 
 @pytest.mark.parametrize("plan", [(32, 1, 1, 64), (32, 1, 2, 2048), (64, 2, 2, 512),
                                   (128, 1, 3, 2048), (128, 8, 2, 2048), (512, 4, 3, 256),
                                   (1024, 8, 2, 2048), (256, 4, 1, 24), (128, 1, 2, 7),
                                   (32, 2, 2, 6), (128, 1, 2, 1024), (128, 1, 2, 2), (128, 1, 3, 3),
-                                  (2048, 1, 1, 1024)])
+                                  (2048, 1, 1, 1024), (128, 1, 2, 1024, 1), (32, 1, 2, 9, 1)])
 def test_every_launch_plan_gives_the_same_answer(oracle_mod, plan):
     lens = [300, 1, 1025, 47, 640]
     w = workloads.make_custom("plan", seed=32, S=len(lens), H_q=10, H_k=2, d=128, B=16, NB=160,
