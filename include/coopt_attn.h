@@ -101,6 +101,17 @@ int coopt_kv_cache_write_fp16(const void* k, const void* v, const int64_t* slot_
                               const coopt_shape* shape, void* hip_stream);
 
 /*
+ * The same write with the SkipSet of Opt-KV Eq. 5 spelled out: token index i of this call is left
+ * out if bit i%32 of skip_set[i/32] is set (device, uint32 [ceil(num_tokens/32)]; NULL = empty
+ * set) or its slot is negative.  Dispatches on shape->kv_dtype: E4M3 as coopt_kv_cache_write_fp8,
+ * fp16 as coopt_kv_cache_write_fp16 (k_scale and v_scale are then ignored and may be NULL).
+ */
+int coopt_kv_cache_write_skipset(const void* k, const void* v, const int64_t* slot_mapping,
+                                 const uint32_t* skip_set, int32_t num_tokens, void* k_cache,
+                                 void* v_cache, float* k_scale, float* v_scale,
+                                 const coopt_shape* shape, void* hip_stream);
+
+/*
  * Single-step grouped-query decode attention over the paged cache
  * (Background Eq. 1; Opt-KV Eq. 6 and Alg. 1 phase 2; Opt-GQA Eq. 7-8 and Alg. 2; Opt-Pa Eq. 9-10
  * and Alg. 3).  For sequence s and query head h, with KV head g = floor(h / (H_q/H_k)):

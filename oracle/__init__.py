@@ -83,26 +83,41 @@ def f16_to_f64(bits: int) -> float:
     return float(_load().orc_f16_to_f64(int(bits) & 0xFFFF))
 
 
-def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, *, H_k, d, B):
+def _skip_bitmap(skip_set, T):
+    """SkipSet of Eq. 5 as the C side takes it: uint32 words, bit i%32 of word i/32 = token i."""
+    if skip_set is None:
+        return None
+    bits = np.zeros((T + 31) // 32, dtype=np.uint32)
+    for i in skip_set:
+        assert 0 <= int(i) < T
+        bits[int(i) >> 5] |= np.uint32(1 << (int(i) & 31))
+    return bits
+
+
+def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, *, H_k, d, B,
+                       skip_set=None):
+    """skip_set: iterable of token indices of this call that are not to be written (Eq. 5)."""
     _chk(k, np.float16, "k"); _chk(v, np.float16, "v"); _chk(slot_mapping, np.int64, "slot_mapping")
     _chk(k_cache, np.uint8, "k_cache"); _chk(v_cache, np.uint8, "v_cache")
     _chk(k_scale, np.float32, "k_scale"); _chk(v_scale, np.float32, "v_scale")
     T = int(slot_mapping.shape[0])
     assert k.size == T * H_k * d and v.size == T * H_k * d
     _chk_dim(d, True)
-    _load().orc_kv_cache_write_fp8(_p(k), _p(v), _p(slot_mapping), ctypes.c_int(T), _p(k_cache),
-                                   _p(v_cache), _p(k_scale), _p(v_scale), ctypes.c_int(H_k),
-                                   ctypes.c_int(d), ctypes.c_int(B))
+    bits = _skip_bitmap(skip_set, T)
+    _load().orc_kv_cache_write_fp8(_p(k), _p(v), _p(slot_mapping), _p(bits), ctypes.c_int(T),
+                                   _p(k_cache), _p(v_cache), _p(k_scale), _p(v_scale),
+                                   ctypes.c_int(H_k), ctypes.c_int(d), ctypes.c_int(B))
 
 
-def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, *, H_k, d, B):
+def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, *, H_k, d, B, skip_set=None):
     _chk(k, np.float16, "k"); _chk(v, np.float16, "v"); _chk(slot_mapping, np.int64, "slot_mapping")
     _chk(k_cache, np.float16, "k_cache"); _chk(v_cache, np.float16, "v_cache")
     T = int(slot_mapping.shape[0])
     assert k.size == T * H_k * d and v.size == T * H_k * d
     _chk_dim(d, False)
-    _load().orc_kv_cache_write_fp16(_p(k), _p(v), _p(slot_mapping), ctypes.c_int(T), _p(k_cache),
-                                    _p(v_cache), ctypes.c_int(H_k), ctypes.c_int(d),
+    bits = _skip_bitmap(skip_set, T)
+    _load().orc_kv_cache_write_fp16(_p(k), _p(v), _p(slot_mapping), _p(bits), ctypes.c_int(T),
+                                    _p(k_cache), _p(v_cache), ctypes.c_int(H_k), ctypes.c_int(d),
                                     ctypes.c_int(B))
 
 

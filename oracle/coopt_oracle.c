@@ -161,15 +161,23 @@ static void quantise_row(const uint16_t *x16, int d, float *scale_out, uint8_t *
     *scale_out = scale;
 }
 
-/* Opt-KV Alg. 1 phase 1 with the E4M3 store: tokens in order, negative slot = skip. */
+/* Membership of token index i in the SkipSet of Eq. 5, given as a bitmap over the call's token
+ * indices (bit i%32 of word i/32); a NULL bitmap is the empty set. */
+static int in_skip_set(const uint32_t *skip_set, int i)
+{
+    return skip_set != NULL && ((skip_set[i >> 5] >> (i & 31)) & 1u);
+}
+
+/* Opt-KV Alg. 1 phase 1 with the E4M3 store: tokens in order; a token is left out if its index
+ * is in the SkipSet (Eq. 5) or its slot is negative. */
 void orc_kv_cache_write_fp8(const uint16_t *k, const uint16_t *v, const int64_t *slot_mapping,
-                            int T, uint8_t *k_cache, uint8_t *v_cache, float *k_scale,
-                            float *v_scale, int H_k, int d, int B)
+                            const uint32_t *skip_set, int T, uint8_t *k_cache, uint8_t *v_cache,
+                            float *k_scale, float *v_scale, int H_k, int d, int B)
 {
     uint8_t *codes = (uint8_t *)malloc((size_t)d);
     for (int i = 0; i < T; i++) {
         int64_t slot = slot_mapping[i];
-        if (slot < 0)
+        if (slot < 0 || in_skip_set(skip_set, i))
             continue;
         int blk = (int)(slot / B);
         int off = (int)(slot % B);
@@ -192,11 +200,12 @@ void orc_kv_cache_write_fp8(const uint16_t *k, const uint16_t *v, const int64_t 
 
 /* Same scatter with the fp16 pattern stored unchanged (the unquantised comparison case). */
 void orc_kv_cache_write_fp16(const uint16_t *k, const uint16_t *v, const int64_t *slot_mapping,
-                             int T, uint16_t *k_cache, uint16_t *v_cache, int H_k, int d, int B)
+                             const uint32_t *skip_set, int T, uint16_t *k_cache, uint16_t *v_cache,
+                             int H_k, int d, int B)
 {
     for (int i = 0; i < T; i++) {
         int64_t slot = slot_mapping[i];
-        if (slot < 0)
+        if (slot < 0 || in_skip_set(skip_set, i))
             continue;
         int blk = (int)(slot / B);
         int off = (int)(slot % B);

@@ -18,7 +18,8 @@ COOPT_KV_FP16 = 0
 COOPT_KV_E4M3 = 1
 
 EXPORTS = [
-    "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_paged_gqa_decode",
+    "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_kv_cache_write_skipset",
+    "coopt_paged_gqa_decode",
     "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
     "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
     "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
@@ -62,6 +63,7 @@ def load_library():
         shp = ctypes.POINTER(Shape)
         lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, i64p, i32, vp, vp, vp, vp, shp, vp]
         lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, i64p, i32, vp, vp, shp, vp]
+        lib.coopt_kv_cache_write_skipset.argtypes = [vp, vp, i64p, vp, i32, vp, vp, vp, vp, shp, vp]
         lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
         lib.coopt_paged_gqa_decode_step.argtypes = [vp, vp, i64p, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                     ctypes.c_size_t, shp, vp]
@@ -111,6 +113,15 @@ def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, s
         _ptr(k), _ptr(v), _ptr(slot_mapping), int(slot_mapping.numel()), _ptr(k_cache),
         _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), ctypes.byref(shape), _stream(stream)),
         "coopt_kv_cache_write_fp8")
+
+
+def kv_cache_write_skipset(k, v, slot_mapping, skip_set, k_cache, v_cache, k_scale, v_scale,
+                           shape: Shape, stream=None) -> None:
+    """skip_set: device uint32 bitmap over the call's token indices, or None."""
+    _check(load_library().coopt_kv_cache_write_skipset(
+        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(skip_set), int(slot_mapping.numel()),
+        _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), ctypes.byref(shape),
+        _stream(stream)), "coopt_kv_cache_write_skipset")
 
 
 def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, shape: Shape, stream=None) -> None:

@@ -88,6 +88,9 @@ def test_null_pointers_and_bad_arguments(lib):
     need2 = lib.coopt_decode_workspace_bytes(ctypes.byref(sh2))
     assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2 - 1), ctypes.byref(sh2), None) == -3
     assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, ctypes.c_void_p(8), ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -3
+    assert lib.coopt_kv_cache_write_skipset(None, one, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -1
+    assert lib.coopt_kv_cache_write_skipset(one, one, one, None, 0, one, one, one, one, ctypes.byref(sh), None) == 0
+    assert lib.coopt_kv_cache_write_skipset(one, one, one, one, 1, one, one, one, one, None, None) == -1
     # fused step: the new rows and a workspace are required
     assert lib.coopt_paged_gqa_decode_step(None, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1
     assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, None, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1

@@ -106,3 +106,36 @@ def test_every_fp16_input_value(oracle_mod):
     oracle_fill(oracle_mod, w, cache=host)
     hip_write(w, devc)
     _compare_caches(w, host, devc, "fp16 sweep")
+
+
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "fp16"])
+def test_explicit_skip_set(oracle_mod, kv_dtype):
+    """Eq. 5 with the SkipSet given as a device bitmap over the call's token indices."""
+    import paper_2602_09323_amd as coopt
+    from gpu_utils import dev, shape_of
+    w = workloads.make_custom("skipset", seed=108, S=4, H_q=10, H_k=2, d=128, B=16, NB=64,
+                              context_lens=[1, 100, 257, 64], kv_dtype=kv_dtype)
+    T = w.total_tokens
+    rng = np.random.default_rng(4)
+    in_set = rng.random(T) < 0.35
+    in_set[[0, 31, 32, 33, T - 1]] = [True, False, True, True, False]
+    slots = w.slots.copy()
+    slots[7] = -1                                   # a negative slot outside the set still skips
+    host, devc = _roundtrip(w)
+    write = oracle_mod.kv_cache_write_fp8 if kv_dtype == "e4m3" else oracle_mod.kv_cache_write_fp16
+    write(w.k_ctx, w.v_ctx, slots, *(host if kv_dtype == "e4m3" else host[:2]), H_k=w.H_k, d=w.d,
+          B=w.B, skip_set=np.nonzero(in_set)[0])
+    bits = np.zeros((T + 31) // 32, dtype=np.uint32)
+    for i in np.nonzero(in_set)[0]:
+        bits[i >> 5] |= np.uint32(1 << (i & 31))
+    coopt.kv_cache_write_skipset(dev(w.k_ctx.view(np.uint16)), dev(w.v_ctx.view(np.uint16)), dev(slots),
+                                 dev(bits), *devc, shape_of(w))
+    torch.cuda.synchronize()
+    _compare_caches(w, host, devc, f"skip set {kv_dtype}")
+    # NULL set = the plain write
+    host2, devc2 = _roundtrip(w)
+    write(w.k_ctx, w.v_ctx, slots, *(host2 if kv_dtype == "e4m3" else host2[:2]), H_k=w.H_k, d=w.d, B=w.B)
+    coopt.kv_cache_write_skipset(dev(w.k_ctx.view(np.uint16)), dev(w.v_ctx.view(np.uint16)), dev(slots),
+                                 None, *devc2, shape_of(w))
+    torch.cuda.synchronize()
+    _compare_caches(w, host2, devc2, f"empty skip set {kv_dtype}")

@@ -110,6 +110,39 @@ def test_skip_rule_and_untouched_slots(oracle_mod):
                 assert np.isnan(k_scale[blk, :, off]).all() and np.isnan(v_scale[blk, :, off]).all()
 
 
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "fp16"])
+def test_explicit_skip_set_is_the_negative_slot_rule(oracle_mod, kv_dtype):
+    """Eq. 5 with the SkipSet spelled out: leaving token indices out through the set gives the same
+    cache, byte for byte, as giving those tokens a negative slot; tokens in neither are written,
+    and a token index outside the set whose slot is negative is still left out."""
+    w = workloads.make_custom("skipset", seed=8, S=3, H_q=4, H_k=2, d=64, B=16, NB=8,
+                              context_lens=[20, 37, 45], kv_dtype=kv_dtype)
+    T = w.total_tokens
+    rng = np.random.default_rng(3)
+    in_set = rng.random(T) < 0.3
+    in_set[[0, 31, 32, 33, 63, 64, T - 1]] = [True, True, False, True, False, True, True]   # word edges
+    neg = np.zeros(T, bool); neg[5] = neg[70] = True; in_set[5] = False
+    by_set = alloc_cache(w, fill_byte=0xA5)
+    by_slot = alloc_cache(w, fill_byte=0xA5)
+    slots_a = w.slots.copy(); slots_a[neg] = -1
+    slots_b = w.slots.copy(); slots_b[in_set | neg] = -7
+    write = oracle_mod.kv_cache_write_fp8 if kv_dtype == "e4m3" else oracle_mod.kv_cache_write_fp16
+    args = lambda c: c if kv_dtype == "e4m3" else c[:2]
+    write(w.k_ctx, w.v_ctx, slots_a, *args(by_set), H_k=w.H_k, d=w.d, B=w.B, skip_set=np.nonzero(in_set)[0])
+    write(w.k_ctx, w.v_ctx, slots_b, *args(by_slot), H_k=w.H_k, d=w.d, B=w.B)
+    for a, b in zip(by_set, by_slot):
+        if a is not None:
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+    # and the set really removed something and kept something
+    full = alloc_cache(w, fill_byte=0xA5)
+    write(w.k_ctx, w.v_ctx, w.slots, *args(full), H_k=w.H_k, d=w.d, B=w.B)
+    assert not np.array_equal(full[0].view(np.uint8), by_set[0].view(np.uint8))
+    assert np.any(by_set[0].view(np.uint8) != 0xA5)
+    empty = alloc_cache(w, fill_byte=0xA5)
+    write(w.k_ctx, w.v_ctx, w.slots, *args(empty), H_k=w.H_k, d=w.d, B=w.B, skip_set=np.arange(T))
+    assert np.all(empty[0].view(np.uint8) == 0xA5) and np.all(empty[1].view(np.uint8) == 0xA5)
+
+
 def test_slot_and_block_indexing_brute_force(oracle_mod):
     """Write tokens one at a time in random order; read back through the block table."""
     w = workloads.make_custom("idx", seed=6, S=3, H_q=6, H_k=3, d=64, B=16, NB=16,
