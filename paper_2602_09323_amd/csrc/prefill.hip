@@ -13,7 +13,8 @@
 //     scales of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
 //     All four then read their operands back with 16-byte LDS loads, conflict-free, and run the
 //     online-softmax update of attn_tile.hpp's arithmetic on each of their tiles.  One barrier
-//     per group; the global loads of group i+2 are in flight while group i is consumed.
+//     per stage of two groups; the global loads of the stage after next are in flight while a
+//     stage is consumed.
 //   * Workgroup ids are dealt to the 8 XCDs round-robin, so the mapping puts all workgroups of a
 //     pair on ONE XCD: the pair's 2 MB of cache are fetched from HBM once and re-read from that
 //     XCD's L2 by the pair's other workgroups.
@@ -39,6 +40,7 @@ struct PrefillArgs {
 };
 
 constexpr int kPrefillWaves = 4;
+constexpr int kPrefillGroupsPerStage = 2;      // two-block groups between two barriers
 
 // Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
 template <int HEAD_DIM>
@@ -132,7 +134,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     constexpr int NL = BlockRegs<HEAD_DIM, KV>::NL;   // 16-byte pieces per lane of a K (or V) tile
     constexpr int NLH = (NL + 1) / 2;                 // V pieces per V wave
     constexpr int NP = NL > 2 * NLH ? NL : 2 * NLH;   // producer registers per wave
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];     // two stages
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];     // two stages of GPS groups
 
     const int lane = threadIdx.x & 63;
     const int wave = wave_uniform((int)(threadIdx.x >> 6));
@@ -203,11 +205,12 @@ prefill_chunk_kernel(const PrefillArgs a)
 
     // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
-    u32x4 pr[NP];
-    floatx4 psc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int GPS = kPrefillGroupsPerStage;
+    u32x4 prs[GPS][NP];
+    floatx4 pscs[GPS];
     const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
     const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
-    auto produce_issue = [&](int p) {
+    auto produce_issue = [&](int p, u32x4 (&pr)[NP], floatx4& psc) {
         const int c = (2 * p) >> 6;
         if (c != cur_chunk) {                              // groups are produced in order
             idv_cur = idv_nxt;
@@ -235,7 +238,7 @@ prefill_chunk_kernel(const PrefillArgs a)
                 psc = loader.load_scales(a.cv.v_scale, wave == 2 ? tA : tB, wave == 2 ? okA : okB);
         }
     };
-    auto produce_store = [&](int p, unsigned char* st) {
+    auto produce_store = [&](int p, unsigned char* st, const u32x4 (&pr)[NP], const floatx4& psc) {
         if (wave < 2) {
             unsigned char* kdst = st + St::kK + wave * (St::kKOps * 1024) + 16 * lane;
 #pragma unroll
@@ -325,18 +328,36 @@ prefill_chunk_kernel(const PrefillArgs a)
         }
     };
 
-    auto stage = [&](int gi) { return lds + (gi & 1) * St::kBytes; };
-    produce_issue(0);
-    produce_store(0, stage(0));
-    if (num_groups > 1) produce_issue(1);
+    // A stage holds GPS consecutive groups; one barrier per stage.
+    const int num_stages = (num_groups + GPS - 1) / GPS;
+    auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
+#pragma unroll
+    for (int sub = 0; sub < GPS; ++sub)
+        if (sub < num_groups) produce_issue(sub, prs[sub], pscs[sub]);
+#pragma unroll
+    for (int sub = 0; sub < GPS; ++sub)
+        if (sub < num_groups) produce_store(sub, slot(0, sub), prs[sub], pscs[sub]);
+#pragma unroll
+    for (int sub = 0; sub < GPS; ++sub)
+        if (GPS + sub < num_groups) produce_issue(GPS + sub, prs[sub], pscs[sub]);
     __syncthreads();
-    for (int gi = 0; gi < num_groups; ++gi) {
-        if (2 * gi * kBlock < my_max) consume(stage(gi), gi);
-        if (gi + 1 < num_groups) {
-            produce_store(gi + 1, stage(gi + 1));
-            if (gi + 2 < num_groups) produce_issue(gi + 2);
+    for (int si = 0; si < num_stages; ++si) {
+#pragma unroll
+        for (int sub = 0; sub < GPS; ++sub) {
+            const int gi = si * GPS + sub;
+            if (gi < num_groups && 2 * gi * kBlock < my_max) consume(slot(si, sub), gi);
         }
-        // group gi+1 is complete in its stage, and nobody still reads group gi's
+#pragma unroll
+        for (int sub = 0; sub < GPS; ++sub) {
+            const int gn = (si + 1) * GPS + sub;
+            if (gn < num_groups) produce_store(gn, slot(si + 1, sub), prs[sub], pscs[sub]);
+        }
+#pragma unroll
+        for (int sub = 0; sub < GPS; ++sub) {
+            const int g2 = (si + 2) * GPS + sub;
+            if (g2 < num_groups) produce_issue(g2, prs[sub], pscs[sub]);
+        }
+        // stage si+1 is complete, and nobody still reads stage si
         __syncthreads();
     }
 
@@ -402,7 +423,8 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     const long long wgs = (long long)((a.num_pairs + 7) / 8) * 8 * a.wgs_per_pair;
     if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     const dim3 grid((unsigned)wgs), block(64 * kPrefillWaves);
-    const size_t lds = 2 * (size_t)(sh->head_dim == 128 ? PrefillStage<128>::kBytes : PrefillStage<64>::kBytes);
+    const size_t lds = 2 * kPrefillGroupsPerStage *
+                       (size_t)(sh->head_dim == 128 ? PrefillStage<128>::kBytes : PrefillStage<64>::kBytes);
     hipStream_t stream = (hipStream_t)hip_stream;
 #define COOPT_PREFILL(D, KV, BIG) \
     hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, NR, BIG>), grid, block, lds, stream, a)
