@@ -69,7 +69,9 @@ struct FlatSchedule {
     __device__ __forceinline__ int cached_len(int s) const
     {
         int t = lens[s];
-        if (new_slots && t > 0 && new_slots[s] >= 0) t -= 1;
+        int64_t slot = -1;
+        if (new_slots) slot = new_slots[s];      // not behind `t > 0`: the two loads overlap
+        if (t > 0 && slot >= 0) t -= 1;
         return t;
     }
 
