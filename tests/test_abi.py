@@ -110,3 +110,17 @@ def test_null_pointers_and_bad_arguments(lib):
         assert coopt.get_decode_plan() == good        # a refused plan changes nothing
     coopt.set_decode_plan(**good)
     assert lib.coopt_set_decode_plan(None) == -1
+
+
+def test_empty_batches_are_accepted_without_launch(lib):
+    """num_seqs = 0 / num_tokens = 0 / no query rows: COOPT_OK before any pointer is looked at."""
+    sh = _shape(num_seqs=0)
+    z = ctypes.c_size_t(0)
+    assert lib.coopt_paged_gqa_decode(None, None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
+    assert lib.coopt_paged_gqa_decode_step(None, None, None, None, None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
+    assert lib.coopt_paged_gqa_decode_split(None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
+    assert lib.coopt_paged_gqa_prefill_chunk(None, None, None, None, None, None, None, None, 0, 0, None, ctypes.byref(sh), None) == 0
+    sh1 = _shape()
+    assert lib.coopt_kv_cache_write_fp8(None, None, None, 0, None, None, None, None, ctypes.byref(sh1), None) == 0
+    assert lib.coopt_kv_cache_write_skipset(None, None, None, None, 0, None, None, None, None, ctypes.byref(sh1), None) == 0
+    assert lib.coopt_paged_gqa_prefill_chunk(None, None, None, None, None, None, None, None, 0, 0, None, ctypes.byref(sh1), None) == 0
