@@ -80,7 +80,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this build has no multi-GPU path "
-                 "(run with --gpus 1; how the path would shard is described in DESIGN.md)")
+                 "(run with --gpus 1; the path shards by sequence or by KV head with no exchange inside attention)")
 
     import torch
     import paper_2602_09323_amd as coopt
