@@ -198,10 +198,10 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- block numbers: 64 per vector load, the chunk in use and the one after it
-    int cur_chunk = 0;
-    int idv_cur = lane < nblk ? bt[lane] : 0;
-    int idv_nxt = 64 + lane < nblk ? bt[64 + lane] : 0;
+    // ---- block numbers come through the scalar unit, one group ahead: a vector load of them
+    // inside the loop would turn the producers' waits on the vector-memory counter into waits for
+    // the tile loads just issued.  Groups are produced in order, p = 0, 1, 2, ...
+    int next_idA = bt[0], next_idB = bt[min(1, nblk - 1)];
 
     // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
@@ -211,15 +211,11 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
     const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
     auto produce_issue = [&](int p, u32x4 (&pr)[NP], floatx4& psc) {
-        const int c = (2 * p) >> 6;
-        if (c != cur_chunk) {                              // groups are produced in order
-            idv_cur = idv_nxt;
-            cur_chunk = c;
-            idv_nxt = 64 * (c + 1) + lane < nblk ? bt[64 * (c + 1) + lane] : 0;
-        }
         const bool okA = 2 * p < nblk, okB = 2 * p + 1 < nblk;
-        const int tA = __builtin_amdgcn_readlane(idv_cur, (2 * p) & 63) * a.H_k + g;
-        const int tB = __builtin_amdgcn_readlane(idv_cur, (2 * p + 1) & 63) * a.H_k + g;
+        const int tA = next_idA * a.H_k + g;
+        const int tB = next_idB * a.H_k + g;
+        next_idA = bt[min(2 * p + 2, nblk - 1)];           // wave-uniform addresses: scalar loads
+        next_idB = bt[min(2 * p + 3, nblk - 1)];
         if (wave < 2) {
             const int tk = wave == 0 ? tA : tB;
             const bool ok = wave == 0 ? okA : okB;
