@@ -5,15 +5,16 @@
 // Query length > 1 makes this a dense contraction, so the matrix cores are used at full width and
 // every cache byte is fetched and converted once per WORKGROUP:
 //   * A score tile has 16 query rows of ONE query head as its columns (column n = chunk row
-//     i0+n).  A wavefront carries NR such tiles, a workgroup of 4 wavefronts 4*NR of them (128 rows
+//     i0+n).  A wavefront carries NR such tiles, a workgroup of 8 wavefronts 8*NR of them (256 rows
 //     at NR = 2), all of the same (sequence, KV head) pair.
 //   * The pair's K/V stream, two 16-token blocks (a group) at a time, through a double-buffered
-//     LDS stage in matrix-core operand order, already converted to fp16: wave 0 brings block A's K,
-//     wave 1 block B's K, waves 2 and 3 the V pieces of both blocks (and zero the V entries and
-//     scales of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
-//     All four then read their operands back with 16-byte LDS loads, conflict-free, and run the
+//     LDS stage in matrix-core operand order, already converted to fp16.  The waves form two
+//     producer teams that take alternate groups; in a team wave 0 brings block A's K, wave 1
+//     block B's K, waves 2 and 3 the V pieces of both blocks (and zero the V entries and scales
+//     of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
+//     All eight then read their operands back with 16-byte LDS loads, conflict-free, and run the
 //     online-softmax update of attn_tile.hpp's arithmetic on each of their tiles.  One barrier
-//     per stage of two groups; the global loads of the stage after next are in flight while a
+//     per stage of four groups; the global loads of the stage after next are in flight while a
 //     stage is consumed.
 //   * Workgroup ids are dealt to the 8 XCDs round-robin, so the mapping puts all workgroups of a
 //     pair on ONE XCD: the pair's 2 MB of cache are fetched from HBM once and re-read from that
@@ -39,8 +40,8 @@ struct PrefillArgs {
     float scale_log2e;
 };
 
-constexpr int kPrefillWaves = 4;
-constexpr int kPrefillGroupsPerStage = 2;      // two-block groups between two barriers
+constexpr int kPrefillWaves = 8;                // two teams of four producer roles
+constexpr int kPrefillGroupsPerStage = 4;      // two-block groups between two barriers
 
 // Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
 template <int HEAD_DIM>
@@ -137,7 +138,10 @@ prefill_chunk_kernel(const PrefillArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];     // two stages of GPS groups
 
     const int lane = threadIdx.x & 63;
-    const int wave = wave_uniform((int)(threadIdx.x >> 6));
+    const int wave_id = wave_uniform((int)(threadIdx.x >> 6));
+    const int wave = wave_id & 3;                      // producer role inside its team
+    const int team = wave_id >> 2;                     // team t produces the groups p with p % kTeams == t
+    constexpr int kTeams = kPrefillWaves / 4;
     const int n = lane & 15, grp = lane >> 4;
     // all workgroups of a (sequence, KV head) pair on one XCD (ids go round-robin over 8 XCDs)
     const int k8 = blockIdx.x >> 3;
@@ -155,7 +159,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int total_tiles = a.G * tiles_per_head;
     const int wg_first_tile = (k8 % a.wgs_per_pair) * (kPrefillWaves * NR);
     if (wg_first_tile >= total_tiles) return;          // the whole workgroup leaves together
-    const int first_tile = wg_first_tile + wave * NR;
+    const int first_tile = wg_first_tile + wave_id * NR;
     const bool active = first_tile < total_tiles;      // a wave without tiles still produces
 
     half8_t qop[NR][HEAD_DIM / 32];
@@ -200,22 +204,23 @@ prefill_chunk_kernel(const PrefillArgs a)
 
     // ---- block numbers come through the scalar unit, one group ahead: a vector load of them
     // inside the loop would turn the producers' waits on the vector-memory counter into waits for
-    // the tile loads just issued.  Groups are produced in order, p = 0, 1, 2, ...
-    int next_idA = bt[0], next_idB = bt[min(1, nblk - 1)];
+    // the tile loads just issued.  A team produces its groups in order, p = team, team + kTeams, ...
+    int next_idA = bt[min(2 * team, nblk - 1)], next_idB = bt[min(2 * team + 1, nblk - 1)];
 
     // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
     constexpr int GPS = kPrefillGroupsPerStage;
-    u32x4 prs[GPS][NP];
-    floatx4 pscs[GPS];
+    static_assert(GPS % kTeams == 0, "every team produces the same number of groups per stage");
+    u32x4 prs[GPS / kTeams][NP];
+    floatx4 pscs[GPS / kTeams];
     const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
     const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
     auto produce_issue = [&](int p, u32x4 (&pr)[NP], floatx4& psc) {
         const bool okA = 2 * p < nblk, okB = 2 * p + 1 < nblk;
         const int tA = next_idA * a.H_k + g;
         const int tB = next_idB * a.H_k + g;
-        next_idA = bt[min(2 * p + 2, nblk - 1)];           // wave-uniform addresses: scalar loads
-        next_idB = bt[min(2 * p + 3, nblk - 1)];
+        next_idA = bt[min(2 * (p + kTeams), nblk - 1)];    // wave-uniform addresses: scalar loads
+        next_idB = bt[min(2 * (p + kTeams) + 1, nblk - 1)];
         if (wave < 2) {
             const int tk = wave == 0 ? tA : tB;
             const bool ok = wave == 0 ? okA : okB;
@@ -327,15 +332,18 @@ prefill_chunk_kernel(const PrefillArgs a)
     // A stage holds GPS consecutive groups; one barrier per stage.
     const int num_stages = (num_groups + GPS - 1) / GPS;
     auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
+    // (sub-group `sub` of a stage belongs to team sub % kTeams; a wave keeps registers for its own)
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub < num_groups) produce_issue(sub, prs[sub], pscs[sub]);
+        if (sub % kTeams == team && sub < num_groups) produce_issue(sub, prs[sub / kTeams], pscs[sub / kTeams]);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub < num_groups) produce_store(sub, slot(0, sub), prs[sub], pscs[sub]);
+        if (sub % kTeams == team && sub < num_groups)
+            produce_store(sub, slot(0, sub), prs[sub / kTeams], pscs[sub / kTeams]);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (GPS + sub < num_groups) produce_issue(GPS + sub, prs[sub], pscs[sub]);
+        if (sub % kTeams == team && GPS + sub < num_groups)
+            produce_issue(GPS + sub, prs[sub / kTeams], pscs[sub / kTeams]);
     __syncthreads();
     for (int si = 0; si < num_stages; ++si) {
 #pragma unroll
@@ -346,12 +354,13 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int gn = (si + 1) * GPS + sub;
-            if (gn < num_groups) produce_store(gn, slot(si + 1, sub), prs[sub], pscs[sub]);
+            if (sub % kTeams == team && gn < num_groups)
+                produce_store(gn, slot(si + 1, sub), prs[sub / kTeams], pscs[sub / kTeams]);
         }
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int g2 = (si + 2) * GPS + sub;
-            if (g2 < num_groups) produce_issue(g2, prs[sub], pscs[sub]);
+            if (sub % kTeams == team && g2 < num_groups) produce_issue(g2, prs[sub / kTeams], pscs[sub / kTeams]);
         }
         // stage si+1 is complete, and nobody still reads stage si
         __syncthreads();
