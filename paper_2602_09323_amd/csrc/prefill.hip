@@ -258,9 +258,11 @@ prefill_chunk_kernel(const PrefillArgs a)
         } else {
             // this lane's 4 tokens of block A start at 32p + 4grp, of block B 16 later
             const int cacheA = t - (32 * p + 4 * grp), cacheB = cacheA - kBlock;
-            uint32_t a0, a1, b0, b1;
-            token_masks<KV>(cacheA, a0, a1);
-            token_masks<KV>(cacheB, b0, b1);
+            uint32_t a0 = 0xffffffffu, a1 = 0xffffffffu, b0 = 0xffffffffu, b1 = 0xffffffffu;
+            if (32 * p + 2 * kBlock > t) {          // wave-uniform: only the cache's last group
+                token_masks<KV>(cacheA, a0, a1);
+                token_masks<KV>(cacheB, b0, b1);
+            }
 #pragma unroll
             for (int jj = 0; jj < NLH; ++jj) {
                 if (jj < vcnt) {
