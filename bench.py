@@ -72,6 +72,10 @@ def main():
     ap.add_argument("--write", choices=["fused", "separate"], default="fused",
                     help="the step's cache write inside the decode launch (coopt_paged_gqa_decode_step) "
                          "or as its own kernel before coopt_paged_gqa_decode (balanced path only)")
+    ap.add_argument("--op", choices=["step", "gather"], default="step",
+                    help="step: the decode / prefill step of the workload (default).  gather: "
+                         "coopt_gather_cached_kv of every sequence's whole context (one launch per "
+                         "sequence; FP8 workloads), reported in GB/s against the HBM peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -108,6 +112,8 @@ def main():
         return
 
     w = workloads.make(args.config)
+    if args.op == "gather":
+        return bench_gather(args, w, coopt, torch, dev)
     if args.config == 4:
         return bench_prefill(args, w, coopt, torch, dev)
     ab = algorithmic_bytes(w)
@@ -370,6 +376,104 @@ def bench_prefill(args, w, coopt, torch, dev):
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_prefill(w, flops)
+    print(json.dumps(result), flush=True)
+
+
+def bench_gather(args, w, coopt, torch, dev):
+    """The dequantising gather over every sequence of the workload: a step = S launches, sequence s
+    reading its t_s cached tokens (codes + scales through the block table) and writing them as
+    contiguous fp16.  Pure data movement, priced against the HBM peak."""
+    e4m3 = w.kv_dtype == "e4m3"
+    es = 1 if e4m3 else 2
+    shape = coopt.Shape(w.S, w.H_q, w.H_k, w.d, w.B, w.NB, w.max_blocks,
+                        coopt.COOPT_KV_E4M3 if e4m3 else coopt.COOPT_KV_FP16,
+                        float(np.float32(w.softmax_scale)))
+    pool_bytes = w.NB * w.H_k * w.B * (2 * w.d * es + (8 if e4m3 else 0))
+    layers = args.layers or max(2, min(8, int(8e9 // pool_bytes)))
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    k_all, v_all = to_dev(w.k_ctx.view(np.uint16)), to_dev(w.v_ctx.view(np.uint16))
+    slots, bt = to_dev(w.slots), to_dev(w.block_tables)
+    pools = []
+    for _ in range(layers):
+        kc = torch.zeros((w.NB, w.H_k, w.B * w.d * es), dtype=torch.uint8, device=dev)
+        vc = torch.zeros_like(kc)
+        ks = torch.zeros((w.NB, w.H_k, w.B), dtype=torch.float32, device=dev) if e4m3 else None
+        vs = torch.zeros_like(ks) if e4m3 else None
+        if e4m3:
+            coopt.kv_cache_write_fp8(k_all, v_all, slots, kc, vc, ks, vs, shape)
+        else:
+            coopt.kv_cache_write_fp16(k_all, v_all, slots, kc, vc, shape)
+        pools.append((kc, vc, ks, vs))
+    lens = [int(t) for t in w.context_lens]
+    outs = [(torch.empty((t, w.H_k, w.d), dtype=torch.float16, device=dev),
+             torch.empty((t, w.H_k, w.d), dtype=torch.float16, device=dev)) for t in lens]
+    torch.cuda.synchronize()
+
+    def step(i):
+        pool = pools[i % layers]
+        for s_, t in enumerate(lens):
+            coopt.gather_cached_kv(*pool, bt, s_, 0, t, outs[s_][0], outs[s_][1], shape)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    steps = min(args.steps, 200)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    step_ms = e0.elapsed_time(e1) / steps
+    # per (token, KV head): K and V codes, their two scales, and the two fp16 rows written
+    per_row = 2 * w.d * es + (8 if e4m3 else 0) + 2 * 2 * w.d
+    total = float(sum(lens)) * w.H_k * per_row + sum((t + w.B - 1) // w.B for t in lens) * 4.0
+    gbps = total / step_ms / 1e6
+    result = {
+        "metric": "dequantising gather of the paged cache (gather_cached_kv): GB/s per step",
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8_e4m3 -> f16" if e4m3 else "f16", "data": "synthetic",
+        "config": {"workload": w.name, "num_seqs": w.S, "kv_heads": w.H_k, "head_dim": w.d,
+                   "block_size": w.B, "tokens": sum(lens), "kv_pools_rotated": layers,
+                   "step": "coopt_gather_cached_kv of tokens [0, t_s) for each of the S sequences",
+                   "launch": "eager, back to back on one stream"},
+        "wall_ms_timed_region": round(wall_ms, 2),
+        "roofline": {"bound": "hbm", "kernel": "gather_cached_kv_kernel (coopt_gather_cached_kv)",
+                     "achieved": round(gbps, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": round(total / len(lens), 1),
+                     "launch_us_mean": round(step_ms * 1e3 / len(lens), 2),
+                     "note": "launch duration = event time of the step / launches (includes the "
+                             "gap between dependent launches)"},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        dt = np.uint8 if e4m3 else np.float16
+        kc = np.zeros((w.NB, w.H_k, w.B * w.d), dtype=dt)
+        vc = np.zeros_like(kc)
+        ks = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32) if e4m3 else None
+        vs = np.zeros_like(ks) if e4m3 else None
+        idx = np.arange(int(w.seq_start[1]))
+        rows = (np.ascontiguousarray(w.k_ctx[idx]), np.ascontiguousarray(w.v_ctx[idx]),
+                np.ascontiguousarray(w.slots[idx]))
+        if e4m3:
+            oracle.kv_cache_write_fp8(*rows, kc, vc, ks, vs, H_k=w.H_k, d=w.d, B=w.B)
+        else:
+            oracle.kv_cache_write_fp16(*rows, kc, vc, H_k=w.H_k, d=w.d, B=w.B)
+        cache = (kc, vc, ks, vs)
+        t0 = time.perf_counter()
+        oracle.gather_cached_kv(*cache, w.block_tables, 0, 0, lens[0], H_k=w.H_k, d=w.d, B=w.B)
+        sec = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(lens[0] * w.H_k * per_row / sec / 1e9, 3), "unit": "GB/s",
+                                  "cores": 1, "kind": "oracle", "seconds": round(sec, 3),
+                                  "sample": f"sequence 0 ({lens[0]} of {sum(lens)} tokens), all KV heads"}
     print(json.dumps(result), flush=True)
 
 

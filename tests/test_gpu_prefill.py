@@ -67,18 +67,21 @@ def test_chunked_prefill_full_size_sampled_rows(oracle_mod):
 
 
 def test_gather_cached_kv(oracle_mod):
+    """Bit-exact: the device rounds code * scale to fp16 once, like the oracle's exact product."""
     for kv_dtype in ("e4m3", "fp16"):
-        w = workloads.make_custom("ga", seed=52, S=2, H_q=4, H_k=2, d=128, B=16, NB=16,
-                                  context_lens=[70, 25], kv_dtype=kv_dtype)
-        cache = oracle_fill(oracle_mod, w)
-        kref, vref = oracle_mod.gather_cached_kv(*cache, w.block_tables, 0, 3, 61, H_k=2, d=128, B=16)
-        k_out = torch.zeros((58, 2, 128), dtype=torch.float16, device="cuda")
-        v_out = torch.zeros_like(k_out)
-        coopt.gather_cached_kv(*cache_to_dev(cache), dev(w.block_tables), 0, 3, 61, k_out, v_out, shape_of(w))
-        torch.cuda.synchronize()
-        for got, ref in ((k_out, kref), (v_out, vref)):
-            got = got.cpu().numpy().astype(np.float64)
-            want = ref.astype(np.float16).astype(np.float64)       # fp16 output rounding
-            ulp = np.maximum(np.abs(want) * 2.0 ** -10, 2.0 ** -24)
-            assert np.all(np.abs(got - want) <= ulp)               # product rounded twice on device
-            assert np.mean(got == want) > 0.99
+        for d, H_k in ((128, 2), (64, 3)):
+            w = workloads.make_custom("ga", seed=52 + d, S=2, H_q=2 * H_k, H_k=H_k, d=d, B=16, NB=24,
+                                      context_lens=[150, 25], kv_dtype=kv_dtype)
+            cache = oracle_fill(oracle_mod, w)
+            dcache = cache_to_dev(cache)
+            for seq, lo, hi in ((0, 3, 61), (0, 0, 150), (0, 16, 144), (0, 149, 150), (1, 7, 25), (1, 0, 16)):
+                kref, vref = oracle_mod.gather_cached_kv(*cache, w.block_tables, seq, lo, hi, H_k=H_k, d=d, B=16)
+                k_out = torch.full((hi - lo + 2, H_k, d), 7.0, dtype=torch.float16, device="cuda")
+                v_out = torch.full_like(k_out, 7.0)
+                coopt.gather_cached_kv(*dcache, dev(w.block_tables), seq, lo, hi, k_out[1:-1], v_out[1:-1], shape_of(w))
+                torch.cuda.synchronize()
+                for got, ref in ((k_out, kref), (v_out, vref)):
+                    got = got.cpu().numpy()
+                    assert np.all(got[0] == 7.0) and np.all(got[-1] == 7.0)      # nothing outside the range
+                    want = ref.astype(np.float16)                                  # one rounding of the exact product
+                    assert np.array_equal(got[1:-1].view(np.uint16), want.view(np.uint16)), (kv_dtype, d, seq, lo, hi)
