@@ -72,10 +72,11 @@ def main():
     ap.add_argument("--write", choices=["fused", "separate"], default="fused",
                     help="the step's cache write inside the decode launch (coopt_paged_gqa_decode_step) "
                          "or as its own kernel before coopt_paged_gqa_decode (balanced path only)")
-    ap.add_argument("--op", choices=["step", "gather"], default="step",
+    ap.add_argument("--op", choices=["step", "gather", "stream-read"], default="step",
                     help="step: the decode / prefill step of the workload (default).  gather: "
                          "coopt_gather_cached_kv of every sequence's whole context (one launch per "
-                         "sequence; FP8 workloads), reported in GB/s against the HBM peak")
+                         "sequence), reported in GB/s against the HBM peak.  stream-read: the "
+                         "read-only streaming probe over 2 GiB, every launch shape it tries")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -111,6 +112,9 @@ def main():
         print(json.dumps({"copy_calibration_bytes": src.numel(), "copies": 10}))
         return
 
+    if args.op == "stream-read":
+        print(json.dumps(stream_read_ceiling(coopt, torch, dev, detail=True)), flush=True)
+        return
     w = workloads.make(args.config)
     if args.op == "gather":
         return bench_gather(args, w, coopt, torch, dev)
@@ -281,6 +285,7 @@ def main():
         if pmc and not args.plan and not partitioned:
             traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
         achieved = alg / (kern_us * 1e-6) / 1e9
+        stream = stream_read_ceiling(coopt, torch, dev)
         result["roofline"] = {"bound": "hbm",
                               "kernel": "paged_decode_kernel (coopt_paged_gqa_decode_partitioned)"
                               if partitioned else "flat_stream_kernel (coopt_paged_gqa_decode_split)",
@@ -289,12 +294,39 @@ def main():
                               "algorithmic_bytes_per_launch": int(alg),
                               "kernel_us_mean": round(kern_us, 3),
                               "launch_floor_us": round(floor_us, 3),
+                              "stream_read_gbs": stream["gbs"],
+                              "frac_of_stream_read": round(achieved / stream["gbs"], 4),
                               "timing": "HIP events around back-to-back launches on the launch "
                                         "stream; includes the inter-launch gap (launch_floor_us), "
                                         "which a kernel trace's begin-to-end duration does not"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, ab)
     print(json.dumps(result), flush=True)
+
+
+def stream_read_ceiling(coopt, torch, dev, detail=False):
+    """GB/s of coopt_stream_read_probe (a kernel that only reads, 16-byte streaming loads) over a
+    2 GiB buffer, far beyond the memory-side cache: the best of a few launch shapes, 10 launches
+    each between two events.  What this GPU delivers when nothing but the loads is in the way."""
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    shapes = {}
+    for wgs in (2048, 4096, 8192, 16384):
+        for _ in range(3):
+            coopt.stream_read_probe(buf, wgs, sink)
+        e0.record()
+        for _ in range(10):
+            coopt.stream_read_probe(buf, wgs, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        shapes[wgs] = round(buf.numel() / (e0.elapsed_time(e1) / 10) / 1e6, 1)
+    del buf
+    best = max(shapes, key=shapes.get)
+    out = {"gbs": shapes[best], "workgroups": best, "bytes": 2 << 30}
+    if detail:
+        out["gbs_by_workgroups"] = shapes
+    return out
 
 
 def bench_prefill(args, w, coopt, torch, dev):

@@ -267,6 +267,17 @@ int coopt_gather_cached_kv(const void* k_cache, const void* v_cache, const float
                            int32_t tok_begin, int32_t tok_end, void* k_out, void* v_out,
                            const coopt_shape* shape, void* hip_stream);
 
+/*
+ * Measurement aid (no part of the paper's method): reads `bytes` of device memory at `buf`
+ * (16-byte aligned) once with 16-byte streaming loads from `workgroups` workgroups of 256 lanes
+ * and writes nothing (one word of `sink`, device memory of at least 4 bytes, only if the XOR of
+ * the data hits an arbitrary constant).  Timed by the caller, it gives the read rate this GPU
+ * sustains for a kernel with no other work: the figure the decode kernels' bandwidth is quoted
+ * beside.  COOPT_ERR_SHAPE for workgroups outside [1, 2^20] or a misaligned buffer.
+ */
+int coopt_stream_read_probe(const void* buf, size_t bytes, int32_t workgroups, void* sink,
+                            void* hip_stream);
+
 /* Static, human-readable text for a coopt_status value. */
 const char* coopt_status_string(int status);
 

@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     COOPT_KV_E4M3, COOPT_KV_FP16, CooptError, DecodePlan, Shape, decode_workspace_bytes, gather_cached_kv,
     get_decode_plan,
     kv_cache_write_fp16, kv_cache_write_fp8, kv_cache_write_skipset, lib_path, load_library, paged_gqa_decode,
-    paged_gqa_decode_merge, paged_gqa_decode_partitioned, paged_gqa_decode_split,
+    paged_gqa_decode_merge, paged_gqa_decode_partitioned, paged_gqa_decode_split, stream_read_probe,
     paged_gqa_decode_step,
     paged_gqa_prefill_chunk, paged_gqa_reduce, set_decode_plan,
     status_string)

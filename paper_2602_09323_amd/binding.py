@@ -23,7 +23,7 @@ EXPORTS = [
     "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
     "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
     "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
-    "coopt_status_string",
+    "coopt_stream_read_probe", "coopt_status_string",
 ]
 
 
@@ -78,6 +78,7 @@ def load_library():
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_paged_gqa_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_gather_cached_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, shp, vp]
+        lib.coopt_stream_read_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, vp]
         lib.coopt_status_string.argtypes = [ctypes.c_int]
         lib.coopt_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -209,6 +210,13 @@ def paged_gqa_prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables,
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
         _ptr(context_lens), _ptr(query_start), int(num_query_rows), int(max_chunk_len), _ptr(out),
         ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_prefill_chunk")
+
+
+def stream_read_probe(buf, workgroups: int, sink, stream=None) -> None:
+    """One streaming read of the whole tensor ``buf`` (measurement aid)."""
+    _check(load_library().coopt_stream_read_probe(
+        _ptr(buf), buf.numel() * buf.element_size(), int(workgroups), _ptr(sink), _stream(stream)),
+        "coopt_stream_read_probe")
 
 
 def gather_cached_kv(k_cache, v_cache, k_scale, v_scale, block_tables, seq: int, tok_begin: int,

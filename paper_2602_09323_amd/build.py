@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcoopt_attn.so")
-SOURCES = ["kv_write.hip", "decode.hip", "decode_flat.hip", "prefill.hip", "gather.hip"]
+SOURCES = ["kv_write.hip", "decode.hip", "decode_flat.hip", "prefill.hip", "gather.hip", "probe.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("common.hpp", "attn_tile.hpp", "kv_quant.hpp",
                                           "decode_internal.hpp")] + [
     os.path.join(ROOT, "include", "coopt_attn.h")]

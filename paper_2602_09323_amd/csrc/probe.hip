@@ -1,0 +1,44 @@
+// Measurement aid, not part of the method: a read-only streaming kernel that gives the rate at
+// which this GPU delivers HBM bytes to a kernel that does nothing else.  The decode kernels'
+// bandwidth is quoted against the nominal HBM peak and, beside it, against this figure.
+#include "common.hpp"
+
+namespace coopt {
+
+typedef unsigned int pu32x4 __attribute__((ext_vector_type(4)));
+
+// Grid-stride over 16-byte words, 8 non-temporal loads in flight per lane.  Nothing is written
+// unless the XOR of everything a lane read equals an arbitrary constant (so the loads stay).
+__global__ void __launch_bounds__(256)
+stream_read_kernel(const pu32x4* __restrict__ p, size_t n16, uint32_t* __restrict__ sink)
+{
+    constexpr int U = 8;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    pu32x4 a = {0u, 0u, 0u, 0u};
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        pu32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = __builtin_nontemporal_load(p + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) a ^= x[u];
+    }
+    for (; i < n16; i += stride) a ^= __builtin_nontemporal_load(p + i);
+    if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9e3779b9u) sink[0] = 1u;
+}
+
+}  // namespace coopt
+
+using namespace coopt;
+
+extern "C" int coopt_stream_read_probe(const void* buf, size_t bytes, int32_t workgroups, void* sink,
+                                       void* hip_stream)
+{
+    if (workgroups <= 0 || workgroups > (1 << 20)) return COOPT_ERR_SHAPE;
+    if (bytes < 16) return COOPT_OK;
+    if (!buf || !sink) return COOPT_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(buf) & 15) != 0) return COOPT_ERR_SHAPE;
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)workgroups), dim3(256), 0,
+                       (hipStream_t)hip_stream, (const pu32x4*)buf, bytes / 16, (uint32_t*)sink);
+    return launch_status();
+}

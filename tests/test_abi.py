@@ -101,6 +101,13 @@ def test_null_pointers_and_bad_arguments(lib):
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, None, one, one, 8, ctypes.byref(sh), None) == -1
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 5, 0, 4, one, one, ctypes.byref(sh), None) == -2
     assert lib.coopt_gather_cached_kv(one, one, one, one, one, 0, 0, 999, one, one, ctypes.byref(sh), None) == -2
+    # the streaming-read probe: launch shape and alignment are checked before anything else
+    assert lib.coopt_stream_read_probe(one, ctypes.c_size_t(1 << 20), 0, one, None) == -2
+    assert lib.coopt_stream_read_probe(one, ctypes.c_size_t(1 << 20), (1 << 20) + 1, one, None) == -2
+    assert lib.coopt_stream_read_probe(ctypes.c_void_p(24), ctypes.c_size_t(1 << 20), 64, one, None) == -2
+    assert lib.coopt_stream_read_probe(None, ctypes.c_size_t(1 << 20), 64, one, None) == -1
+    assert lib.coopt_stream_read_probe(one, ctypes.c_size_t(1 << 20), 64, None, None) == -1
+    assert lib.coopt_stream_read_probe(None, ctypes.c_size_t(0), 64, None, None) == 0
     good = dict(coopt.get_decode_plan())
     for bad in (dict(tokens_per_group=100), dict(tokens_per_group=0), dict(waves_per_group=3),
                 dict(pipeline_depth=4), dict(pipeline_depth=0), dict(grid_waves=0),
