@@ -72,6 +72,11 @@ def main():
     ap.add_argument("--write", choices=["fused", "separate"], default="fused",
                     help="the step's cache write inside the decode launch (coopt_paged_gqa_decode_step) "
                          "or as its own kernel before coopt_paged_gqa_decode (balanced path only)")
+    ap.add_argument("--schedule", choices=["prepared", "live"], default="prepared",
+                    help="balanced path: 'prepared' derives the decode schedule once per rotation "
+                         "over the KV pools (coopt_decode_schedule_prepare, inside the timed region: "
+                         "the layers of one decoding step share block tables and lengths) and runs "
+                         "the layers from it; 'live' derives it inside every launch")
     ap.add_argument("--op", choices=["step", "gather", "stream-read"], default="step",
                     help="step: the decode / prefill step of the workload (default).  gather: "
                          "coopt_gather_cached_kv of every sequence's whole context (one launch per "
@@ -173,9 +178,26 @@ def main():
             coopt.paged_gqa_reduce(tmp_out, max_logits, exp_sums, lens, P, max_parts, out, shape)
 
     fused = args.write == "fused" and not partitioned
+    prepared = args.schedule == "prepared" and not partitioned
+    if prepared:
+        sched = torch.zeros(coopt.decode_schedule_bytes(shape), dtype=torch.uint8, device=dev)
+        sched_split = torch.zeros_like(sched)            # plain-decode schedule for the kernel-alone timing
+        coopt.decode_schedule_prepare(bt, lens, None, sched_split, shape)
 
     def step(i):
         kc, vc, ks, vs = pools[i % layers]
+        if prepared:
+            if i % layers == 0:                          # one decoding step of the model begins
+                coopt.decode_schedule_prepare(bt, lens, s_new if fused else None, sched, shape)
+            if not fused:
+                if e4m3:
+                    coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
+                else:
+                    coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
+            coopt.paged_gqa_decode_scheduled(k_new if fused else None, v_new if fused else None,
+                                             s_new if fused else None, q, kc, vc, ks, vs, lens, out,
+                                             ws, sched, shape)
+            return
         if fused:
             coopt.paged_gqa_decode_step(k_new, v_new, s_new, q, kc, vc, ks, vs, bt, lens, out, ws, shape)
             return
@@ -240,7 +262,11 @@ def main():
         if partitioned:
             return attend(i, reduce=False)
         kc, vc, ks, vs = pools[i % layers]
-        coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape)
+        if prepared:
+            coopt.paged_gqa_decode_scheduled(None, None, None, q, kc, vc, ks, vs, lens, None, ws,
+                                             sched_split, shape)
+        else:
+            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape)
     kern_us = timed(kern, args.steps) * 1e3
 
     # the same kernel on empty contexts: what one launch costs before any byte moves (the gap
@@ -252,8 +278,14 @@ def main():
         if partitioned:
             coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens_zero, P, tmp_out,
                                                max_logits, exp_sums, max_parts, shape)
+        elif prepared:
+            coopt.paged_gqa_decode_scheduled(None, None, None, q, kc, vc, ks, vs, lens_zero, None, ws,
+                                             sched_empty, shape)
         else:
             coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape)
+    if prepared:
+        sched_empty = torch.zeros_like(sched)
+        coopt.decode_schedule_prepare(bt, lens_zero, None, sched_empty, shape)
     floor_us = timed(kern_empty, min(args.steps, 200)) * 1e3
 
     kv_gbs = ab["kv"] / (step_ms * 1e-3) / 1e9
@@ -272,6 +304,9 @@ def main():
                             "one layer" % P) if partitioned else
                            ("paged_gqa_decode_step (cache write fused into the decode launch), one layer"
                             if fused else "kv_cache_write + paged_gqa_decode, one layer"),
+                   "schedule": ("prepared once per %d steps (one per decoding step of a %d-layer model), "
+                                "inside the timed region" % (layers, layers)) if prepared else
+                               ("fixed partitions" if partitioned else "derived inside every launch"),
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),
@@ -288,7 +323,8 @@ def main():
         stream = stream_read_ceiling(coopt, torch, dev)
         result["roofline"] = {"bound": "hbm",
                               "kernel": "paged_decode_kernel (coopt_paged_gqa_decode_partitioned)"
-                              if partitioned else "flat_stream_kernel (coopt_paged_gqa_decode_split)",
+                              if partitioned else ("flat_stream_prepared_kernel (coopt_paged_gqa_decode_scheduled)"
+                                                   if prepared else "flat_stream_kernel (coopt_paged_gqa_decode_split)"),
                               "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                               "algorithmic_bytes_per_launch": int(alg),

@@ -174,6 +174,45 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
                                 float* v_scale, const int32_t* block_tables,
                                 const int32_t* context_lens, void* out, void* workspace,
                                 size_t workspace_bytes, const coopt_shape* shape, void* hip_stream);
+/*
+ * The same decode with its schedule prepared ahead.  Block tables, context lengths and the slots of
+ * the new tokens are the same for every layer of a model during one decoding step, so the schedule
+ * that coopt_paged_gqa_decode derives inside every launch (which workgroup reads which cache tiles
+ * of Eq. 9, where each (sequence, KV head) pair's partial results go) can be derived once per step:
+ * coopt_decode_schedule_prepare writes it to device memory, and coopt_paged_gqa_decode_scheduled
+ * runs any number of layers from it.  A scheduled launch reaches its first cache load one memory
+ * round trip after it starts, without the schedule arithmetic and the block-table read.
+ *
+ *   schedule      device, coopt_decode_schedule_bytes(shape) bytes, 16-byte aligned, owned by the
+ *                 caller; opaque.  Valid for the shape, the decode plan and the mode (plain decode
+ *                 or fused step) it was prepared with, and for as long as block_tables,
+ *                 context_lens and slot_mapping keep their contents.
+ *   prepare:  slot_mapping NULL = schedule for plain decode (attention over context_lens tokens);
+ *             non-NULL = schedule for the fused step (as coopt_paged_gqa_decode_step: sequences
+ *             with a non-negative slot append their last token in the same launch).
+ *   scheduled decode:  k, v, slot_mapping all NULL = plain decode, all non-NULL = fused step
+ *             (COOPT_ERR_NULL if mixed); the other arguments as in coopt_paged_gqa_decode_step,
+ *             without block_tables.  out NULL = stop after the partial results (the workspace then
+ *             holds what coopt_paged_gqa_decode_split leaves).
+ * A schedule prepared for another shape, plan or mode is recognised on the device by a tag: such a
+ * launch reads and writes nothing except word 1 of the schedule, which it sets to 1 (prepare
+ * resets it to 0), and `out` keeps its old contents.  A schedule whose tables or lengths have
+ * changed since it was prepared is NOT recognised: prepare again.  Host-side errors as for
+ * coopt_paged_gqa_decode_step, COOPT_ERR_WORKSPACE also for a schedule buffer that is too small or
+ * misaligned, COOPT_ERR_SHAPE (bytes: 0) where a share or a pair's partial count would not fit the
+ * record fields (more than 65 535 partials per pair).
+ */
+size_t coopt_decode_schedule_bytes(const coopt_shape* shape);
+int coopt_decode_schedule_prepare(const int32_t* block_tables, const int32_t* context_lens,
+                                  const int64_t* slot_mapping, void* schedule, size_t schedule_bytes,
+                                  const coopt_shape* shape, void* hip_stream);
+int coopt_paged_gqa_decode_scheduled(const void* k, const void* v, const int64_t* slot_mapping,
+                                     const void* q, void* k_cache, void* v_cache, float* k_scale,
+                                     float* v_scale, const int32_t* context_lens, void* out,
+                                     void* workspace, size_t workspace_bytes, const void* schedule,
+                                     size_t schedule_bytes, const coopt_shape* shape,
+                                     void* hip_stream);
+
 
 /* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under the current decode plan
  * (0 if the shape is unsupported). */

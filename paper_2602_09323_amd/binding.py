@@ -23,6 +23,7 @@ EXPORTS = [
     "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
     "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
     "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
+    "coopt_decode_schedule_bytes", "coopt_decode_schedule_prepare", "coopt_paged_gqa_decode_scheduled",
     "coopt_stream_read_probe", "coopt_status_string",
 ]
 
@@ -78,11 +79,16 @@ def load_library():
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_paged_gqa_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_gather_cached_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, shp, vp]
+        lib.coopt_decode_schedule_bytes.argtypes = [shp]
+        lib.coopt_decode_schedule_bytes.restype = ctypes.c_size_t
+        lib.coopt_decode_schedule_prepare.argtypes = [vp, vp, i64p, vp, ctypes.c_size_t, shp, vp]
+        lib.coopt_paged_gqa_decode_scheduled.argtypes = [vp, vp, i64p, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                         ctypes.c_size_t, vp, ctypes.c_size_t, shp, vp]
         lib.coopt_stream_read_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, vp]
         lib.coopt_status_string.argtypes = [ctypes.c_int]
         lib.coopt_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name not in ("coopt_decode_workspace_bytes", "coopt_status_string",
+            if name not in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes", "coopt_status_string",
                             "coopt_get_decode_plan"):
                 getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -210,6 +216,31 @@ def paged_gqa_prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables,
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
         _ptr(context_lens), _ptr(query_start), int(num_query_rows), int(max_chunk_len), _ptr(out),
         ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_prefill_chunk")
+
+
+def decode_schedule_bytes(shape: Shape) -> int:
+    return int(load_library().coopt_decode_schedule_bytes(ctypes.byref(shape)))
+
+
+def decode_schedule_prepare(block_tables, context_lens, slot_mapping, schedule, shape: Shape,
+                            stream=None) -> None:
+    """Write the decode schedule (``slot_mapping`` None: plain decode; else the fused step)."""
+    _check(load_library().coopt_decode_schedule_prepare(
+        _ptr(block_tables), _ptr(context_lens), _ptr(slot_mapping), _ptr(schedule),
+        schedule.numel() * schedule.element_size(), ctypes.byref(shape), _stream(stream)),
+        "coopt_decode_schedule_prepare")
+
+
+def paged_gqa_decode_scheduled(k, v, slot_mapping, q, k_cache, v_cache, k_scale, v_scale, context_lens,
+                               out, workspace, schedule, shape: Shape, stream=None) -> None:
+    """Decode (k, v, slot_mapping None) or fused step from a prepared schedule; ``out`` None stops
+    after the partial results."""
+    _check(load_library().coopt_paged_gqa_decode_scheduled(
+        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
+        _ptr(v_scale), _ptr(context_lens), _ptr(out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _ptr(schedule),
+        schedule.numel() * schedule.element_size(), ctypes.byref(shape), _stream(stream)),
+        "coopt_paged_gqa_decode_scheduled")
 
 
 def stream_read_probe(buf, workgroups: int, sink, stream=None) -> None:

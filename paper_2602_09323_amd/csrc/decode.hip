@@ -432,6 +432,59 @@ extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
     return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
 }
 
+extern "C" size_t coopt_decode_schedule_bytes(const coopt_shape* sh)
+{
+    if (check_shape(sh) != COOPT_OK) return 0;
+    return flat_schedule_bytes(sh, flat_plan());
+}
+
+extern "C" int coopt_decode_schedule_prepare(const int32_t* block_tables,
+                                             const int32_t* context_lens,
+                                             const int64_t* slot_mapping, void* schedule,
+                                             size_t schedule_bytes, const coopt_shape* sh,
+                                             void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    if (!block_tables || !context_lens || !schedule) return COOPT_ERR_NULL;
+    const size_t need = flat_schedule_bytes(sh, flat_plan());
+    if (need == 0) return COOPT_ERR_SHAPE;
+    if (schedule_bytes < need || ((uintptr_t)schedule & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    return launch_flat_prepare(block_tables, context_lens, slot_mapping, schedule, sh, flat_plan(),
+                               (hipStream_t)hip_stream);
+}
+
+extern "C" int coopt_paged_gqa_decode_scheduled(const void* k, const void* v,
+                                                const int64_t* slot_mapping, const void* q,
+                                                void* k_cache, void* v_cache, float* k_scale,
+                                                float* v_scale, const int32_t* context_lens,
+                                                void* out, void* workspace, size_t workspace_bytes,
+                                                const void* schedule, size_t schedule_bytes,
+                                                const coopt_shape* sh, void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    const bool fused = k || v || slot_mapping;
+    if (fused && (!k || !v || !slot_mapping)) return COOPT_ERR_NULL;
+    // no block table here: the schedule's records name the tiles
+    st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, context_lens, context_lens, sh);
+    if (st != COOPT_OK) return st;
+    if (!workspace || !schedule) return COOPT_ERR_NULL;
+    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    const size_t need = flat_schedule_bytes(sh, flat_plan());
+    if (need == 0) return COOPT_ERR_SHAPE;
+    if (schedule_bytes < need || ((uintptr_t)schedule & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const FlatAppend append{k, v, slot_mapping};
+    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, nullptr, context_lens, workspace,
+                           sh, flat_plan(), stream, fused ? &append : nullptr, schedule);
+    if (st != COOPT_OK || !out) return st;
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream, schedule, fused);
+}
+
 extern "C" int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
                                             const float* k_scale, const float* v_scale,
                                             const int32_t* block_tables,

@@ -187,6 +187,13 @@ struct FlatArgs {
     uint8_t* v_cache_w;
     float* k_scale_w;
     float* v_scale_w;
+    // prepared schedule (see PreparedSource): read by the prepared kernels, written by the
+    // prepare kernel; offsets and the region stride in 32-bit words
+    const uint32_t* sched;
+    uint32_t* sched_w;
+    uint32_t sched_tag;
+    int32_t sched_regions;
+    int32_t sched_stride;
 };
 
 // How the flattened groups are cut into contiguous shares: `nwg` workgroups, the first `r` with
@@ -274,9 +281,24 @@ __device__ __forceinline__ void stage_q_operand(unsigned char* stage, const half
 // values it has just quantised -- the attention workgroups of the same launch read only the tokens
 // that were in the cache before, so nothing in the launch waits for anything else.  It also leaves
 // the pair's partial count (the attention workgroups' partials plus this one).
+// Partials the attention workgroups write for (sequence, KV head) pair `pair`, from the schedule.
+__device__ __forceinline__ int attention_partials_of(const FlatArgs& a, const FlatSchedule& sched,
+                                                     const FlatCut& cut, int ctotal, int pair)
+{
+    const int seq = pair / a.H_k;
+    const int g = pair - seq * a.H_k;
+    const int ng = groups_of(sched.cached_len(seq));
+    if (ng <= 0 || ctotal <= 0) return 0;
+    const int pair_first = sched.cost_first_of(seq) + g * (ng + a.pair_extra) + a.pair_extra;
+    return cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+}
+
+// `count` = partials of the pair that come from the attention workgroups.  With `total` >= 0 (a
+// prepared schedule, whose count includes this token's partial) it is derived from that instead
+// and the pair's count is not written again.
 template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void append_and_attend(const FlatArgs& a, const FlatSchedule& sched,
-                                                  const FlatCut& cut, int ctotal, int pair, int lane)
+__device__ __forceinline__ void append_and_attend(const FlatArgs& a, int pair, int lane, int count,
+                                                  int total)
 {
     constexpr int E = HEAD_DIM / 64;
     const int seq = pair / a.H_k;
@@ -284,15 +306,9 @@ __device__ __forceinline__ void append_and_attend(const FlatArgs& a, const FlatS
     if (seq >= a.num_seqs) return;
     const int64_t slot = a.new_slots[seq];
     const bool appends = slot >= 0 && a.context_lens[seq] > 0;
-    // partials the attention workgroups write for this pair
-    const int t_cached = sched.cached_len(seq);
-    const int ng = groups_of(t_cached);
-    int count = 0;
-    if (ng > 0 && ctotal > 0) {
-        const int pair_first = sched.cost_first_of(seq) + g * (ng + a.pair_extra) + a.pair_extra;
-        count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
-    }
-    if (lane == 0) a.counts[pair] = count + (appends ? 1 : 0);
+    if (total >= 0) count = total - (appends ? 1 : 0);
+    else if (lane == 0) a.counts[pair] = count + (appends ? 1 : 0);
+    count = min(max(count, 0), a.max_slots - 1);                // whatever the schedule says, stay inside
     if (!appends) return;                                       // Eq. 5: filtered token
 
     const int64_t blk = slot / kBlock;
@@ -343,14 +359,170 @@ __device__ __forceinline__ void append_and_attend(const FlatArgs& a, const FlatS
     }
 }
 
-// One wave per workgroup; the wave's share is ONE stream of groups that runs across the
-// boundaries between (sequence, KV head) pairs.  The loads of the next pair's first groups are in
-// flight while the last groups of the current pair are being consumed, and the pair's partial is
-// stored from the accumulator registers in between.  The block numbers of up to 32 groups come from
-// one gathered vector load (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
-template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
-__global__ void __launch_bounds__(64)
-flat_stream_kernel(const FlatArgs a)
+// Where a wavefront's share comes from.  A source describes the share as entries 0 .. size()-1
+// (one two-block group each), 32 at a time: load_chunk(c0) makes entries c0 .. c0+nc-1 current, and
+// the accessors below answer for entry e of the current chunk.  Everything they return is
+// wave-uniform.
+//
+// LiveSource derives the schedule in the kernel from the context lengths (and reads the block
+// table); PreparedSource reads records that coopt_decode_schedule_prepare left in memory.
+
+// Lane 2j + h of the current chunk describes block h of entry j.
+struct LiveSource {
+    const FlatArgs& a;
+    const FlatSchedule& sched;
+    const FlatCut& cut;
+    int lane, x_begin, x_end;
+    int nc = 0;
+    int seq_l = 0, cfirst_l = 0, t_l = 0, g_l = 0, gi_l = 0, tile_l = -1;
+    unsigned long long last_mask = 0;
+
+    __device__ __forceinline__ LiveSource(const FlatArgs& args, const FlatSchedule& s, const FlatCut& c,
+                                          int lane_id, int xb, int xe)
+        : a(args), sched(s), cut(c), lane(lane_id), x_begin(xb), x_end(xe) {}
+    __device__ __forceinline__ int size() const { return x_end - x_begin; }
+
+    __device__ __forceinline__ void load_chunk(int c0)
+    {
+        const int xc = x_begin + c0;
+        nc = min(32, x_end - xc);
+        const int xl = xc + (lane >> 1);
+        int first_l = 0;
+        seq_l = 0; cfirst_l = 0; t_l = 0;
+        for (int xs = xc; xs < xc + nc;) {
+            int s, first, cfirst, t;
+            sched.template locate<false>(xs, s, first, cfirst, t);
+            const int span_end = first + a.H_k * groups_of(t);     // > xs: the owner has groups
+            if (xl >= xs && xl < span_end) { seq_l = s; first_l = first; cfirst_l = cfirst; t_l = t; }
+            xs = span_end;
+        }
+        const int nb_l = (t_l + kBlock - 1) / kBlock;
+        const int ng_l = max((nb_l + 1) >> 1, 1);
+        g_l = (xl - first_l) / ng_l;
+        gi_l = xl - first_l - g_l * ng_l;
+        const int b_l = 2 * gi_l + (lane & 1);
+        const bool in_chunk = (lane >> 1) < nc;
+        tile_l = -1;
+        if (in_chunk && b_l < nb_l) tile_l = a.block_tables[(size_t)seq_l * a.max_blocks + b_l] * a.H_k + g_l;
+        // entries that end a segment: last group of their pair, or last group of the share
+        last_mask = __builtin_amdgcn_ballot_w64(
+            in_chunk && (lane & 1) == 0 && (gi_l == ng_l - 1 || xl == x_end - 1));
+    }
+    __device__ __forceinline__ void tiles(int e, int& tA, int& tB) const
+    {
+        tA = __builtin_amdgcn_readlane(tile_l, 2 * e);
+        tB = __builtin_amdgcn_readlane(tile_l, 2 * e + 1);
+    }
+    // tokens of the pair from the entry's first token on (the entry sees min(rem, 32) of them)
+    __device__ __forceinline__ int rem(int e) const
+    {
+        return __builtin_amdgcn_readlane(t_l, 2 * e) - 2 * kBlock * __builtin_amdgcn_readlane(gi_l, 2 * e);
+    }
+    __device__ __forceinline__ bool last(int e) const { return (last_mask >> (2 * e)) & 1; }
+    // first entry of the segment after the one that contains entry e (nc if there is none)
+    __device__ __forceinline__ int next_segment(int e) const
+    {
+        const unsigned long long rest = e < 32 ? last_mask >> (2 * e) : 0ull;
+        return rest ? e + (__builtin_ctzll(rest) >> 1) + 1 : nc;
+    }
+    __device__ __forceinline__ const half_t* q_rows(int e, int head_dim) const
+    {
+        const int s = __builtin_amdgcn_readlane(seq_l, 2 * e), g = __builtin_amdgcn_readlane(g_l, 2 * e);
+        return a.q + ((size_t)s * a.H_q + g * a.G) * head_dim;
+    }
+    __device__ __forceinline__ PartialSlot slot(int e) const
+    {
+        const int seq = __builtin_amdgcn_readlane(seq_l, 2 * e);
+        const int g = __builtin_amdgcn_readlane(g_l, 2 * e);
+        const int t = __builtin_amdgcn_readlane(t_l, 2 * e);
+        const int ng = (((t + kBlock - 1) / kBlock) + 1) >> 1;
+        // cost-axis position of the pair's first group
+        const int pair_first = __builtin_amdgcn_readlane(cfirst_l, 2 * e) +
+                               g * (ng + a.pair_extra) + a.pair_extra;
+        PartialSlot ps;
+        ps.row0 = seq * a.H_q + g * a.G;
+        ps.slot = blockIdx.x - cut.wg_of(pair_first);
+        // the pair's first workgroup also counts the pair's partials
+        // (in the fused step the appending workgroups do the counting)
+        ps.count_at = (ps.slot == 0 && !a.new_slots) ? seq * a.H_k + g : -1;
+        ps.count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+        return ps;
+    }
+};
+
+// A prepared schedule in memory (32-bit words):
+//   [0] layout tag  [1] status (0, or 1 once a launch found the wrong tag)  [2..15] unused
+//   counts[num_seqs * H_k]: partials per (sequence, KV head)       (rounded up to 4 words)
+//   one region per attention workgroup, `stride` words each:
+//     [0] entries in the share  [1..3] unused  then one 4-word record per entry:
+//     tile of block A, tile of block B (-1: absent), pair | last << 31, rem | slot << 16
+//   pair = sequence * H_k + KV head; rem as LiveSource::rem, capped at 0x7fff; slot = index of the
+//   partial this workgroup writes for the pair.
+constexpr int kSchedHeaderWords = 16;
+constexpr int kSchedRemCap = 0x7fff;
+
+// Lane j of the current chunk holds the record of entry j.
+struct PreparedSource {
+    const FlatArgs& a;
+    const uint32_t* region;
+    int lane, count;
+    int nc = 0;
+    uint32_t tA_l = ~0u, tB_l = ~0u, pair_l = 0, rs_l = 0;
+    unsigned long long last_mask = 0;
+
+    __device__ __forceinline__ PreparedSource(const FlatArgs& args, const uint32_t* reg, int lane_id, int n)
+        : a(args), region(reg), lane(lane_id), count(n) {}
+    __device__ __forceinline__ int size() const { return count; }
+
+    __device__ __forceinline__ void load_chunk(int c0)
+    {
+        nc = min(32, count - c0);
+        tA_l = ~0u; tB_l = ~0u; pair_l = 0; rs_l = 0;
+        if (lane < nc) {
+            typedef unsigned int rec_t __attribute__((ext_vector_type(4)));
+            const rec_t r = *reinterpret_cast<const rec_t*>(region + 4 + 4 * (c0 + lane));
+            tA_l = r.x; tB_l = r.y; pair_l = r.z; rs_l = r.w;
+        }
+        last_mask = __builtin_amdgcn_ballot_w64(lane < nc && (pair_l >> 31) != 0);
+    }
+    __device__ __forceinline__ void tiles(int e, int& tA, int& tB) const
+    {
+        tA = __builtin_amdgcn_readlane((int)tA_l, e);
+        tB = __builtin_amdgcn_readlane((int)tB_l, e);
+    }
+    __device__ __forceinline__ int rem(int e) const
+    {
+        return __builtin_amdgcn_readlane((int)rs_l, e) & 0xffff;
+    }
+    __device__ __forceinline__ bool last(int e) const { return (last_mask >> e) & 1; }
+    __device__ __forceinline__ int next_segment(int e) const
+    {
+        const unsigned long long rest = e < 32 ? last_mask >> e : 0ull;
+        return rest ? e + __builtin_ctzll(rest) + 1 : nc;
+    }
+    __device__ __forceinline__ const half_t* q_rows(int e, int head_dim) const
+    {
+        const int pair = __builtin_amdgcn_readlane((int)pair_l, e) & 0x7fffffff;
+        return a.q + (size_t)pair * a.G * head_dim;
+    }
+    __device__ __forceinline__ PartialSlot slot(int e) const
+    {
+        PartialSlot ps;
+        ps.row0 = (__builtin_amdgcn_readlane((int)pair_l, e) & 0x7fffffff) * a.G;
+        ps.slot = (int)((uint32_t)__builtin_amdgcn_readlane((int)rs_l, e) >> 16);
+        ps.count_at = -1;                  // the counts were written with the schedule
+        ps.count = 0;
+        return ps;
+    }
+};
+
+// The wave's share is ONE stream of groups that runs across the boundaries between (sequence, KV
+// head) pairs.  The loads of the next pair's first groups are in flight while the last groups of
+// the current pair are being consumed, and the pair's partial is stored from the accumulator
+// registers in between.
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, typename Source>
+__device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, unsigned char* q_stage,
+                                             int lane)
 {
     // vector-memory loads per group: two blocks of K and V chunks plus, for FP8, their scales
     constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (KV == COOPT_KV_E4M3 ? 2 : 0));
@@ -358,27 +530,12 @@ flat_stream_kernel(const FlatArgs a)
     constexpr int kWaitStaged = (kGroupLoads & 15) | (7 << 4) | (15 << 8) | ((kGroupLoads >> 4) << 14);
     constexpr int kWaitLds = 15 | (7 << 4) | (0 << 8) | (3 << 14);
     static_assert(kGroupLoads < 64, "vmcnt is a 6-bit counter");
-    const int lane = threadIdx.x;
     const int n = lane & 15, grp = lane >> 4;
-
-    const FlatSchedule sched(a.context_lens, a.new_slots, a.num_seqs, a.H_k, a.pair_extra, lane);
-    const int ctotal = sched.cost_total();
-    const FlatCut cut(max(ctotal, 1), a.decode_wgs, a.min_share);   // shares of the cost axis
-    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
-        append_and_attend<HEAD_DIM, KV>(a, sched, cut, ctotal, blockIdx.x - a.decode_wgs, lane);
-        return;
-    }
-    if (ctotal == 0) return;
-    if ((int)blockIdx.x >= cut.nwg) return;
-    const int x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
-    const int x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
-    if (x_begin >= x_end) return;           // a share that lies inside one pair's extra units
 
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
     BlockRegs<HEAD_DIM, KV> regs[DEPTH][2];
     // q operand of the pair in progress; the next pair's is staged in LDS by loads that write LDS
     // directly, so taking it over is an LDS read and never waits on a register in flight.
-    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // HEAD_DIM / 32 KiB
     constexpr int kParkAcc = HEAD_DIM / 16 * 1024;               // parked o, then m and l per lane
     unsigned char* park = q_stage + HEAD_DIM / 32 * 1024;
     float* red = reinterpret_cast<float*>(park + kParkAcc + 512);  // BLOCK_REDUCE: 128 floats
@@ -390,46 +547,17 @@ flat_stream_kernel(const FlatArgs a)
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int xc = x_begin; xc < x_end; xc += 32) {
-        const int nc = min(32, x_end - xc);                 // groups in this chunk
-        // ---- per-lane description of entry j = lane / 2, block h = lane & 1
-        const int xl = xc + (lane >> 1);
-        int seq_l = 0, first_l = 0, cfirst_l = 0, t_l = 0;
-        for (int xs = xc; xs < xc + nc;) {
-            int s, first, cfirst, t;
-            sched.template locate<false>(xs, s, first, cfirst, t);
-            const int span_end = first + a.H_k * groups_of(t);     // > xs: the owner has groups
-            if (xl >= xs && xl < span_end) { seq_l = s; first_l = first; cfirst_l = cfirst; t_l = t; }
-            xs = span_end;
-        }
-        const int nb_l = (t_l + kBlock - 1) / kBlock;
-        const int ng_l = max((nb_l + 1) >> 1, 1);
-        const int g_l = (xl - first_l) / ng_l;
-        const int gi_l = xl - first_l - g_l * ng_l;
-        const int b_l = 2 * gi_l + (lane & 1);
-        const bool in_chunk = (lane >> 1) < nc;
-        int tile_l = -1;
-        if (in_chunk && b_l < nb_l) tile_l = a.block_tables[(size_t)seq_l * a.max_blocks + b_l] * a.H_k + g_l;
-        // entries that end a segment: last group of their pair, or last group of the share
-        const unsigned long long last_mask = __builtin_amdgcn_ballot_w64(
-            in_chunk && (lane & 1) == 0 && (gi_l == ng_l - 1 || xl == x_end - 1));
-
-        auto q_rows = [&](int e) {         // q rows of the pair that entry e belongs to
-            const int s = __builtin_amdgcn_readlane(seq_l, 2 * e), g = __builtin_amdgcn_readlane(g_l, 2 * e);
-            return a.q + ((size_t)s * a.H_q + g * a.G) * HEAD_DIM;
-        };
-        // first entry of the segment after the one that contains entry e (nc if there is none)
-        auto next_segment = [&](int e) {
-            const unsigned long long rest = e < 32 ? last_mask >> (2 * e) : 0ull;
-            return rest ? e + (__builtin_ctzll(rest) >> 1) + 1 : nc;
-        };
-        load_q_operand_rows<HEAD_DIM, KV>(q_cur, q_rows(0), a.G, true, n, grp);
-        stage_q_operand<HEAD_DIM, KV>(q_stage, q_rows(min(next_segment(0), nc - 1)), a.G, n, grp);
+    const int total = src.size();
+    for (int c0 = 0; c0 < total; c0 += 32) {
+        src.load_chunk(c0);
+        const int nc = src.nc;
+        load_q_operand_rows<HEAD_DIM, KV>(q_cur, src.q_rows(0, HEAD_DIM), a.G, true, n, grp);
+        stage_q_operand<HEAD_DIM, KV>(q_stage, src.q_rows(min(src.next_segment(0), nc - 1), HEAD_DIM),
+                                      a.G, n, grp);
 
         auto issue_entry = [&](BlockRegs<HEAD_DIM, KV> (&r)[2], int e) {
-            const int ec = min(e, 31);
-            const int tA = __builtin_amdgcn_readlane(tile_l, 2 * ec);
-            const int tB = __builtin_amdgcn_readlane(tile_l, 2 * ec + 1);
+            int tA, tB;
+            src.tiles(min(e, 31), tA, tB);
             loader.issue(r[0], max(tA, 0), e < nc && tA >= 0);
             loader.issue(r[1], max(tB, 0), e < nc && tB >= 0);
         };
@@ -443,37 +571,23 @@ flat_stream_kernel(const FlatArgs a)
             for (int u = 0; u < DEPTH; ++u) {
                 const int e = j + u;
                 if (e < nc) {
-                    const int t = __builtin_amdgcn_readlane(t_l, 2 * e);
-                    const int gi = __builtin_amdgcn_readlane(gi_l, 2 * e);
-                    const int baseA = 2 * gi * kBlock;
-                    const int visA = t - baseA - 4 * grp;
+                    const int rem = src.rem(e);
+                    const int visA = rem - 4 * grp;
                     if constexpr (BLOCK_REDUCE)
                         group_update_block_reduce<HEAD_DIM, KV>(
-                            regs[u][0], regs[u][1], q_cur, m, l, acc, baseA + 2 * kBlock > t, visA,
+                            regs[u][0], regs[u][1], q_cur, m, l, acc, rem < 2 * kBlock, visA,
                             visA - kBlock, visA, visA - kBlock, a.scale_log2e, red, lane);
                     else
                         group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], q_cur, m, l, acc,
-                                                   baseA + 2 * kBlock > t, visA, visA - kBlock, visA,
+                                                   rem < 2 * kBlock, visA, visA - kBlock, visA,
                                                    visA - kBlock, a.scale_log2e);
-                    if ((last_mask >> (2 * e)) & 1) {
+                    if (src.last(e)) {
                         // ---- the segment ends: its partial is (m, l, acc / l)
-                        const int seq = __builtin_amdgcn_readlane(seq_l, 2 * e);
-                        const int g = __builtin_amdgcn_readlane(g_l, 2 * e);
-                        const int ng = (((t + kBlock - 1) / kBlock) + 1) >> 1;
-                        // cost-axis position of the pair's first group
-                        const int pair_first = __builtin_amdgcn_readlane(cfirst_l, 2 * e) +
-                                               g * (ng + a.pair_extra) + a.pair_extra;
-                        PartialSlot ps;
-                        ps.row0 = seq * a.H_q + g * a.G;
-                        ps.slot = blockIdx.x - cut.wg_of(pair_first);
-                        // the pair's first workgroup also counts the pair's partials
-                        // (in the fused step the appending workgroups do the counting)
-                        ps.count_at = (ps.slot == 0 && !a.new_slots) ? seq * a.H_k + g : -1;
-                        ps.count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
+                        const PartialSlot ps = src.slot(e);
                         l += __shfl_xor(l, 16);
                         l += __shfl_xor(l, 32);
                         const float inv = 1.0f / l;
-                        if (xc + e == x_end - 1) {
+                        if (c0 + e == total - 1) {
                             // end of the share: nothing runs behind these stores
 #pragma unroll
                             for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= inv;
@@ -502,8 +616,9 @@ flat_stream_kernel(const FlatArgs a)
                             for (int jj = 0; jj < HEAD_DIM / 32; ++jj)
                                 q_cur[jj] = *reinterpret_cast<const half8_t*>(q_stage + 1024 * jj + 16 * lane);
                             __builtin_amdgcn_s_waitcnt(kWaitLds);      // read before it is restaged
-                            const int e2 = next_segment(e + 1);
-                            if (e2 < nc) stage_q_operand<HEAD_DIM, KV>(q_stage, q_rows(e2), a.G, n, grp);
+                            const int e2 = src.next_segment(e + 1);
+                            if (e2 < nc)
+                                stage_q_operand<HEAD_DIM, KV>(q_stage, src.q_rows(e2, HEAD_DIM), a.G, n, grp);
                         }
                     }
                 }
@@ -512,6 +627,115 @@ flat_stream_kernel(const FlatArgs a)
                 issue_entry(regs[u], e + DEPTH);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    }
+}
+
+// One wave per workgroup.  The block numbers of up to 32 groups come from one gathered vector load
+// (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
+__global__ void __launch_bounds__(64)
+flat_stream_kernel(const FlatArgs a)
+{
+    const int lane = threadIdx.x;
+    const FlatSchedule sched(a.context_lens, a.new_slots, a.num_seqs, a.H_k, a.pair_extra, lane);
+    const int ctotal = sched.cost_total();
+    const FlatCut cut(max(ctotal, 1), a.decode_wgs, a.min_share);   // shares of the cost axis
+    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
+        const int pair = blockIdx.x - a.decode_wgs;
+        int count = 0;
+        if (pair < a.num_seqs * a.H_k) count = attention_partials_of(a, sched, cut, ctotal, pair);
+        append_and_attend<HEAD_DIM, KV>(a, pair, lane, count, -1);
+        return;
+    }
+    if (ctotal == 0) return;
+    if ((int)blockIdx.x >= cut.nwg) return;
+    const int x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
+    const int x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
+    if (x_begin >= x_end) return;           // a share that lies inside one pair's extra units
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // see launch_flat_depth
+    LiveSource src(a, sched, cut, lane, x_begin, x_end);
+    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
+}
+
+// The same stream from a prepared schedule: no schedule arithmetic and no block-table read stand
+// between the launch and the first tile load, only the load of the workgroup's records.
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
+__global__ void __launch_bounds__(64)
+flat_stream_prepared_kernel(const FlatArgs a)
+{
+    const int lane = threadIdx.x;
+    if (wave_uniform((int)a.sched[0]) != (int)a.sched_tag) {
+        // not the schedule this launch was told to expect: do nothing, leave a mark
+        if (blockIdx.x == 0 && lane == 0) a.sched_w[1] = 1u;
+        return;
+    }
+    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
+        const int pair = blockIdx.x - a.decode_wgs;
+        const int total = pair < a.num_seqs * a.H_k ? (int)a.sched[kSchedHeaderWords + pair] : 0;
+        append_and_attend<HEAD_DIM, KV>(a, pair, lane, 0, total);
+        return;
+    }
+    const uint32_t* region = a.sched + a.sched_regions + (size_t)blockIdx.x * a.sched_stride;
+    const int count = wave_uniform((int)region[0]);
+    if (count <= 0) return;
+    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];
+    PreparedSource src(a, region, lane, min(count, (a.sched_stride - 4) / 4));
+    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
+}
+
+// Writes the schedule that flat_stream_prepared_kernel reads: the same grid as the attention launch
+// it prepares (one wavefront per share, then one per (sequence, KV head) pair for the counts), each
+// wavefront deriving its share exactly as flat_stream_kernel does and leaving one record per entry.
+__global__ void __launch_bounds__(64)
+flat_prepare_kernel(const FlatArgs a)
+{
+    const int lane = threadIdx.x;
+    const FlatSchedule sched(a.context_lens, a.new_slots, a.num_seqs, a.H_k, a.pair_extra, lane);
+    const int ctotal = sched.cost_total();
+    const FlatCut cut(max(ctotal, 1), a.decode_wgs, a.min_share);
+    uint32_t* out = a.sched_w;
+    if ((int)blockIdx.x >= a.decode_wgs) {
+        const int pair = blockIdx.x - a.decode_wgs;
+        if (pair < a.num_seqs * a.H_k) {
+            const int seq = pair / a.H_k;
+            const int count = attention_partials_of(a, sched, cut, ctotal, pair);
+            const bool appends = a.new_slots && a.new_slots[seq] >= 0 && a.context_lens[seq] > 0;
+            if (lane == 0) out[kSchedHeaderWords + pair] = (uint32_t)(count + (appends ? 1 : 0));
+        }
+        if (pair == 0 && lane == 0) {
+            out[1] = 0u;
+            out[0] = a.sched_tag;
+        }
+        return;
+    }
+    uint32_t* region = out + a.sched_regions + (size_t)blockIdx.x * a.sched_stride;
+    int x_begin = 0, x_end = 0;
+    if (ctotal > 0 && (int)blockIdx.x < cut.nwg) {
+        x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
+        x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
+    }
+    // the region holds every share the cut can produce; the clamp only keeps the stores inside
+    const int count = min(max(x_end - x_begin, 0), (a.sched_stride - 4) / 4);
+    if (lane == 0) region[0] = (uint32_t)count;
+    if (count == 0) return;
+    LiveSource src(a, sched, cut, lane, x_begin, x_begin + count);
+    for (int c0 = 0; c0 < count; c0 += 32) {
+        src.load_chunk(c0);
+        const int tile_b = __shfl_down(src.tile_l, 1);
+        const int nb = (src.t_l + kBlock - 1) / kBlock;
+        const int ng = max((nb + 1) >> 1, 1);
+        const int pair_first = src.cfirst_l + src.g_l * (ng + a.pair_extra) + a.pair_extra;
+        const int slot = min(max((int)blockIdx.x - cut.wg_of(pair_first), 0), a.max_slots - 1);
+        const int rem = min(src.t_l - 2 * kBlock * src.gi_l, kSchedRemCap);
+        const uint32_t last = (uint32_t)((src.last_mask >> lane) & 1);
+        const uint32_t pair = (uint32_t)(src.seq_l * a.H_k + src.g_l);
+        if ((lane & 1) == 0 && (lane >> 1) < src.nc) {
+            typedef unsigned int rec_t __attribute__((ext_vector_type(4)));
+            *reinterpret_cast<rec_t*>(region + 4 + 4 * (c0 + (lane >> 1))) =
+                rec_t{(uint32_t)src.tile_l, (uint32_t)tile_b, pair | (last << 31),
+                      (uint32_t)rem | ((uint32_t)slot << 16)};
         }
     }
 }
@@ -527,6 +751,8 @@ flat_merge_kernel(const FlatArgs a)
 {
     constexpr int E = HEAD_DIM / 64;
     constexpr int kSpec = 8;
+    // a prepared schedule that is not the expected one: the split kernel did nothing, nor does this
+    if (a.sched && wave_uniform((int)a.sched[0]) != (int)a.sched_tag) return;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // seq * H_q + head
     if (row >= a.num_seqs * a.H_q) return;
     const int lane = threadIdx.x & 63;
@@ -597,20 +823,31 @@ flat_merge_kernel(const FlatArgs a)
     for (int e = 0; e < E; ++e) a.out[(size_t)row * HEAD_DIM + lane + 64 * e] = (half_t)o[e];
 }
 
-template <int HEAD_DIM, int KV, bool BIG>
-static void launch_flat_depth(const FlatArgs& a, const FlatPlan& plan, dim3 grid, hipStream_t stream)
+template <int HEAD_DIM, int KV, bool BIG, int DEPTH, bool BLOCK_REDUCE>
+static void launch_flat_kernel(const FlatArgs& a, dim3 grid, hipStream_t stream)
 {
     const dim3 block(64);
     // staging area of one q operand + one parked partial (o, m, l per lane) + reduction scratch
     const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512 + 512;
+    if (a.sched)
+        hipLaunchKernelGGL((flat_stream_prepared_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>), grid,
+                           block, lds, stream, a);
+    else
+        hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>), grid, block,
+                           lds, stream, a);
+}
+
+template <int HEAD_DIM, int KV, bool BIG>
+static void launch_flat_depth(const FlatArgs& a, const FlatPlan& plan, dim3 grid, hipStream_t stream)
+{
     if (plan.block_reduce) {             // comparison variant: depth 2 only
-        hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG, true>), grid, block, lds, stream, a);
+        launch_flat_kernel<HEAD_DIM, KV, BIG, 2, true>(a, grid, stream);
         return;
     }
     switch (plan.depth) {
-    case 1: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 1, BIG, false>), grid, block, lds, stream, a); break;
-    case 3: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 3, BIG, false>), grid, block, lds, stream, a); break;
-    default: hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, 2, BIG, false>), grid, block, lds, stream, a); break;
+    case 1: launch_flat_kernel<HEAD_DIM, KV, BIG, 1, false>(a, grid, stream); break;
+    case 3: launch_flat_kernel<HEAD_DIM, KV, BIG, 3, false>(a, grid, stream); break;
+    default: launch_flat_kernel<HEAD_DIM, KV, BIG, 2, false>(a, grid, stream); break;
     }
 }
 
@@ -680,10 +917,71 @@ static FlatArgs flat_args(const coopt_shape* sh, const FlatPlan& plan, void* wor
     return a;
 }
 
+// Where the parts of a prepared schedule lie (32-bit words) and the tag that names the layout and
+// everything the records depend on besides the block tables and the lengths themselves.
+struct SchedLayout {
+    uint32_t tag;
+    int regions, stride;
+    size_t words;
+};
+
+static SchedLayout sched_layout(const coopt_shape* sh, const FlatPlan& plan, bool fused)
+{
+    SchedLayout L;
+    const int wgs = flat_grid_groups(sh, plan);
+    const int min_share = plan.min_share_groups();
+    // a share never exceeds this many cost units, hence groups (see FlatCut): + 2 of slack
+    const long long cap = std::max(flat_max_cost(sh) / wgs, 2LL * min_share) + 3;
+    L.stride = (int)(4 + 4 * cap);
+    const int pairs = sh->num_seqs * sh->num_kv_heads;
+    L.regions = kSchedHeaderWords + ((pairs + 3) & ~3);
+    L.words = (size_t)L.regions + (size_t)wgs * L.stride;
+    uint32_t h = 2166136261u;
+    const int fields[] = {0x53434831, sh->num_seqs, sh->num_q_heads, sh->num_kv_heads, sh->head_dim,
+                          sh->num_blocks, sh->max_blocks_per_seq, wgs, L.stride, min_share,
+                          kPairExtra, flat_max_slots(sh, plan), fused ? 1 : 0};
+    for (int f : fields)
+        for (int b = 0; b < 4; ++b) h = (h ^ ((uint32_t)f >> (8 * b) & 0xffu)) * 16777619u;
+    L.tag = h | 1u;                      // never the zero of fresh memory
+    return L;
+}
+
+size_t flat_schedule_bytes(const coopt_shape* sh, const FlatPlan& plan)
+{
+    if (flat_max_cost(sh) > 0x7fffffffLL) return 0;
+    const SchedLayout L = sched_layout(sh, plan, false);
+    // record fields: 16 bits of slot, a region stride that stays a small int
+    if (flat_max_slots(sh, plan) > 0xffff) return 0;
+    if (flat_max_cost(sh) / flat_grid_groups(sh, plan) > (1 << 24)) return 0;
+    return L.words * sizeof(uint32_t);
+}
+
+int launch_flat_prepare(const int32_t* block_tables, const int32_t* context_lens,
+                        const int64_t* slot_mapping, void* schedule, const coopt_shape* sh,
+                        const FlatPlan& plan, hipStream_t stream)
+{
+    if (flat_schedule_bytes(sh, plan) == 0) return COOPT_ERR_SHAPE;
+    FlatArgs a = flat_args(sh, plan, nullptr);
+    const SchedLayout L = sched_layout(sh, plan, slot_mapping != nullptr);
+    a.block_tables = block_tables;
+    a.context_lens = context_lens;
+    a.new_slots = slot_mapping;
+    a.decode_wgs = flat_grid_groups(sh, plan);
+    a.sched_w = (uint32_t*)schedule;
+    a.sched_tag = L.tag;
+    a.sched_regions = L.regions;
+    a.sched_stride = L.stride;
+    const long long wgs = (long long)a.decode_wgs + (long long)sh->num_seqs * sh->num_kv_heads;
+    if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    hipLaunchKernelGGL(flat_prepare_kernel, dim3((unsigned)wgs), dim3(64), 0, stream, a);
+    return launch_status();
+}
+
 int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
                       const float* v_scale, const int32_t* block_tables,
                       const int32_t* context_lens, void* workspace, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append)
+                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append,
+                      const void* schedule)
 {
     if (flat_max_cost(sh) > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     FlatArgs a = flat_args(sh, plan, workspace);
@@ -703,6 +1001,15 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
         a.v_scale_w = const_cast<float*>(v_scale);
         wgs += (long long)sh->num_seqs * sh->num_kv_heads;
     }
+    if (schedule) {
+        if (flat_schedule_bytes(sh, plan) == 0) return COOPT_ERR_SHAPE;
+        const SchedLayout L = sched_layout(sh, plan, append != nullptr);
+        a.sched = (const uint32_t*)schedule;
+        a.sched_w = (uint32_t*)const_cast<void*>(schedule);
+        a.sched_tag = L.tag;
+        a.sched_regions = L.regions;
+        a.sched_stride = L.stride;
+    }
     if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     const dim3 grid((unsigned)wgs);
     const bool big = !pool_fits_small(sh);
@@ -717,11 +1024,16 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
 }
 
 int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream)
+                      const FlatPlan& plan, hipStream_t stream, const void* schedule, bool fused)
 {
     FlatArgs a = flat_args(sh, plan, workspace);
     a.context_lens = context_lens;
     a.out = (half_t*)out;
+    if (schedule) {    // the prepared counts instead of the ones a live split kernel leaves
+        a.counts = reinterpret_cast<int32_t*>(const_cast<void*>(schedule)) + kSchedHeaderWords;
+        a.sched = (const uint32_t*)schedule;
+        a.sched_tag = sched_layout(sh, plan, fused).tag;
+    }
     const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
     const dim3 rgrid((unsigned)((rows + 3) / 4)), rblock(256);
     if (sh->head_dim == 128)

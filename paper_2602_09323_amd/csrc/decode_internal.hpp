@@ -29,12 +29,25 @@ struct FlatAppend {
 // Enqueue the balanced split kernel (attention -> partial results in the workspace; with `append`
 // also the cache write of one new token per sequence and that token's partial) and the merge
 // kernel (partials -> fp16 output rows).  Both derive the same schedule from the context lengths
-// and the plan, so the plan must not change between them.  Each returns a coopt_status.
+// and the plan, so the plan must not change between them.  With `schedule` (written by
+// launch_flat_prepare for the same shape, plan and mode) the split kernel reads its shares from
+// there instead of deriving them (block_tables is then unused), and the merge kernel the counts
+// (`fused` = the mode the schedule was prepared for).
+// Each returns a coopt_status.
 int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
                       const float* v_scale, const int32_t* block_tables,
                       const int32_t* context_lens, void* workspace, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append = nullptr);
+                      const FlatPlan& plan, hipStream_t stream, const FlatAppend* append = nullptr,
+                      const void* schedule = nullptr);
 int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream);
+                      const FlatPlan& plan, hipStream_t stream, const void* schedule = nullptr,
+                      bool fused = false);
+
+// Bytes of a prepared schedule for this shape and plan (0: the shape is out of range), and the
+// launch that writes one: slot_mapping NULL for plain decode, else the fused step's new tokens.
+size_t flat_schedule_bytes(const coopt_shape* sh, const FlatPlan& plan);
+int launch_flat_prepare(const int32_t* block_tables, const int32_t* context_lens,
+                        const int64_t* slot_mapping, void* schedule, const coopt_shape* sh,
+                        const FlatPlan& plan, hipStream_t stream);
 
 }  // namespace coopt

@@ -69,6 +69,7 @@ def test_unsupported_shapes_are_refused_without_launch(lib, bad):
     assert lib.coopt_paged_gqa_decode(one, one, one, one, one, one, one, one, None, ctypes.c_size_t(0), ctypes.byref(sh), None) == -2
     assert lib.coopt_paged_gqa_reduce(one, one, one, one, 16, 1, one, ctypes.byref(sh), None) == -2
     assert lib.coopt_decode_workspace_bytes(ctypes.byref(sh)) == 0
+    assert lib.coopt_decode_schedule_bytes(ctypes.byref(sh)) == 0
 
 
 def test_null_pointers_and_bad_arguments(lib):
@@ -95,6 +96,21 @@ def test_null_pointers_and_bad_arguments(lib):
     assert lib.coopt_paged_gqa_decode_step(None, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1
     assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, None, ctypes.c_size_t(need2), ctypes.byref(sh2), None) == -1
     assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2 - 1), ctypes.byref(sh2), None) == -3
+    # prepared schedule: buffers are required, sized and aligned; a fused call needs all three rows
+    nsched = lib.coopt_decode_schedule_bytes(ctypes.byref(sh2))
+    assert nsched > 0 and nsched % 16 == 0
+    cs = ctypes.c_size_t
+    assert lib.coopt_decode_schedule_prepare(one, one, None, None, cs(nsched), ctypes.byref(sh2), None) == -1
+    assert lib.coopt_decode_schedule_prepare(None, one, None, one, cs(nsched), ctypes.byref(sh2), None) == -1
+    assert lib.coopt_decode_schedule_prepare(one, one, None, one, cs(nsched - 1), ctypes.byref(sh2), None) == -3
+    assert lib.coopt_decode_schedule_prepare(one, one, None, ctypes.c_void_p(8), cs(nsched), ctypes.byref(sh2), None) == -3
+    run = lib.coopt_paged_gqa_decode_scheduled
+    assert run(None, None, None, one, one, one, one, one, one, one, one, cs(need2), None, cs(nsched), ctypes.byref(sh2), None) == -1
+    assert run(one, None, one, one, one, one, one, one, one, one, one, cs(need2), one, cs(nsched), ctypes.byref(sh2), None) == -1
+    assert run(None, None, None, one, one, one, one, one, one, one, one, cs(need2 - 1), one, cs(nsched), ctypes.byref(sh2), None) == -3
+    assert run(None, None, None, one, one, one, one, one, one, one, one, cs(need2), one, cs(nsched - 1), ctypes.byref(sh2), None) == -3
+    assert run(None, None, None, one, one, one, one, one, one, one, one, cs(need2), ctypes.c_void_p(8), cs(nsched), ctypes.byref(sh2), None) == -3
+    assert run(None, None, None, None, one, one, one, one, one, one, one, cs(need2), one, cs(nsched), ctypes.byref(sh2), None) == -1
     # partitioned: partition size must be a positive multiple of 16; buffers must cover the table
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 24, one, one, one, 8, ctypes.byref(sh), None) == -2
     assert lib.coopt_paged_gqa_decode_partitioned(one, one, one, one, one, one, one, 16, one, one, one, 7, ctypes.byref(sh), None) == -3
@@ -126,6 +142,8 @@ def test_empty_batches_are_accepted_without_launch(lib):
     assert lib.coopt_paged_gqa_decode(None, None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
     assert lib.coopt_paged_gqa_decode_step(None, None, None, None, None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
     assert lib.coopt_paged_gqa_decode_split(None, None, None, None, None, None, None, None, z, ctypes.byref(sh), None) == 0
+    assert lib.coopt_decode_schedule_prepare(None, None, None, None, z, ctypes.byref(sh), None) == 0
+    assert lib.coopt_paged_gqa_decode_scheduled(None, None, None, None, None, None, None, None, None, None, None, z, None, z, ctypes.byref(sh), None) == 0
     assert lib.coopt_paged_gqa_prefill_chunk(None, None, None, None, None, None, None, None, 0, 0, None, ctypes.byref(sh), None) == 0
     sh1 = _shape()
     assert lib.coopt_kv_cache_write_fp8(None, None, None, 0, None, None, None, None, ctypes.byref(sh1), None) == 0
