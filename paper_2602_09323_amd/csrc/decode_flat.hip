@@ -461,29 +461,35 @@ struct LiveSource {
 constexpr int kSchedHeaderWords = 16;
 constexpr int kSchedRemCap = 0x7fff;
 
-// Lane j of the current chunk holds the record of entry j.
+typedef unsigned int sched_rec_t __attribute__((ext_vector_type(4)));
+
+// Lane j of the current chunk holds the record of entry j.  The records of the first chunk are
+// loaded by the kernel before it knows the share's size (a region always has room for 32).
 struct PreparedSource {
     const FlatArgs& a;
     const uint32_t* region;
     int lane, count;
+    sched_rec_t first;
     int nc = 0;
     uint32_t tA_l = ~0u, tB_l = ~0u, pair_l = 0, rs_l = 0;
     unsigned long long last_mask = 0;
 
-    __device__ __forceinline__ PreparedSource(const FlatArgs& args, const uint32_t* reg, int lane_id, int n)
-        : a(args), region(reg), lane(lane_id), count(n) {}
+    __device__ __forceinline__ PreparedSource(const FlatArgs& args, const uint32_t* reg, int lane_id, int n,
+                                              sched_rec_t first_chunk)
+        : a(args), region(reg), lane(lane_id), count(n), first(first_chunk) {}
     __device__ __forceinline__ int size() const { return count; }
 
     __device__ __forceinline__ void load_chunk(int c0)
     {
         nc = min(32, count - c0);
-        tA_l = ~0u; tB_l = ~0u; pair_l = 0; rs_l = 0;
-        if (lane < nc) {
-            typedef unsigned int rec_t __attribute__((ext_vector_type(4)));
-            const rec_t r = *reinterpret_cast<const rec_t*>(region + 4 + 4 * (c0 + lane));
-            tA_l = r.x; tB_l = r.y; pair_l = r.z; rs_l = r.w;
-        }
-        last_mask = __builtin_amdgcn_ballot_w64(lane < nc && (pair_l >> 31) != 0);
+        sched_rec_t r = first;
+        if (c0 > 0 && lane < nc) r = *reinterpret_cast<const sched_rec_t*>(region + 4 + 4 * (c0 + lane));
+        const bool have = lane < nc;
+        tA_l = have ? r.x : ~0u;
+        tB_l = have ? r.y : ~0u;
+        pair_l = have ? r.z : 0u;
+        rs_l = have ? r.w : 0u;
+        last_mask = __builtin_amdgcn_ballot_w64(have && (pair_l >> 31) != 0);
     }
     __device__ __forceinline__ void tiles(int e, int& tA, int& tB) const
     {
@@ -666,22 +672,26 @@ __global__ void __launch_bounds__(64)
 flat_stream_prepared_kernel(const FlatArgs a)
 {
     const int lane = threadIdx.x;
+    // the tag, the share's size and its first 32 records are loaded together: one round trip
+    const bool attends = (int)blockIdx.x < a.decode_wgs;
+    const uint32_t* region = a.sched + a.sched_regions + (size_t)(attends ? blockIdx.x : 0) * a.sched_stride;
+    sched_rec_t first = {~0u, ~0u, 0u, 0u};
+    if (attends && lane < 32) first = *reinterpret_cast<const sched_rec_t*>(region + 4 + 4 * lane);
+    const int count = wave_uniform((int)region[0]);
     if (wave_uniform((int)a.sched[0]) != (int)a.sched_tag) {
         // not the schedule this launch was told to expect: do nothing, leave a mark
         if (blockIdx.x == 0 && lane == 0) a.sched_w[1] = 1u;
         return;
     }
-    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
+    if (!attends) {                                                  // fused step only
         const int pair = blockIdx.x - a.decode_wgs;
         const int total = pair < a.num_seqs * a.H_k ? (int)a.sched[kSchedHeaderWords + pair] : 0;
         append_and_attend<HEAD_DIM, KV>(a, pair, lane, 0, total);
         return;
     }
-    const uint32_t* region = a.sched + a.sched_regions + (size_t)blockIdx.x * a.sched_stride;
-    const int count = wave_uniform((int)region[0]);
     if (count <= 0) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];
-    PreparedSource src(a, region, lane, min(count, (a.sched_stride - 4) / 4));
+    PreparedSource src(a, region, lane, min(count, (a.sched_stride - 4) / 4), first);
     stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
 }
 
@@ -732,9 +742,8 @@ flat_prepare_kernel(const FlatArgs a)
         const uint32_t last = (uint32_t)((src.last_mask >> lane) & 1);
         const uint32_t pair = (uint32_t)(src.seq_l * a.H_k + src.g_l);
         if ((lane & 1) == 0 && (lane >> 1) < src.nc) {
-            typedef unsigned int rec_t __attribute__((ext_vector_type(4)));
-            *reinterpret_cast<rec_t*>(region + 4 + 4 * (c0 + (lane >> 1))) =
-                rec_t{(uint32_t)src.tile_l, (uint32_t)tile_b, pair | (last << 31),
+            *reinterpret_cast<sched_rec_t*>(region + 4 + 4 * (c0 + (lane >> 1))) =
+                sched_rec_t{(uint32_t)src.tile_l, (uint32_t)tile_b, pair | (last << 31),
                       (uint32_t)rem | ((uint32_t)slot << 16)};
         }
     }
@@ -931,7 +940,8 @@ static SchedLayout sched_layout(const coopt_shape* sh, const FlatPlan& plan, boo
     const int wgs = flat_grid_groups(sh, plan);
     const int min_share = plan.min_share_groups();
     // a share never exceeds this many cost units, hence groups (see FlatCut): + 2 of slack
-    const long long cap = std::max(flat_max_cost(sh) / wgs, 2LL * min_share) + 3;
+    // (and a region always holds 32 records, so the first chunk can be read unconditionally)
+    const long long cap = std::max(std::max(flat_max_cost(sh) / wgs, 2LL * min_share) + 3, 32LL);
     L.stride = (int)(4 + 4 * cap);
     const int pairs = sh->num_seqs * sh->num_kv_heads;
     L.regions = kSchedHeaderWords + ((pairs + 3) & ~3);
