@@ -34,9 +34,13 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # 256 MiB device copy: FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  The summaries
 # with the commands are under profiles/; the figures belong to the default decode plan.
 PMC_TRAFFIC = {
-    "llama13b_gqa_fp8_decode": {"fetch_kib": 37957.3, "fetch_scale": 2.0,
-                                "write_kib": 3372.2, "write_scale": 1.0,
-                                "source": "profiles/flat_stream_kernel_llama13b_gqa_fp8_decode.md"},
+    # (workload, schedule) -> counters of the kernel that `roofline` times
+    ("llama13b_gqa_fp8_decode", "prepared"): {
+        "fetch_kib": 38265.5, "fetch_scale": 2.0, "write_kib": 3366.6, "write_scale": 1.0,
+        "source": "profiles/flat_stream_prepared_kernel_llama13b_gqa_fp8_decode.md"},
+    ("llama13b_gqa_fp8_decode", "live"): {
+        "fetch_kib": 37957.3, "fetch_scale": 2.0, "write_kib": 3372.2, "write_scale": 1.0,
+        "source": "profiles/flat_stream_kernel_llama13b_gqa_fp8_decode.md"},
 }
 
 
@@ -315,7 +319,7 @@ def main():
         # algorithmic bytes of one decode-kernel launch: KV codes + scales of the visible tokens,
         # q, and the block-table entries used (partials are a by-product of the split, not counted)
         alg = ab["kv"] + ab["q_out"] // 2 + ab["tables"]
-        pmc = PMC_TRAFFIC.get(w.name)
+        pmc = PMC_TRAFFIC.get((w.name, args.schedule))
         traffic = None
         if pmc and not args.plan and not partitioned:
             traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
