@@ -306,8 +306,11 @@ def main():
                    "decode_plan": plan,
                    "step": ("kv_cache_write + paged_gqa_decode_partitioned (P=%d) + paged_gqa_reduce, "
                             "one layer" % P) if partitioned else
-                           ("paged_gqa_decode_step (cache write fused into the decode launch), one layer"
-                            if fused else "kv_cache_write + paged_gqa_decode, one layer"),
+                           (("paged_gqa_decode_scheduled" if prepared else "paged_gqa_decode_step") +
+                            " (cache write fused into the decode launch), one layer"
+                            if fused else
+                            "kv_cache_write + " + ("paged_gqa_decode_scheduled" if prepared else "paged_gqa_decode") +
+                            ", one layer"),
                    "schedule": ("prepared once per %d steps (one per decoding step of a %d-layer model), "
                                 "inside the timed region" % (layers, layers)) if prepared else
                                ("fixed partitions" if partitioned else "derived inside every launch"),
