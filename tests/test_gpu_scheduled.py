@@ -8,7 +8,7 @@ import torch
 import paper_2602_09323_amd as coopt
 import workloads
 from gpu_utils import alloc_dev_cache, assert_close, dev, dev_cache_to_host, hip_write, shape_of
-from helpers import oracle_fill
+from helpers import alloc_cache, oracle_fill
 
 pytestmark = pytest.mark.gpu
 
@@ -206,7 +206,7 @@ def test_schedule_that_does_not_fit_is_refused_on_the_device(oracle_mod):
 
 
 def test_full_size_configs(oracle_mod):
-    for cfg in (1, 3):
+    for cfg in (1, 2, 3):
         w = workloads.make(cfg)
         cache = oracle_fill(oracle_mod, w)
         new_slots = w.slots[w.new_index()]
@@ -216,3 +216,18 @@ def test_full_size_configs(oracle_mod):
         _same_cache(w, dcache, cache, f"cfg{cfg} scheduled step")
         ref = _oracle_decode(oracle_mod, w, cache)
         print("cfg%d scheduled step max-abs %.2e" % (cfg, assert_close(got, ref, f"cfg{cfg} scheduled")), flush=True)
+
+
+def test_stale_slots_are_never_read(oracle_mod):
+    """Opt-Pa Eq. 9 from a prepared schedule: tokens >= t and blocks >= ceil(t/B) hold NaN codes
+    and NaN scales, and the records name no tile beyond the context."""
+    from gpu_utils import cache_to_dev
+    lens = [37, 50, 129, 16, 1]
+    for kv_dtype in ("e4m3", "fp16"):
+        w = workloads.make_custom("spoison", seed=85, S=len(lens), H_q=10, H_k=2, d=128, B=16, NB=40,
+                                  context_lens=lens, max_blocks=12, kv_dtype=kv_dtype)
+        ref = _oracle_decode(oracle_mod, w, oracle_fill(oracle_mod, w))
+        poisoned = alloc_cache(w, fill_byte=0x7F)            # E4M3 NaN / fp16 NaN; scales NaN
+        oracle_fill(oracle_mod, w, cache=poisoned)
+        got = _run(w, cache_to_dev(poisoned), _prepare(w))
+        assert_close(got, ref, f"scheduled decode over a poisoned {kv_dtype} cache")
