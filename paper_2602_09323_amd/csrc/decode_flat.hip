@@ -749,21 +749,27 @@ flat_prepare_kernel(const FlatArgs a)
     }
 }
 
-// One wavefront per (sequence, query head) row merges the row's partials.  The number of partials
-// of the row's (sequence, KV head) pair was left by the split kernel; pairs with no token at all
-// have no writer, so the context length decides whether the count is meaningful.  All loads of the
-// first kSpec partials are issued before the count is known (they lie inside the workspace whatever
-// the count is), so the kernel is one memory round trip deep.
-template <int HEAD_DIM>
+// Merges the partials of each (sequence, query head) row.  The number of partials of the row's
+// (sequence, KV head) pair was left by the split kernel; pairs with no token at all have no writer,
+// so the context length decides whether the count is meaningful.  All loads of the first kSpec
+// partials are issued before the count is known (they lie inside the workspace whatever the count
+// is), so the kernel is one memory round trip deep for rows of up to kSpec partials.
+//   WIDE = false: one wavefront per row, four rows per workgroup.
+//   WIDE = true (long contexts, tens of partials per row): one workgroup per row; wavefront w takes
+//   partials w, w + 4, ... -- 4 * kSpec in the first round trip -- and the four sums meet in LDS.
+template <int HEAD_DIM, bool WIDE>
 __global__ void __launch_bounds__(256)
 flat_merge_kernel(const FlatArgs a)
 {
     constexpr int E = HEAD_DIM / 64;
     constexpr int kSpec = 8;
+    constexpr int kStep = WIDE ? 4 : 1;                 // distance between a wavefront's partials
     // a prepared schedule that is not the expected one: the split kernel did nothing, nor does this
     if (a.sched && wave_uniform((int)a.sched[0]) != (int)a.sched_tag) return;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // seq * H_q + head
-    if (row >= a.num_seqs * a.H_q) return;
+    const int wave = wave_uniform((int)(threadIdx.x >> 6));
+    const int row = WIDE ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;   // seq * H_q + head
+    if (row >= a.num_seqs * a.H_q) return;              // (WIDE: never, the grid is the row count)
+    const int first = WIDE ? wave : 0;                  // this wavefront's first partial
     const int lane = threadIdx.x & 63;
     const int seq = row / a.H_q;
     const int g = (row - seq * a.H_q) / a.G;
@@ -772,12 +778,13 @@ flat_merge_kernel(const FlatArgs a)
     const float* es = a.exp_sums + base;
     const float* po = a.tmp_out + base * HEAD_DIM + lane;
 
-    const int nspec = min(kSpec, a.max_slots);
     float o_spec[kSpec][E];
 #pragma unroll
-    for (int j = 0; j < kSpec; ++j)
+    for (int j = 0; j < kSpec; ++j) {
+        const int p = first + kStep * j;
 #pragma unroll
-        for (int e = 0; e < E; ++e) o_spec[j][e] = j < nspec ? po[(size_t)j * HEAD_DIM + 64 * e] : 0.0f;
+        for (int e = 0; e < E; ++e) o_spec[j][e] = p < a.max_slots ? po[(size_t)p * HEAD_DIM + 64 * e] : 0.0f;
+    }
     const float ml_l = lane < a.max_slots ? ml[lane] : 0.0f;
     const float es_l = lane < a.max_slots ? es[lane] : 0.0f;
     const int t = a.context_lens[seq];
@@ -788,48 +795,76 @@ flat_merge_kernel(const FlatArgs a)
     float o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] = 0.0f;
+    float W = 1.0f;
     if (count > 0) {
         float M = lane < count ? ml_l : -INFINITY;
         for (int p = 64 + lane; p < count; p += 64) M = fmaxf(M, ml[p]);
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) M = fmaxf(M, __shfl_xor(M, s));
         const float wv = lane < count ? es_l * __expf(ml_l - M) : 0.0f;   // weights of partials 0..63
-        float W = wv;
+        W = wv;
 #pragma unroll
         for (int j = 0; j < kSpec; ++j) {
+            const int p = first + kStep * j;                               // < 64
             const float wj = __builtin_bit_cast(
-                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j));
-            if (j < count) {
+                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), p));
+            if (p < count) {
 #pragma unroll
                 for (int e = 0; e < E; ++e) o[e] += wj * o_spec[j][e];
             }
         }
-        for (int j = kSpec; j < min(count, 64); ++j) {
-            const float wj = __builtin_bit_cast(
-                float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv), j));
+        // further partials kSpec at a time, all loads of a batch in flight together (long contexts
+        // have tens of partials per row: one dependent load per partial would cost a round trip each).
+        // w holds the weights of partials b0 .. b0+63; the batch is partials p0, p0 + kStep, ...
+        auto add_batch = [&](float w, int b0, int p0, int end) {
+            float x[kSpec][E];
 #pragma unroll
-            for (int e = 0; e < E; ++e) o[e] += wj * po[(size_t)j * HEAD_DIM + 64 * e];
-        }
+            for (int jj = 0; jj < kSpec; ++jj) {
+                const int p = min(p0 + kStep * jj, end - 1);
+#pragma unroll
+                for (int e = 0; e < E; ++e) x[jj][e] = po[(size_t)p * HEAD_DIM + 64 * e];
+            }
+#pragma unroll
+            for (int jj = 0; jj < kSpec; ++jj) {
+                const int p = p0 + kStep * jj;
+                const float wj = __builtin_bit_cast(
+                    float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), (p - b0) & 63));
+                if (p < end) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) o[e] += wj * x[jj][e];
+                }
+            }
+        };
+        const int end0 = min(count, 64);
+        for (int p0 = first + kStep * kSpec; p0 < end0; p0 += kStep * kSpec) add_batch(wv, 0, p0, end0);
         for (int b0 = 64; b0 < count; b0 += 64) {                          // very long contexts
             const int p = b0 + lane;
             const float w2 = p < count ? es[p] * __expf(ml[p] - M) : 0.0f;
             W += w2;
-            const int cnt = min(64, count - b0);
-            for (int j = 0; j < cnt; ++j) {
-                const float wj = __builtin_bit_cast(
-                    float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w2), j));
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] += wj * po[(size_t)(b0 + j) * HEAD_DIM + 64 * e];
-            }
+            const int end = min(b0 + 64, count);
+            for (int p0 = b0 + first; p0 < end; p0 += kStep * kSpec) add_batch(w2, b0, p0, end);
         }
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) W += __shfl_xor(W, s);
-        const float inv = 1.0f / W;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] *= inv;
     }
+    if constexpr (WIDE) {
+        __shared__ float sm[4][HEAD_DIM];
 #pragma unroll
-    for (int e = 0; e < E; ++e) a.out[(size_t)row * HEAD_DIM + lane + 64 * e] = (half_t)o[e];
+        for (int e = 0; e < E; ++e) sm[wave][lane + 64 * e] = o[e];
+        __syncthreads();
+        if (wave == 0) {
+            const float inv = count > 0 ? 1.0f / W : 0.0f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const int d = lane + 64 * e;
+                a.out[(size_t)row * HEAD_DIM + d] = (half_t)((sm[0][d] + sm[1][d] + sm[2][d] + sm[3][d]) * inv);
+            }
+        }
+    } else {
+        const float inv = count > 0 ? 1.0f / W : 0.0f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) a.out[(size_t)row * HEAD_DIM + lane + 64 * e] = (half_t)(o[e] * inv);
+    }
 }
 
 template <int HEAD_DIM, int KV, bool BIG, int DEPTH, bool BLOCK_REDUCE>
@@ -1045,11 +1080,20 @@ int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, c
         a.sched_tag = sched_layout(sh, plan, fused).tag;
     }
     const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
-    const dim3 rgrid((unsigned)((rows + 3) / 4)), rblock(256);
-    if (sh->head_dim == 128)
-        hipLaunchKernelGGL(flat_merge_kernel<128>, rgrid, rblock, 0, stream, a);
-    else
-        hipLaunchKernelGGL(flat_merge_kernel<64>, rgrid, rblock, 0, stream, a);
+    const dim3 rblock(256);
+    if (a.max_slots > 32) {      // rows may have tens of partials: a workgroup per row
+        const dim3 rgrid((unsigned)rows);
+        if (sh->head_dim == 128)
+            hipLaunchKernelGGL((flat_merge_kernel<128, true>), rgrid, rblock, 0, stream, a);
+        else
+            hipLaunchKernelGGL((flat_merge_kernel<64, true>), rgrid, rblock, 0, stream, a);
+    } else {
+        const dim3 rgrid((unsigned)((rows + 3) / 4));
+        if (sh->head_dim == 128)
+            hipLaunchKernelGGL((flat_merge_kernel<128, false>), rgrid, rblock, 0, stream, a);
+        else
+            hipLaunchKernelGGL((flat_merge_kernel<64, false>), rgrid, rblock, 0, stream, a);
+    }
     return launch_status();
 }
 
