@@ -4,8 +4,9 @@
 // lane), a butterfly max gives the row's absmax, and each lane encodes and stores its own
 // elements.  Both tiles are stored in matrix-core operand order (see attn_tile.hpp), so a row is
 // scattered in 16-byte (K) and 1-byte (V) pieces.  Write volume is a few hundred bytes per
-// row, against kilobytes per token read by attention, so this kernel is latency-, not
-// bandwidth-bound and is kept simple.
+// row, against kilobytes per token read by attention, so for a decode step's one token per sequence
+// this kernel is latency-, not bandwidth-bound and is kept simple; calls with many tokens take the
+// bulk kernel further down.
 #include "kv_quant.hpp"
 
 namespace coopt {
@@ -38,6 +39,159 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
                                     lane, k_cache, v_cache, k_scale, v_scale);
 }
 
+// ---- bulk form (prefill chunks, cache fills): many tokens per call.
+//
+// The row-per-wavefront kernel above stores a row's V codes one byte at a time (the V tile keeps
+// four tokens of one dim in a dword), which is fine for one token per sequence and slow for
+// thousands.  Here 16 dims (one 16-byte K chunk) belong to a lane, d/16 lanes make a row and a
+// wavefront takes 64/(d/16) CONSECUTIVE tokens of one KV head: K is one 16-byte store per lane;
+// and wherever four consecutive tokens sit in four consecutive slots of one block, starting at a
+// multiple of four -- the usual case of a chunk written into fresh blocks -- their V codes are
+// exchanged between the four rows' lanes and leave as whole dwords.  Any other slot pattern
+// (skipped tokens, scattered slots) falls back to byte stores, row by row.  Same arithmetic as the
+// row kernel, hence the same bytes.
+
+// max over the groups of CH neighbouring lanes (CH a power of two)
+template <int CH>
+__device__ __forceinline__ float group_max(float a)
+{
+#pragma unroll
+    for (int o = CH / 2; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+    return a;
+}
+
+typedef unsigned int wu32x4 __attribute__((ext_vector_type(4)));
+
+// 16 fp16 values (two 16-byte words) -> their group's scale and 16 E4M3 codes, element e in byte e
+template <int CH>
+__device__ __forceinline__ wu32x4 quantise_chunk(wu32x4 lo, wu32x4 hi, float& scale)
+{
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        // (through scalars: a bit cast taken straight from a vector element reads element 0)
+        const uint32_t wl = lo[i], wh = hi[i];
+        const half2_t a = __builtin_bit_cast(half2_t, wl), b = __builtin_bit_cast(half2_t, wh);
+        x[2 * i] = (float)a[0];
+        x[2 * i + 1] = (float)a[1];
+        x[8 + 2 * i] = (float)b[0];
+        x[8 + 2 * i + 1] = (float)b[1];
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(x[e]));
+    amax = group_max<CH>(amax);
+    scale = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kE4M3Max);
+    wu32x4 codes;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            y[e] = fminf(fmaxf(__fdiv_rn(x[4 * d + e], scale), -kE4M3Max), kE4M3Max);
+        int w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w, true);
+        codes[d] = (uint32_t)w;
+    }
+    return codes;
+}
+
+template <int HEAD_DIM>
+__global__ void __launch_bounds__(256)
+kv_write_fp8_bulk_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
+                         const int64_t* __restrict__ slot_mapping,
+                         const uint32_t* __restrict__ skip_set, int num_tokens, int H_k,
+                         uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache,
+                         float* __restrict__ k_scale, float* __restrict__ v_scale)
+{
+    constexpr int CH = HEAD_DIM / 16;           // lanes per row
+    constexpr int R = 64 / CH;                  // rows (consecutive tokens) per wavefront
+    const int lane = threadIdx.x & 63;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);       // token group * H_k + head
+    const int tg = unit / H_k, head = unit - tg * H_k;
+    if (tg * R >= num_tokens) return;
+    const int r = lane / CH, c = lane % CH;
+    const int tok = tg * R + r;
+    const bool in_range = tok < num_tokens;
+    const int64_t slot = in_range ? slot_mapping[tok] : -1;
+    const bool valid = slot >= 0 && !in_skip_set(skip_set, in_range ? tok : 0);   // Eq. 5
+    const int64_t blk = valid ? slot / kBlock : 0;
+    const int off = valid ? (int)(slot - blk * kBlock) : 0;
+    const size_t tile = (size_t)(blk * H_k + head);
+
+    // ---- the quad (rows 4q .. 4q+3) stores V as dwords if its four tokens fill slots s, s+1, s+2,
+    // s+3 with s a multiple of four (then they share a block and a token quad of the tile)
+    const int j = r & 3;                                        // row inside its quad
+    const int64_t slot0 = __shfl(slot, (lane & ~(3 * CH)) | 0, 64);   // the quad's first row, same c
+    int fits = (valid && slot == slot0 + j && (slot0 & 3) == 0) ? 1 : 0;
+    fits &= __shfl_xor(fits, CH);                 // every lane takes part in both exchanges
+    fits &= __shfl_xor(fits, 2 * CH);
+    const bool quad = fits != 0;
+
+    const size_t row_at = ((size_t)(in_range ? tok : 0) * H_k + head) * HEAD_DIM + 16 * c;
+    const wu32x4* kp = reinterpret_cast<const wu32x4*>(k + row_at);
+    const wu32x4* vp = reinterpret_cast<const wu32x4*>(v + row_at);
+    const wu32x4 k_lo = kp[0], k_hi = kp[1], v_lo = vp[0], v_hi = vp[1];
+
+    float ks, vs;
+    const wu32x4 kc = quantise_chunk<CH>(k_lo, k_hi, ks);
+    const wu32x4 vc = quantise_chunk<CH>(v_lo, v_hi, vs);
+
+    uint8_t* ktile = k_cache + tile * (kBlock * HEAD_DIM);
+    uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
+    if (valid) {
+        // K tile [d/16][16 tokens][16]
+        *reinterpret_cast<wu32x4*>(ktile + (c * kBlock + off) * 16) = kc;
+        if (c == 0) {
+            k_scale[tile * kBlock + off] = ks;
+            v_scale[tile * kBlock + off] = vs;
+        }
+    }
+
+    // ---- V: lane j of a quad collects dword j (dims 4j .. 4j+3 of the chunk) of all four rows
+    uint32_t got[4];
+    got[0] = vc[0];
+#pragma unroll
+    for (int x = 1; x < 4; ++x) {
+        // send the partner (row j ^ x) its dword, receive mine from it
+        const int want = j ^ x;
+        const uint32_t send = want == 0 ? vc[0] : want == 1 ? vc[1] : want == 2 ? vc[2] : vc[3];
+        got[x] = (uint32_t)__shfl_xor((int)send, x * CH);
+    }
+    got[0] = j == 0 ? vc[0] : j == 1 ? vc[1] : j == 2 ? vc[2] : vc[3];
+    // got[x] = dword j of row j ^ x; order them by row
+    uint32_t g4[4];
+    {
+        const bool s1 = (j & 1) != 0, s2 = (j & 2) != 0;
+        const uint32_t a0 = s1 ? got[1] : got[0], a1 = s1 ? got[0] : got[1];
+        const uint32_t a2 = s1 ? got[3] : got[2], a3 = s1 ? got[2] : got[3];
+        g4[0] = s2 ? a2 : a0;
+        g4[1] = s2 ? a3 : a1;
+        g4[2] = s2 ? a0 : a2;
+        g4[3] = s2 ? a1 : a3;
+    }
+    if (quad) {
+        // byte b of g4[t] = code of dim 16c + 4j + b, token t of the quad: transpose to dwords of
+        // four tokens
+        const uint32_t lo01 = __builtin_amdgcn_perm(g4[1], g4[0], 0x05010400u);
+        const uint32_t hi01 = __builtin_amdgcn_perm(g4[1], g4[0], 0x07030602u);
+        const uint32_t lo23 = __builtin_amdgcn_perm(g4[3], g4[2], 0x05010400u);
+        const uint32_t hi23 = __builtin_amdgcn_perm(g4[3], g4[2], 0x07030602u);
+        const uint32_t out[4] = {__builtin_amdgcn_perm(lo23, lo01, 0x05040100u),
+                                 __builtin_amdgcn_perm(lo23, lo01, 0x07060302u),
+                                 __builtin_amdgcn_perm(hi23, hi01, 0x05040100u),
+                                 __builtin_amdgcn_perm(hi23, hi01, 0x07060302u)};
+        const int off0 = off - j;                                // the quad's first token
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<uint32_t*>(vtile + v_tile_index<1>(off0, 16 * c + 4 * j + b)) = out[b];
+    } else if (valid) {
+#pragma unroll
+        for (int n = 0; n < 16; ++n)
+            vtile[v_tile_index<1>(off, 16 * c + n)] = (uint8_t)(vc[n >> 2] >> (8 * (n & 3)));
+    }
+}
+
 template <int HEAD_DIM>
 __global__ void __launch_bounds__(256)
 kv_write_fp16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -67,6 +221,9 @@ kv_write_fp16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict_
 
 using namespace coopt;
 
+// From this many tokens per call on, the bulk kernel (a call of a decode step has one per sequence).
+constexpr int kBulkWriteTokens = 64;
+
 static int write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
                      const uint32_t* skip_set, int32_t num_tokens, uint8_t* k_cache,
                      uint8_t* v_cache, float* k_scale, float* v_scale, const coopt_shape* shape,
@@ -80,8 +237,24 @@ static int write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
         return COOPT_ERR_NULL;
     const long long rows = (long long)num_tokens * shape->num_kv_heads;
     if (rows > 0x7fffffffLL) return COOPT_ERR_SHAPE;
-    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
     hipStream_t stream = (hipStream_t)hip_stream;
+    const dim3 block(256);
+    if (num_tokens >= kBulkWriteTokens) {
+        // 64 / (d/16) consecutive tokens of one head per wavefront
+        const int per_wave = shape->head_dim == 128 ? 8 : 16;
+        const long long units = (long long)((num_tokens + per_wave - 1) / per_wave) * shape->num_kv_heads;
+        const dim3 grid((unsigned)((units + 3) / 4));
+        if (shape->head_dim == 128)
+            hipLaunchKernelGGL(kv_write_fp8_bulk_kernel<128>, grid, block, 0, stream, (const half_t*)k,
+                               (const half_t*)v, slot_mapping, skip_set, num_tokens,
+                               shape->num_kv_heads, k_cache, v_cache, k_scale, v_scale);
+        else
+            hipLaunchKernelGGL(kv_write_fp8_bulk_kernel<64>, grid, block, 0, stream, (const half_t*)k,
+                               (const half_t*)v, slot_mapping, skip_set, num_tokens,
+                               shape->num_kv_heads, k_cache, v_cache, k_scale, v_scale);
+        return launch_status();
+    }
+    const dim3 grid((unsigned)((rows + 3) / 4));
     if (shape->head_dim == 128)
         hipLaunchKernelGGL(kv_write_fp8_kernel<128>, grid, block, 0, stream, (const half_t*)k,
                            (const half_t*)v, slot_mapping, skip_set, (int)rows, shape->num_kv_heads,
