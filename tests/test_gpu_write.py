@@ -139,3 +139,45 @@ def test_explicit_skip_set(oracle_mod, kv_dtype):
                                  None, *devc2, shape_of(w))
     torch.cuda.synchronize()
     _compare_caches(w, host2, devc2, f"empty skip set {kv_dtype}")
+
+
+@pytest.mark.parametrize("d,H_k", [(128, 2), (64, 3)])
+def test_bulk_calls_with_every_slot_pattern(oracle_mod, d, H_k):
+    """Calls of 64 tokens and more take the bulk kernel, whose V stores depend on how four
+    consecutive tokens' slots lie: aligned runs, runs that start off a multiple of four, runs cut
+    by skipped tokens, slots scattered at random -- all against the oracle, and the same tokens
+    again through calls small enough for the row kernel."""
+    import paper_2602_09323_amd as coopt
+    from gpu_utils import dev, shape_of
+    T, NB = 333, 64
+    w = workloads.make_custom("bulk", seed=200 + d, S=1, H_q=H_k, H_k=H_k, d=d, B=16, NB=NB,
+                              context_lens=[T])
+    rng = np.random.default_rng(d)
+    patterns = {}
+    patterns["aligned runs"] = np.arange(T, dtype=np.int64) + 32
+    patterns["runs from an odd slot"] = np.arange(T, dtype=np.int64) + 37
+    scattered = rng.permutation(NB * 16)[:T].astype(np.int64)
+    patterns["scattered"] = scattered
+    cut = np.arange(T, dtype=np.int64) + 48
+    cut[rng.random(T) < 0.2] = -1
+    patterns["runs cut by skipped tokens"] = cut
+    mixed = np.arange(T, dtype=np.int64) + 16
+    mixed[100:200] = scattered[:100][np.argsort(rng.random(100))] % (NB * 16 - 600) + 500   # may collide: dedupe
+    _, first = np.unique(mixed, return_index=True)
+    keep = np.zeros(T, bool); keep[first] = True
+    mixed[~keep] = -1
+    patterns["runs and scatter mixed"] = mixed
+    shape = shape_of(w)
+    dk, dv = dev(w.k_ctx.view(np.uint16)), dev(w.v_ctx.view(np.uint16))
+    for name, slots in patterns.items():
+        host, devc = _roundtrip(w)
+        oracle_mod.kv_cache_write_fp8(w.k_ctx, w.v_ctx, slots, *host, H_k=H_k, d=d, B=16)
+        coopt.kv_cache_write_fp8(dk, dv, dev(slots), *devc, shape)            # one bulk call
+        torch.cuda.synchronize()
+        _compare_caches(w, host, devc, f"bulk d={d}: {name}")
+        _, devr = _roundtrip(w)
+        ds = dev(slots)
+        for i in range(0, T, 40):                                            # row kernel
+            coopt.kv_cache_write_fp8(dk[i:i + 40], dv[i:i + 40], ds[i:i + 40], *devr, shape)
+        torch.cuda.synchronize()
+        _compare_caches(w, host, devr, f"rows d={d}: {name}")
