@@ -443,7 +443,7 @@ def bench_prefill(args, w, coopt, torch, dev):
                    "step": "kv_cache_write of the chunk + paged_gqa_prefill_chunk, one layer",
                    "launch": "eager"},
         "wall_ms_timed_region": round(wall_ms, 2),
-        "roofline": {"bound": "mfma", "kernel": "prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk)",
+        "roofline": {"bound": "mfma", "kernel": "prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk: its two launches, full and half-size workgroups)",
                      "achieved": round(flops / kern_ms / 1e9, 1), "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(flops / kern_ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4),
                      "traffic": None, "algorithmic_flops_per_launch": flops,

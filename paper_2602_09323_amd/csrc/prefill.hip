@@ -37,11 +37,14 @@ struct PrefillArgs {
     int32_t pool_tiles;
     int32_t num_pairs;        // num_seqs * H_k
     int32_t wgs_per_pair;
+    int32_t tile_base;        // this launch covers tiles [tile_base, tile_limit) of every pair
+    int32_t tile_limit;
     float scale_log2e;
 };
 
 constexpr int kPrefillWaves = 8;                // two teams of four producer roles
 constexpr int kPrefillGroupsPerStage = 4;      // two-block groups between two barriers
+constexpr int kPrefillCUs = 256;               // MI355X: the launch shape is planned for its CU count
 
 // Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
 template <int HEAD_DIM>
@@ -157,10 +160,11 @@ prefill_chunk_kernel(const PrefillArgs a)
     if (C <= 0) return;
     const int tiles_per_head = (C + 15) / 16;
     const int total_tiles = a.G * tiles_per_head;
-    const int wg_first_tile = (k8 % a.wgs_per_pair) * (kPrefillWaves * NR);
-    if (wg_first_tile >= total_tiles) return;          // the whole workgroup leaves together
+    const int end_tile = min(total_tiles, a.tile_limit);
+    const int wg_first_tile = a.tile_base + (k8 % a.wgs_per_pair) * (kPrefillWaves * NR);
+    if (wg_first_tile >= end_tile) return;             // the whole workgroup leaves together
     const int first_tile = wg_first_tile + wave_id * NR;
-    const bool active = first_tile < total_tiles;      // a wave without tiles still produces
+    const bool active = first_tile < end_tile;         // a wave without tiles still produces
 
     half8_t qop[NR][HEAD_DIM / 32];
     int limit[NR];          // tokens visible to column n of tile r
@@ -168,7 +172,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     int my_max = 0, min_row = 0x7fffffff;
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-        const int tile = min(first_tile + r, total_tiles - 1);   // surplus tiles repeat the last
+        const int tile = min(first_tile + r, end_tile - 1);      // surplus tiles repeat the last
         const int hh = tile / tiles_per_head;
         const int i0 = (tile - hh * tiles_per_head) * 16;
         const int row = min(i0 + n, C - 1);                      // surplus rows repeat row C-1
@@ -184,7 +188,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     // the workgroup streams as far as its longest column needs
     int wg_max = 0;
     for (int i = 0; i < kPrefillWaves * NR; ++i) {
-        const int tile = min(wg_first_tile + i, total_tiles - 1);
+        const int tile = min(wg_first_tile + i, end_tile - 1);
         const int i0 = (tile % tiles_per_head) * 16;
         wg_max = max(wg_max, t_ctx + min(i0 + 15, C - 1) + 1);
     }
@@ -376,7 +380,7 @@ prefill_chunk_kernel(const PrefillArgs a)
         L += __shfl_xor(L, 32);
         const float inv = 1.0f / L;                       // the common power of two of acc and l cancels
         const int row = row0[r] + n;
-        if (first_tile + r < total_tiles && row < C) {
+        if (first_tile + r < end_tile && row < C) {
             half_t* dst = a.out + ((size_t)(qs + row) * a.H_q + head[r]) * HEAD_DIM + 4 * grp;
 #pragma unroll
             for (int c = 0; c < HEAD_DIM / 16; ++c) {
@@ -423,19 +427,50 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
 
-    constexpr int NR = 2;
+    // One workgroup (8 waves, 2 tiles each) fills a CU, so the launch runs in rounds of one
+    // workgroup per CU, and a last round that is mostly empty costs a full one.  Where that
+    // happens, the last tiles of every pair go to a second launch of half-size workgroups (one
+    // tile per wave), which takes about 0.65 of a round.
     const int tiles = a.G * ((max_chunk_len + 15) / 16);
     a.num_pairs = sh->num_seqs * sh->num_kv_heads;
-    a.wgs_per_pair = (tiles + kPrefillWaves * NR - 1) / (kPrefillWaves * NR);
-    const long long wgs = (long long)((a.num_pairs + 7) / 8) * 8 * a.wgs_per_pair;
-    if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
-    const dim3 grid((unsigned)wgs), block(64 * kPrefillWaves);
+    const int pairs8 = (a.num_pairs + 7) / 8 * 8;
+    const int full_per_pair = (tiles + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves);
+    int a_per_pair = full_per_pair, b_per_pair = 0;
+    {
+        auto rounds = [](long long wgs) { return (double)((wgs + kPrefillCUs - 1) / kPrefillCUs); };
+        const long long W = (long long)pairs8 * full_per_pair;
+        const int cand = (int)((W / kPrefillCUs) * kPrefillCUs / pairs8);   // full rounds only
+        if (cand >= 1 && cand < full_per_pair) {
+            const int rest = tiles - cand * 2 * kPrefillWaves;
+            const int small = (rest + kPrefillWaves - 1) / kPrefillWaves;
+            const double split = rounds((long long)pairs8 * cand) + 0.65 * rounds((long long)pairs8 * small);
+            if (split < rounds(W)) {
+                a_per_pair = cand;
+                b_per_pair = small;
+            }
+        }
+    }
+    const dim3 block(64 * kPrefillWaves);
     const size_t lds = 2 * kPrefillGroupsPerStage *
                        (size_t)(sh->head_dim == 128 ? PrefillStage<128>::kBytes : PrefillStage<64>::kBytes);
     hipStream_t stream = (hipStream_t)hip_stream;
-#define COOPT_PREFILL(D, KV, BIG) \
-    hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, NR, BIG>), grid, block, lds, stream, a)
     const bool big = !pool_fits_small(sh);
+#define COOPT_PREFILL(D, KV, BIG)                                                                   \
+    do {                                                                                            \
+        a.tile_base = 0;                                                                            \
+        a.tile_limit = b_per_pair ? a_per_pair * 2 * kPrefillWaves : 0x7fffffff;                    \
+        a.wgs_per_pair = a_per_pair;                                                                \
+        hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 2, BIG>),                                   \
+                           dim3((unsigned)((long long)pairs8 * a_per_pair)), block, lds, stream, a); \
+        if (b_per_pair) {                                                                           \
+            a.tile_base = a.tile_limit;                                                             \
+            a.tile_limit = 0x7fffffff;                                                              \
+            a.wgs_per_pair = b_per_pair;                                                            \
+            hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 1, BIG>),                               \
+                               dim3((unsigned)((long long)pairs8 * b_per_pair)), block, lds, stream, a); \
+        }                                                                                           \
+    } while (0)
+    if ((long long)pairs8 * full_per_pair > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E4M3, true); else COOPT_PREFILL(128, COOPT_KV_E4M3, false); }
         else { if (big) COOPT_PREFILL(64, COOPT_KV_E4M3, true); else COOPT_PREFILL(64, COOPT_KV_E4M3, false); }
