@@ -194,6 +194,8 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  *             (COOPT_ERR_NULL if mixed); the other arguments as in coopt_paged_gqa_decode_step,
  *             without block_tables.  out NULL = stop after the partial results (the workspace then
  *             holds what coopt_paged_gqa_decode_split leaves).
+ * prepare only enqueues a kernel on hip_stream: the launches that use the schedule must be ordered
+ * after it (same stream, or an event), and two launches that use one schedule may overlap.
  * A schedule prepared for another shape, plan or mode is recognised on the device by a tag: such a
  * launch reads and writes nothing except word 1 of the schedule, which it sets to 1 (prepare
  * resets it to 0), and `out` keeps its old contents.  A schedule whose tables or lengths have
