@@ -217,6 +217,83 @@ kv_write_fp16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict_
     }
 }
 
+// The bulk form for fp16 caches: a pure scatter.  8 dims (one 16-byte K chunk) per lane, d/8 lanes
+// per row, 64/(d/8) consecutive tokens of one KV head per wavefront.  K is one 16-byte store per
+// lane.  The V tile keeps four tokens of one dim in 8 bytes: the lanes of an aligned run of four
+// tokens exchange their halves and store 8 bytes per dim, else 2 bytes each.
+template <int HEAD_DIM>
+__global__ void __launch_bounds__(256)
+kv_write_fp16_bulk_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                          const int64_t* __restrict__ slot_mapping,
+                          const uint32_t* __restrict__ skip_set, int num_tokens, int H_k,
+                          uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache)
+{
+    constexpr int CH = HEAD_DIM / 8;            // lanes per row
+    constexpr int R = 64 / CH;                  // rows (consecutive tokens) per wavefront: 4 or 8
+    const int lane = threadIdx.x & 63;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);       // token group * H_k + head
+    const int tg = unit / H_k, head = unit - tg * H_k;
+    if (tg * R >= num_tokens) return;
+    const int r = lane / CH, c = lane % CH;
+    const int tok = tg * R + r;
+    const bool in_range = tok < num_tokens;
+    const int64_t slot = in_range ? slot_mapping[tok] : -1;
+    const bool valid = slot >= 0 && !in_skip_set(skip_set, in_range ? tok : 0);   // Eq. 5
+    const int64_t blk = valid ? slot / kBlock : 0;
+    const int off = valid ? (int)(slot - blk * kBlock) : 0;
+    const size_t tile = (size_t)(blk * H_k + head);
+
+    const int j = r & 3;                                        // row inside its quad
+    const int64_t slot0 = __shfl(slot, lane & ~(3 * CH), 64);   // the quad's first row, same c
+    int fits = (valid && slot == slot0 + j && (slot0 & 3) == 0) ? 1 : 0;
+    fits &= __shfl_xor(fits, CH);                 // every lane takes part in both exchanges
+    fits &= __shfl_xor(fits, 2 * CH);
+    const bool quad = fits != 0;
+
+    const size_t row_at = ((size_t)(in_range ? tok : 0) * H_k + head) * HEAD_DIM + 8 * c;
+    const wu32x4 kc = *reinterpret_cast<const wu32x4*>(k + row_at);   // dims 8c .. 8c+7
+    const wu32x4 vc = *reinterpret_cast<const wu32x4*>(v + row_at);
+    uint16_t* ktile = k_cache + tile * (kBlock * HEAD_DIM);
+    uint16_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
+    // K tile [d/8][16 tokens][8]
+    if (valid) *reinterpret_cast<wu32x4*>(ktile + (c * kBlock + off) * 8) = kc;
+
+    // ---- V: lane j of a quad collects dword j (dims 8c + 2j, 8c + 2j + 1) of all four rows
+    uint32_t got[4];
+#pragma unroll
+    for (int x = 1; x < 4; ++x) {
+        const int want = j ^ x;
+        const uint32_t send = want == 0 ? vc[0] : want == 1 ? vc[1] : want == 2 ? vc[2] : vc[3];
+        got[x] = (uint32_t)__shfl_xor((int)send, x * CH);
+    }
+    got[0] = j == 0 ? vc[0] : j == 1 ? vc[1] : j == 2 ? vc[2] : vc[3];
+    uint32_t g4[4];                                              // g4[t] = dword j of row t
+    {
+        const bool s1 = (j & 1) != 0, s2 = (j & 2) != 0;
+        const uint32_t a0 = s1 ? got[1] : got[0], a1 = s1 ? got[0] : got[1];
+        const uint32_t a2 = s1 ? got[3] : got[2], a3 = s1 ? got[2] : got[3];
+        g4[0] = s2 ? a2 : a0;
+        g4[1] = s2 ? a3 : a1;
+        g4[2] = s2 ? a0 : a2;
+        g4[3] = s2 ? a1 : a3;
+    }
+    if (quad) {
+        const int off0 = off - j;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {           // dim 8c + 2j + h: the four tokens' halves
+            const uint32_t sel = h == 0 ? 0x05040100u : 0x07060302u;
+            const uint32_t t01 = __builtin_amdgcn_perm(g4[1], g4[0], sel);
+            const uint32_t t23 = __builtin_amdgcn_perm(g4[3], g4[2], sel);
+            typedef unsigned int wu32x2 __attribute__((ext_vector_type(2)));
+            *reinterpret_cast<wu32x2*>(vtile + v_tile_index<2>(off0, 8 * c + 2 * j + h)) = wu32x2{t01, t23};
+        }
+    } else if (valid) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n)
+            vtile[v_tile_index<2>(off, 8 * c + n)] = (uint16_t)(vc[n >> 1] >> (16 * (n & 1)));
+    }
+}
+
 }  // namespace coopt
 
 using namespace coopt;
@@ -277,8 +354,23 @@ static int write_fp16(const void* k, const void* v, const int64_t* slot_mapping,
     if (!k || !v || !slot_mapping || !k_cache || !v_cache) return COOPT_ERR_NULL;
     const long long rows = (long long)num_tokens * shape->num_kv_heads;
     if (rows > 0x7fffffffLL) return COOPT_ERR_SHAPE;
-    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
     hipStream_t stream = (hipStream_t)hip_stream;
+    const dim3 block(256);
+    if (num_tokens >= kBulkWriteTokens) {
+        const int per_wave = shape->head_dim == 128 ? 4 : 8;     // 64 / (d/8) tokens per wavefront
+        const long long units = (long long)((num_tokens + per_wave - 1) / per_wave) * shape->num_kv_heads;
+        const dim3 grid((unsigned)((units + 3) / 4));
+        if (shape->head_dim == 128)
+            hipLaunchKernelGGL(kv_write_fp16_bulk_kernel<128>, grid, block, 0, stream, (const uint16_t*)k,
+                               (const uint16_t*)v, slot_mapping, skip_set, num_tokens,
+                               shape->num_kv_heads, (uint16_t*)k_cache, (uint16_t*)v_cache);
+        else
+            hipLaunchKernelGGL(kv_write_fp16_bulk_kernel<64>, grid, block, 0, stream, (const uint16_t*)k,
+                               (const uint16_t*)v, slot_mapping, skip_set, num_tokens,
+                               shape->num_kv_heads, (uint16_t*)k_cache, (uint16_t*)v_cache);
+        return launch_status();
+    }
+    const dim3 grid((unsigned)((rows + 3) / 4));
     if (shape->head_dim == 128)
         hipLaunchKernelGGL(kv_write_fp16_kernel<128>, grid, block, 0, stream, (const uint16_t*)k,
                            (const uint16_t*)v, slot_mapping, skip_set, (int)rows,

@@ -141,8 +141,9 @@ def test_explicit_skip_set(oracle_mod, kv_dtype):
     _compare_caches(w, host2, devc2, f"empty skip set {kv_dtype}")
 
 
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "fp16"])
 @pytest.mark.parametrize("d,H_k", [(128, 2), (64, 3)])
-def test_bulk_calls_with_every_slot_pattern(oracle_mod, d, H_k):
+def test_bulk_calls_with_every_slot_pattern(oracle_mod, d, H_k, kv_dtype):
     """Calls of 64 tokens and more take the bulk kernel, whose V stores depend on how four
     consecutive tokens' slots lie: aligned runs, runs that start off a multiple of four, runs cut
     by skipped tokens, slots scattered at random -- all against the oracle, and the same tokens
@@ -151,8 +152,11 @@ def test_bulk_calls_with_every_slot_pattern(oracle_mod, d, H_k):
     from gpu_utils import dev, shape_of
     T, NB = 333, 64
     w = workloads.make_custom("bulk", seed=200 + d, S=1, H_q=H_k, H_k=H_k, d=d, B=16, NB=NB,
-                              context_lens=[T])
+                              context_lens=[T], kv_dtype=kv_dtype)
     rng = np.random.default_rng(d)
+    fp8 = kv_dtype == "e4m3"
+    o_write = oracle_mod.kv_cache_write_fp8 if fp8 else oracle_mod.kv_cache_write_fp16
+    d_write = coopt.kv_cache_write_fp8 if fp8 else coopt.kv_cache_write_fp16
     patterns = {}
     patterns["aligned runs"] = np.arange(T, dtype=np.int64) + 32
     patterns["runs from an odd slot"] = np.arange(T, dtype=np.int64) + 37
@@ -171,13 +175,13 @@ def test_bulk_calls_with_every_slot_pattern(oracle_mod, d, H_k):
     dk, dv = dev(w.k_ctx.view(np.uint16)), dev(w.v_ctx.view(np.uint16))
     for name, slots in patterns.items():
         host, devc = _roundtrip(w)
-        oracle_mod.kv_cache_write_fp8(w.k_ctx, w.v_ctx, slots, *host, H_k=H_k, d=d, B=16)
-        coopt.kv_cache_write_fp8(dk, dv, dev(slots), *devc, shape)            # one bulk call
+        o_write(w.k_ctx, w.v_ctx, slots, *(host if fp8 else host[:2]), H_k=H_k, d=d, B=16)
+        d_write(dk, dv, dev(slots), *(devc if fp8 else devc[:2]), shape)       # one bulk call
         torch.cuda.synchronize()
-        _compare_caches(w, host, devc, f"bulk d={d}: {name}")
+        _compare_caches(w, host, devc, f"bulk {kv_dtype} d={d}: {name}")
         _, devr = _roundtrip(w)
         ds = dev(slots)
         for i in range(0, T, 40):                                            # row kernel
-            coopt.kv_cache_write_fp8(dk[i:i + 40], dv[i:i + 40], ds[i:i + 40], *devr, shape)
+            d_write(dk[i:i + 40], dv[i:i + 40], ds[i:i + 40], *(devr if fp8 else devr[:2]), shape)
         torch.cuda.synchronize()
-        _compare_caches(w, host, devr, f"rows d={d}: {name}")
+        _compare_caches(w, host, devr, f"rows {kv_dtype} d={d}: {name}")
