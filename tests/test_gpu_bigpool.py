@@ -46,6 +46,15 @@ def test_decode_all_paths(big, oracle_mod):
     for split in (True, False):
         assert_close(hip_decode(w, dcache, q=q, split=split), ref, f"big pool split={split}")
     shape = shape_of(w)
+    # the same decode from a prepared schedule
+    sched = torch.zeros(coopt.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    outs = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
+    coopt.decode_schedule_prepare(dev(w.block_tables), dev(w.context_lens), None, sched, shape)
+    coopt.paged_gqa_decode_scheduled(None, None, None, dev(q.view(np.uint16)), *dcache,
+                                     dev(w.context_lens), outs, ws, sched, shape)
+    torch.cuda.synchronize()
+    assert_close(outs.cpu().numpy().astype(np.float64), ref, "big pool, prepared schedule")
     P, max_parts = 256, (w.max_blocks * w.B + 255) // 256
     tmp_out = torch.empty((w.S, w.H_q, max_parts, w.d), dtype=torch.float32, device="cuda")
     ml = torch.empty((w.S, w.H_q, max_parts), dtype=torch.float32, device="cuda")
