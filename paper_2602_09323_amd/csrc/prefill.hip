@@ -144,7 +144,6 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int wave_id = wave_uniform((int)(threadIdx.x >> 6));
     const int wave = wave_id & 3;                      // producer role inside its team
     const int team = wave_id >> 2;                     // team t produces the groups p with p % kTeams == t
-    constexpr int kTeams = kPrefillWaves / 4;
     const int n = lane & 15, grp = lane >> 4;
     // all workgroups of a (sequence, KV head) pair on one XCD (ids go round-robin over 8 XCDs)
     const int k8 = blockIdx.x >> 3;
@@ -206,31 +205,43 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- block numbers come through the scalar unit, one group ahead: a vector load of them
-    // inside the loop would turn the producers' waits on the vector-memory counter into waits for
-    // the tile loads just issued.  A team produces its groups in order, p = team, team + kTeams, ...
-    int next_idA = bt[min(2 * team, nblk - 1)], next_idB = bt[min(2 * team + 1, nblk - 1)];
+    // ---- block numbers: the team's groups of a stage are p = stage * GPS + i * kTeams + team; lane
+    // 2i + b fetches the number of block b of group i, in ONE vector load per stage that is issued a
+    // whole stage before the tile loads it serves and ahead of the tile loads of the stage before
+    // (the vector-memory counter is in order: by the time those tiles have been waited for, the
+    // numbers are back).  Fetched where they are needed -- through the scalar unit or not -- their
+    // latency sat between two tile loads and again in front of the barrier, every stage.
+    constexpr int GPS = kPrefillGroupsPerStage;
+    constexpr int kTeams = kPrefillWaves / 4;
+    static_assert(GPS % kTeams == 0, "every team produces the same number of groups per stage");
+    const __amdgpu_buffer_rsrc_t bt_rsrc = TileLoader<HEAD_DIM, KV, BIG>::rsrc(bt, a.max_blocks * 4);
+    auto load_ids = [&](int stage) {
+        const int p = stage * GPS + (lane >> 1) * kTeams + team;
+        const int b = min(2 * p + (lane & 1), nblk - 1);
+        return __builtin_amdgcn_raw_buffer_load_b32(bt_rsrc, lane < 2 * (GPS / kTeams) ? 4 * b : 0, 0, 0);
+    };
+    auto id_of = [&](uint32_t ids, int i, int b) { return __builtin_amdgcn_readlane((int)ids, 2 * i + b); };
 
     // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
-    constexpr int GPS = kPrefillGroupsPerStage;
-    static_assert(GPS % kTeams == 0, "every team produces the same number of groups per stage");
     u32x4 prs[GPS / kTeams][NP];
     floatx4 pscs[GPS / kTeams];
     const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
     const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
-    auto produce_issue = [&](int p, u32x4 (&pr)[NP], floatx4& psc) {
+    auto produce_issue = [&](int p, int blockA, int blockB, u32x4 (&pr)[NP], floatx4& psc) {
         const bool okA = 2 * p < nblk, okB = 2 * p + 1 < nblk;
-        const int tA = next_idA * a.H_k + g;
-        const int tB = next_idB * a.H_k + g;
-        next_idA = bt[min(2 * (p + kTeams), nblk - 1)];    // wave-uniform addresses: scalar loads
-        next_idB = bt[min(2 * (p + kTeams) + 1, nblk - 1)];
+        const int tA = blockA * a.H_k + g;
+        const int tB = blockB * a.H_k + g;
+        // (one comparison for "is my block there": a choice between the two flags okA and okB
+        // would be made in vector registers, the very ones the loads issued a moment ago will
+        // fill, and cost a wait for those loads)
+        const int mine = wave & 1;                         // waves 0, 2: block A; waves 1, 3: block B
+        const bool ok_mine = 2 * p + mine < nblk;
+        const int t_mine = mine ? tB : tA;
         if (wave < 2) {
-            const int tk = wave == 0 ? tA : tB;
-            const bool ok = wave == 0 ? okA : okB;
 #pragma unroll
-            for (int j = 0; j < NL; ++j) pr[j] = loader.load_piece(a.cv.k_cache, tk, j, ok);
-            if constexpr (FP8) psc = loader.load_scales(a.cv.k_scale, tk, ok);
+            for (int j = 0; j < NL; ++j) pr[j] = loader.load_piece(a.cv.k_cache, t_mine, j, ok_mine);
+            if constexpr (FP8) psc = loader.load_scales(a.cv.k_scale, t_mine, ok_mine);
         } else {
 #pragma unroll
             for (int jj = 0; jj < NLH; ++jj) {
@@ -239,8 +250,7 @@ prefill_chunk_kernel(const PrefillArgs a)
                     pr[2 * jj + 1] = loader.load_piece(a.cv.v_cache, tB, vj0 + jj, okB);
                 }
             }
-            if constexpr (FP8)
-                psc = loader.load_scales(a.cv.v_scale, wave == 2 ? tA : tB, wave == 2 ? okA : okB);
+            if constexpr (FP8) psc = loader.load_scales(a.cv.v_scale, t_mine, ok_mine);
         }
     };
     auto produce_store = [&](int p, unsigned char* st, const u32x4 (&pr)[NP], const floatx4& psc) {
@@ -339,9 +349,14 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int num_stages = (num_groups + GPS - 1) / GPS;
     auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
     // (sub-group `sub` of a stage belongs to team sub % kTeams; a wave keeps registers for its own)
+    uint32_t ids = load_ids(0);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub % kTeams == team && sub < num_groups) produce_issue(sub, prs[sub / kTeams], pscs[sub / kTeams]);
+        if (sub % kTeams == team && sub < num_groups)
+            produce_issue(sub, id_of(ids, sub / kTeams, 0), id_of(ids, sub / kTeams, 1), prs[sub / kTeams],
+                          pscs[sub / kTeams]);
+    ids = load_ids(1);
+    uint32_t ids_next = load_ids(2);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
         if (sub % kTeams == team && sub < num_groups)
@@ -349,7 +364,8 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
         if (sub % kTeams == team && GPS + sub < num_groups)
-            produce_issue(GPS + sub, prs[sub / kTeams], pscs[sub / kTeams]);
+            produce_issue(GPS + sub, id_of(ids, sub / kTeams, 0), id_of(ids, sub / kTeams, 1),
+                          prs[sub / kTeams], pscs[sub / kTeams]);
     __syncthreads();
     for (int si = 0; si < num_stages; ++si) {
 #pragma unroll
@@ -363,10 +379,23 @@ prefill_chunk_kernel(const PrefillArgs a)
             if (sub % kTeams == team && gn < num_groups)
                 produce_store(gn, slot(si + 1, sub), prs[sub / kTeams], pscs[sub / kTeams]);
         }
+        // the numbers fetched a stage ago go to scalar registers before anything new is issued,
+        // so that taking them waits for nothing younger than the tiles just stored
+        int blk[GPS / kTeams][2];
+#pragma unroll
+        for (int i = 0; i < GPS / kTeams; ++i) {
+            blk[i][0] = id_of(ids_next, i, 0);
+            blk[i][1] = id_of(ids_next, i, 1);
+            // (pinned here: moved down to their uses, each would wait for the loads issued before it)
+            asm volatile("" : "+s"(blk[i][0]), "+s"(blk[i][1]));
+        }
+        ids_next = load_ids(si + 3);
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int g2 = (si + 2) * GPS + sub;
-            if (sub % kTeams == team && g2 < num_groups) produce_issue(g2, prs[sub / kTeams], pscs[sub / kTeams]);
+            if (sub % kTeams == team && g2 < num_groups)
+                produce_issue(g2, blk[sub / kTeams][0], blk[sub / kTeams][1], prs[sub / kTeams],
+                              pscs[sub / kTeams]);
         }
         // stage si+1 is complete, and nobody still reads stage si
         __syncthreads();
