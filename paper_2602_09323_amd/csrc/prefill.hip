@@ -9,9 +9,10 @@
 //     at NR = 2), all of the same (sequence, KV head) pair.
 //   * The pair's K/V stream, two 16-token blocks (a group) at a time, through a double-buffered
 //     LDS stage in matrix-core operand order, already converted to fp16.  The waves form two
-//     producer teams that take alternate groups; in a team wave 0 brings block A's K, wave 1
-//     block B's K, waves 2 and 3 the V pieces of both blocks (and zero the V entries and scales
-//     of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
+//     producer teams that share a stage's groups three to one (the first team's waves are the
+//     older ones on their SIMDs and get through a stage sooner); in a team wave 0 brings block
+//     A's K, wave 1 block B's K, waves 2 and 3 the V pieces of both blocks (and zero the V entries
+//     and scales of tokens that are not in the cache, so stale bytes cannot reach an accumulator).
 //     All eight then read their operands back with 16-byte LDS loads, conflict-free, and run the
 //     online-softmax update of attn_tile.hpp's arithmetic on each of their tiles.  One barrier
 //     per stage of four groups; the global loads of the stage after next are in flight while a
@@ -44,6 +45,8 @@ struct PrefillArgs {
 
 constexpr int kPrefillWaves = 8;                // two teams of four producer roles
 constexpr int kPrefillGroupsPerStage = 4;      // two-block groups between two barriers
+// Groups of a stage produced by the first team (waves 0-3); the second team takes the rest.
+constexpr int kPrefillFirstTeamGroups = 3;
 constexpr int kPrefillCUs = 256;               // MI355X: the launch shape is planned for its CU count
 
 // Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
@@ -143,7 +146,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int lane = threadIdx.x & 63;
     const int wave_id = wave_uniform((int)(threadIdx.x >> 6));
     const int wave = wave_id & 3;                      // producer role inside its team
-    const int team = wave_id >> 2;                     // team t produces the groups p with p % kTeams == t
+    const int team = wave_id >> 2;                     // which groups of a stage it produces: below
     const int n = lane & 15, grp = lane >> 4;
     // all workgroups of a (sequence, KV head) pair on one XCD (ids go round-robin over 8 XCDs)
     const int k8 = blockIdx.x >> 3;
@@ -205,27 +208,33 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- block numbers: the team's groups of a stage are p = stage * GPS + i * kTeams + team; lane
-    // 2i + b fetches the number of block b of group i, in ONE vector load per stage that is issued a
-    // whole stage before the tile loads it serves and ahead of the tile loads of the stage before
-    // (the vector-memory counter is in order: by the time those tiles have been waited for, the
-    // numbers are back).  Fetched where they are needed -- through the scalar unit or not -- their
-    // latency sat between two tile loads and again in front of the barrier, every stage.
+    // ---- which team produces which group of a stage.  The two waves of a SIMD do not get equal
+    // shares of it: the older one (a wave of the first team) is through with a stage's groups well
+    // before the younger one, so the first team produces more of the next stage.
     constexpr int GPS = kPrefillGroupsPerStage;
-    constexpr int kTeams = kPrefillWaves / 4;
-    static_assert(GPS % kTeams == 0, "every team produces the same number of groups per stage");
+    constexpr int kFirst = kPrefillFirstTeamGroups;           // sub-groups 0 .. kFirst-1: team 0
+    constexpr int kOwn = kFirst > GPS - kFirst ? kFirst : GPS - kFirst;   // most groups a wave holds
+    static_assert(kFirst >= 1 && kFirst <= GPS, "the first team produces at least one group");
+    auto owner = [](int sub) { return sub < kFirst ? 0 : 1; };
+    auto own_index = [](int sub) { return sub < kFirst ? sub : sub - kFirst; };
+    // ---- block numbers: lane 2i + b fetches the number of block b of the team's i-th group, in ONE
+    // vector load per stage that is issued a whole stage before the tile loads it serves and ahead
+    // of the tile loads of the stage before (the vector-memory counter is in order: by the time
+    // those tiles have been waited for, the numbers are back).  Fetched where they are needed --
+    // through the scalar unit or not -- their latency sat between two tile loads and again in
+    // front of the barrier, every stage.
     const __amdgpu_buffer_rsrc_t bt_rsrc = TileLoader<HEAD_DIM, KV, BIG>::rsrc(bt, a.max_blocks * 4);
     auto load_ids = [&](int stage) {
-        const int p = stage * GPS + (lane >> 1) * kTeams + team;
+        const int p = stage * GPS + (team == 0 ? 0 : kFirst) + (lane >> 1);
         const int b = min(2 * p + (lane & 1), nblk - 1);
-        return __builtin_amdgcn_raw_buffer_load_b32(bt_rsrc, lane < 2 * (GPS / kTeams) ? 4 * b : 0, 0, 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(bt_rsrc, lane < 2 * kOwn ? 4 * b : 0, 0, 0);
     };
     auto id_of = [&](uint32_t ids, int i, int b) { return __builtin_amdgcn_readlane((int)ids, 2 * i + b); };
 
     // ---- producer side: this wave's pieces of group p
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
-    u32x4 prs[GPS / kTeams][NP];
-    floatx4 pscs[GPS / kTeams];
+    u32x4 prs[kOwn][NP];
+    floatx4 pscs[kOwn];
     const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
     const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
     auto produce_issue = [&](int p, int blockA, int blockB, u32x4 (&pr)[NP], floatx4& psc) {
@@ -348,24 +357,24 @@ prefill_chunk_kernel(const PrefillArgs a)
     // A stage holds GPS consecutive groups; one barrier per stage.
     const int num_stages = (num_groups + GPS - 1) / GPS;
     auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
-    // (sub-group `sub` of a stage belongs to team sub % kTeams; a wave keeps registers for its own)
+    // (a wave keeps registers for the sub-groups of its own team)
     uint32_t ids = load_ids(0);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub % kTeams == team && sub < num_groups)
-            produce_issue(sub, id_of(ids, sub / kTeams, 0), id_of(ids, sub / kTeams, 1), prs[sub / kTeams],
-                          pscs[sub / kTeams]);
+        if (owner(sub) == team && sub < num_groups)
+            produce_issue(sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1), prs[own_index(sub)],
+                          pscs[own_index(sub)]);
     ids = load_ids(1);
     uint32_t ids_next = load_ids(2);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub % kTeams == team && sub < num_groups)
-            produce_store(sub, slot(0, sub), prs[sub / kTeams], pscs[sub / kTeams]);
+        if (owner(sub) == team && sub < num_groups)
+            produce_store(sub, slot(0, sub), prs[own_index(sub)], pscs[own_index(sub)]);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (sub % kTeams == team && GPS + sub < num_groups)
-            produce_issue(GPS + sub, id_of(ids, sub / kTeams, 0), id_of(ids, sub / kTeams, 1),
-                          prs[sub / kTeams], pscs[sub / kTeams]);
+        if (owner(sub) == team && GPS + sub < num_groups)
+            produce_issue(GPS + sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1),
+                          prs[own_index(sub)], pscs[own_index(sub)]);
     __syncthreads();
     for (int si = 0; si < num_stages; ++si) {
 #pragma unroll
@@ -376,14 +385,14 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int gn = (si + 1) * GPS + sub;
-            if (sub % kTeams == team && gn < num_groups)
-                produce_store(gn, slot(si + 1, sub), prs[sub / kTeams], pscs[sub / kTeams]);
+            if (owner(sub) == team && gn < num_groups)
+                produce_store(gn, slot(si + 1, sub), prs[own_index(sub)], pscs[own_index(sub)]);
         }
         // the numbers fetched a stage ago go to scalar registers before anything new is issued,
         // so that taking them waits for nothing younger than the tiles just stored
-        int blk[GPS / kTeams][2];
+        int blk[kOwn][2];
 #pragma unroll
-        for (int i = 0; i < GPS / kTeams; ++i) {
+        for (int i = 0; i < kOwn; ++i) {
             blk[i][0] = id_of(ids_next, i, 0);
             blk[i][1] = id_of(ids_next, i, 1);
             // (pinned here: moved down to their uses, each would wait for the loads issued before it)
@@ -393,9 +402,9 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int g2 = (si + 2) * GPS + sub;
-            if (sub % kTeams == team && g2 < num_groups)
-                produce_issue(g2, blk[sub / kTeams][0], blk[sub / kTeams][1], prs[sub / kTeams],
-                              pscs[sub / kTeams]);
+            if (owner(sub) == team && g2 < num_groups)
+                produce_issue(g2, blk[own_index(sub)][0], blk[own_index(sub)][1], prs[own_index(sub)],
+                              pscs[own_index(sub)]);
         }
         // stage si+1 is complete, and nobody still reads stage si
         __syncthreads();
