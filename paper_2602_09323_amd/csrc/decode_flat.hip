@@ -764,11 +764,13 @@ flat_merge_kernel(const FlatArgs a)
     constexpr int E = HEAD_DIM / 64;
     constexpr int kSpec = 8;
     constexpr int kStep = WIDE ? 4 : 1;                 // distance between a wavefront's partials
-    // a prepared schedule that is not the expected one: the split kernel did nothing, nor does this
-    if (a.sched && wave_uniform((int)a.sched[0]) != (int)a.sched_tag) return;
+    // Every load whose address does not depend on loaded data is issued before the first branch --
+    // the schedule's tag, the pair's count, the length, the first 64 (max, sum) pairs and the first
+    // kSpec partial rows -- so that the kernel is two memory round trips long, not one per check.
     const int wave = wave_uniform((int)(threadIdx.x >> 6));
-    const int row = WIDE ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;   // seq * H_q + head
-    if (row >= a.num_seqs * a.H_q) return;              // (WIDE: never, the grid is the row count)
+    const int rows = a.num_seqs * a.H_q;
+    const int row_id = WIDE ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;   // seq * H_q + head
+    const int row = min(row_id, rows - 1);              // (a surplus wavefront reads the last row)
     const int first = WIDE ? wave : 0;                  // this wavefront's first partial
     const int lane = threadIdx.x & 63;
     const int seq = row / a.H_q;
@@ -778,6 +780,10 @@ flat_merge_kernel(const FlatArgs a)
     const float* es = a.exp_sums + base;
     const float* po = a.tmp_out + base * HEAD_DIM + lane;
 
+    const uint32_t* tag_at = a.sched ? a.sched : reinterpret_cast<const uint32_t*>(a.counts);
+    const uint32_t tag = *tag_at;
+    const int t = a.context_lens[seq];
+    int count = a.counts[seq * a.H_k + g];
     float o_spec[kSpec][E];
 #pragma unroll
     for (int j = 0; j < kSpec; ++j) {
@@ -787,8 +793,12 @@ flat_merge_kernel(const FlatArgs a)
     }
     const float ml_l = lane < a.max_slots ? ml[lane] : 0.0f;
     const float es_l = lane < a.max_slots ? es[lane] : 0.0f;
-    const int t = a.context_lens[seq];
-    int count = a.counts[seq * a.H_k + g];
+    // (the three scalar loads are taken here, together: left to the compiler, each moves down to
+    // its first use, behind a branch that waits for the one before)
+    asm volatile("" : "+s"(count) : "s"(tag), "s"(t));
+    // a prepared schedule that is not the expected one: the split kernel wrote nothing, nor does this
+    if (a.sched && tag != a.sched_tag) return;
+    if (row_id >= rows) return;                         // (WIDE: never, the grid is the row count)
     if (t <= 0) count = 0;
     count = wave_uniform(min(count, a.max_slots));
 
