@@ -197,7 +197,7 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  * prepare only enqueues a kernel on hip_stream: the launches that use the schedule must be ordered
  * after it (same stream, or an event), and two launches that use one schedule may overlap.
  * A schedule prepared for another shape, plan or mode is recognised on the device by a tag: such a
- * launch reads and writes nothing except word 1 of the schedule, which it sets to 1 (prepare
+ * launch writes nothing except word 1 of the schedule, which it sets to 1 (prepare
  * resets it to 0), and `out` keeps its old contents.  A schedule whose tables or lengths have
  * changed since it was prepared is NOT recognised: prepare again.  Host-side errors as for
  * coopt_paged_gqa_decode_step, COOPT_ERR_WORKSPACE also for a schedule buffer that is too small or
