@@ -198,35 +198,54 @@ partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restri
     const int wave = threadIdx.x >> 6;
     const int sub = lane / LPR, piece = lane % LPR;
     const int seq = row / H_q;
-    const int t = context_lens[seq];
-    const int nparts = min((t + partition_size - 1) / partition_size, max_parts);
     half_t* out_row = out + (size_t)row * HEAD_DIM;
+    const float* ml = max_logits + (size_t)row * max_parts;
+    const float* es = exp_sums + (size_t)row * max_parts;
+    const float* po = tmp_out + (size_t)row * max_parts * HEAD_DIM + 4 * piece;
+    // Everything whose address does not depend on the length is asked for before the length is
+    // back: the first 64 (max, sum) pairs and this lane's rows of the first 64 partials (slots
+    // beyond the sequence's partitions hold whatever the caller left there: selected away below).
+    constexpr int kRows = 64 / (4 * PPW);       // rows per lane and 64 partials
+    const int t = context_lens[seq];
+    const float ml0 = lane < max_parts ? ml[lane] : -INFINITY;
+    const float es0 = lane < max_parts ? es[lane] : 0.0f;
+    floatx4 x0[kRows];
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        const int j = (i * 4 + wave) * PPW + sub;
+        x0[i] = *reinterpret_cast<const floatx4*>(po + (size_t)min(j, max_parts - 1) * HEAD_DIM);
+    }
+    const int nparts = min((t + partition_size - 1) / partition_size, max_parts);
     if (nparts <= 0) {                         // the whole workgroup takes this branch together
         if (threadIdx.x < HEAD_DIM) out_row[threadIdx.x] = (half_t)0.0f;
         return;
     }
-    const float* ml = max_logits + (size_t)row * max_parts;
-    const float* es = exp_sums + (size_t)row * max_parts;
-    const float* po = tmp_out + (size_t)row * max_parts * HEAD_DIM + 4 * piece;
 
-    float M = -INFINITY;
-    for (int p = lane; p < nparts; p += 64) M = fmaxf(M, ml[p]);
+    float M = lane < nparts ? ml0 : -INFINITY;
+    for (int p = 64 + lane; p < nparts; p += 64) M = fmaxf(M, ml[p]);
 #pragma unroll
     for (int s = 32; s > 0; s >>= 1) M = fmaxf(M, __shfl_xor(M, s));
     floatx4 o = {0.f, 0.f, 0.f, 0.f};
     float W = 0.0f;
     for (int base = 0; base < nparts; base += 64) {
         const int p = base + lane;
-        const float wv = p < nparts ? es[p] * __expf(ml[p] - M) : 0.0f;   // weight of partial base+lane
+        float wv = 0.0f;                                                   // weight of partial base+lane
+        if (p < nparts) wv = base == 0 ? es0 * __expf(ml0 - M) : es[p] * __expf(ml[p] - M);
         W += wv;
         const int cnt = min(64, nparts - base);
 #pragma unroll
-        for (int i = 0; i < 64 / (4 * PPW); ++i) {
+        for (int i = 0; i < kRows; ++i) {
             const int j = (i * 4 + wave) * PPW + sub;                      // < 64
             const float wj = __shfl(wv, j);
             const bool ok = j < cnt;
-            const floatx4 x = *reinterpret_cast<const floatx4*>(po + (size_t)(base + (ok ? j : 0)) * HEAD_DIM);
-            o += x * (ok ? wj : 0.0f);
+            floatx4 x;
+            if (base == 0) {
+                x = x0[i];
+            } else {
+                x = *reinterpret_cast<const floatx4*>(po + (size_t)(base + (ok ? j : 0)) * HEAD_DIM);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] += ok ? x[c] * wj : 0.0f;     // (an unused slot may hold NaN)
         }
     }
 #pragma unroll
