@@ -51,6 +51,30 @@ def test_chunk_written_on_device_then_attended(oracle_mod):
     assert_close(_hip_prefill(w, devc), ref, "cfg4/16")
 
 
+@pytest.mark.parametrize("kv_dtype,chunks", [("e4m3", [512] * 8), ("fp16", [512, 500, 17, 512, 1, 300, 512, 496])])
+def test_two_launch_split_every_row(oracle_mod, kv_dtype, chunks):
+    """As many workgroups as the full configuration (64 pairs, up to 160 tiles each), so the entry
+    point splits the work into its two launches, over a short history so that the oracle can check
+    every row; the second case has a different chunk length per sequence."""
+    S, H_q, H_k, d = len(chunks), 40, 8, 128
+    history = [48, 0, 100, 16, 33, 64, 7, 250]
+    lens = [h + c for h, c in zip(history, chunks)]
+    w = workloads.make_custom("split", seed=77, S=S, H_q=H_q, H_k=H_k, d=d, B=16, NB=512,
+                              context_lens=lens, kv_dtype=kv_dtype)
+    query_start = np.zeros(S + 1, dtype=np.int32)
+    query_start[1:] = np.cumsum(chunks)
+    rows = int(query_start[-1])
+    q = np.random.default_rng(78).standard_normal((rows, H_q, d), dtype=np.float32).astype(np.float16)
+    cache = oracle_fill(oracle_mod, w)
+    ref = oracle_mod.paged_gqa_prefill_chunk(q, *cache, w.block_tables, w.context_lens, query_start, H_q=H_q,
+                                             H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale)
+    out = torch.full((rows, H_q, d), -7.0, dtype=torch.float16, device="cuda")
+    coopt.paged_gqa_prefill_chunk(dev(q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables),
+                                  dev(w.context_lens), dev(query_start), rows, max(chunks), out, shape_of(w))
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy().astype(np.float64), ref, f"two launches {kv_dtype} {chunks}")
+
+
 def test_chunked_prefill_full_size_sampled_rows(oracle_mod):
     """Full configuration; the oracle computes a sample of rows (first, last, tile edges, random)."""
     w = workloads.make(4)
