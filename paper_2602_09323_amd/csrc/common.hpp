@@ -46,6 +46,10 @@ inline int check_shape(const coopt_shape* sh)
     if (sh->num_q_heads % sh->num_kv_heads != 0) return COOPT_ERR_SHAPE;
     if (sh->num_q_heads / sh->num_kv_heads > 16) return COOPT_ERR_SHAPE;
     if (sh->num_blocks <= 0 || sh->max_blocks_per_seq <= 0) return COOPT_ERR_SHAPE;
+    // index arithmetic in the kernels is 32-bit where the products below fit
+    if (sh->num_seqs > (1 << 20) || sh->num_q_heads > (1 << 12)) return COOPT_ERR_SHAPE;
+    if (sh->max_blocks_per_seq > (1 << 24)) return COOPT_ERR_SHAPE;
+    if ((long long)sh->num_blocks * sh->num_kv_heads > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     if (sh->kv_dtype != COOPT_KV_FP16 && sh->kv_dtype != COOPT_KV_E4M3) return COOPT_ERR_SHAPE;
     return COOPT_OK;
 }

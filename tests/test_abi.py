@@ -61,7 +61,10 @@ def _shape(**kw):
 
 @pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block_size=32), dict(num_q_heads=41),
                                  dict(num_q_heads=8 * 17), dict(kv_dtype=2), dict(num_blocks=0),
-                                 dict(num_kv_heads=0)])
+                                 dict(num_kv_heads=0), dict(num_seqs=(1 << 20) + 1),
+                                 dict(num_q_heads=8192, num_kv_heads=1024),
+                                 dict(max_blocks_per_seq=(1 << 24) + 1),
+                                 dict(num_blocks=1 << 29, num_kv_heads=8)])
 def test_unsupported_shapes_are_refused_without_launch(lib, bad):
     sh = _shape(**bad)
     one = ctypes.c_void_p(16)          # never dereferenced: validation comes first
