@@ -47,21 +47,20 @@ struct QuantRow {
     float k_scale, v_scale;
 };
 
-// Quantises the K and V rows (HEAD_DIM fp16 values each) and stores codes and scales into tile
-// `tile` (= physical block * H_k + KV head) at token offset `off`.  Returns what it stored.
+// Quantises one K row and one V row (HEAD_DIM values each, lane i holding elements i*E .. i*E+E-1
+// as binary32) and stores codes and scales into tile `tile` (= physical block * H_k + KV head) at
+// token offset `off`.  Returns what it stored.
 template <int HEAD_DIM>
-__device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
-    const half_t* __restrict__ k_row, const half_t* __restrict__ v_row, size_t tile, int off, int lane,
+__device__ __forceinline__ QuantRow<HEAD_DIM> quantise_values_to_cache(
+    const float (&kx)[HEAD_DIM / 64], const float (&vx)[HEAD_DIM / 64], size_t tile, int off, int lane,
     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache, float* __restrict__ k_scale,
     float* __restrict__ v_scale)
 {
     constexpr int E = HEAD_DIM / 64;
     QuantRow<HEAD_DIM> qr;
-    float x[E], y[E];
+    float y[E];
     // ---- K tile [d/16][16 tokens][16]: the lane's E dims are neighbours inside one 16-byte chunk
-#pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = (float)k_row[lane * E + e];
-    qr.k_scale = scale_row<E>(x, y);
+    qr.k_scale = scale_row<E>(kx, y);
     uint8_t* kdst = k_cache + tile * (kBlock * HEAD_DIM) + k_tile_index<1>(off, lane * E);
     if constexpr (E == 2) {
         qr.k_codes = encode_pair(y[0], y[1]);
@@ -73,9 +72,7 @@ __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
     if (lane == 0) k_scale[tile * kBlock + off] = qr.k_scale;
 
     // ---- V tile: token index innermost, one byte per (dim, token)
-#pragma unroll
-    for (int e = 0; e < E; ++e) x[e] = (float)v_row[lane * E + e];
-    qr.v_scale = scale_row<E>(x, y);
+    qr.v_scale = scale_row<E>(vx, y);
     uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
     if constexpr (E == 2) {
         qr.v_codes = encode_pair(y[0], y[1]);
@@ -87,6 +84,29 @@ __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
     }
     if (lane == 0) v_scale[tile * kBlock + off] = qr.v_scale;
     return qr;
+}
+
+// A lane's E elements of an fp16 row, widened.
+template <int HEAD_DIM>
+__device__ __forceinline__ void load_row_values(const half_t* __restrict__ row, int lane,
+                                                float (&x)[HEAD_DIM / 64])
+{
+    constexpr int E = HEAD_DIM / 64;
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = (float)row[lane * E + e];
+}
+
+// The same from the rows in memory (HEAD_DIM fp16 values each).
+template <int HEAD_DIM>
+__device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
+    const half_t* __restrict__ k_row, const half_t* __restrict__ v_row, size_t tile, int off, int lane,
+    uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache, float* __restrict__ k_scale,
+    float* __restrict__ v_scale)
+{
+    float kx[HEAD_DIM / 64], vx[HEAD_DIM / 64];
+    load_row_values<HEAD_DIM>(k_row, lane, kx);
+    load_row_values<HEAD_DIM>(v_row, lane, vx);
+    return quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
 }
 
 }  // namespace coopt

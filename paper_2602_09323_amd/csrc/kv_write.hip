@@ -28,15 +28,18 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // token * H_k + head
     if (row >= num_rows) return;
     const int tok = row / H_k, head = row - tok * H_k;
+    const int lane = threadIdx.x & 63;
+    // the rows are asked for together with the slot, not after it: one memory round trip
+    float kx[HEAD_DIM / 64], vx[HEAD_DIM / 64];
+    load_row_values<HEAD_DIM>(k + (size_t)row * HEAD_DIM, lane, kx);
+    load_row_values<HEAD_DIM>(v + (size_t)row * HEAD_DIM, lane, vx);
     const int64_t slot = slot_mapping[tok];
-    if (slot < 0 || in_skip_set(skip_set, tok)) return;         // Eq. 5: filtered token
+    const bool skip = in_skip_set(skip_set, tok);
+    if (slot < 0 || skip) return;                               // Eq. 5: filtered token
     const int64_t blk = slot / kBlock;
     const int off = (int)(slot - blk * kBlock);
-    const int lane = threadIdx.x & 63;
     const size_t tile = (size_t)(blk * H_k + head);
-
-    quantise_row_to_cache<HEAD_DIM>(k + (size_t)row * HEAD_DIM, v + (size_t)row * HEAD_DIM, tile, off,
-                                    lane, k_cache, v_cache, k_scale, v_scale);
+    quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
 }
 
 // ---- bulk form (prefill chunks, cache fills): many tokens per call.
