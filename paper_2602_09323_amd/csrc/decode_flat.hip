@@ -9,8 +9,8 @@
 //     The cut is made on a cost axis that charges a few group times for every (sequence, KV head)
 //     pair that ends inside a share; shares differ by at most one cost unit.  Context lengths live
 //     on the device, so every workgroup derives the schedule itself: one vector load of the
-//     lengths and wave scans.  There are no empty or short workgroups, and consecutive workgroup
-//     ids (which land on different XCDs) carry equal work.
+//     lengths and wave scans.  There are no empty or short workgroups; all shares carry equal
+//     work, and each XCD's workgroups take a contiguous eighth of them (share_of_workgroup).
 //   * A share may straddle the boundary between (sequence, KV head) pairs; the part in one pair is
 //     a segment.  The software pipeline runs across segment boundaries: tiles of the next pair are
 //     in flight while the current pair's last groups are consumed, the next pair's q operand waits
@@ -372,14 +372,14 @@ struct LiveSource {
     const FlatArgs& a;
     const FlatSchedule& sched;
     const FlatCut& cut;
-    int lane, x_begin, x_end;
+    int lane, share, x_begin, x_end;
     int nc = 0;
     int seq_l = 0, cfirst_l = 0, t_l = 0, g_l = 0, gi_l = 0, tile_l = -1;
     unsigned long long last_mask = 0;
 
     __device__ __forceinline__ LiveSource(const FlatArgs& args, const FlatSchedule& s, const FlatCut& c,
-                                          int lane_id, int xb, int xe)
-        : a(args), sched(s), cut(c), lane(lane_id), x_begin(xb), x_end(xe) {}
+                                          int lane_id, int share_id, int xb, int xe)
+        : a(args), sched(s), cut(c), lane(lane_id), share(share_id), x_begin(xb), x_end(xe) {}
     __device__ __forceinline__ int size() const { return x_end - x_begin; }
 
     __device__ __forceinline__ void load_chunk(int c0)
@@ -441,7 +441,7 @@ struct LiveSource {
                                g * (ng + a.pair_extra) + a.pair_extra;
         PartialSlot ps;
         ps.row0 = seq * a.H_q + g * a.G;
-        ps.slot = blockIdx.x - cut.wg_of(pair_first);
+        ps.slot = share - cut.wg_of(pair_first);
         // the pair's first workgroup also counts the pair's partials
         // (in the fused step the appending workgroups do the counting)
         ps.count_at = (ps.slot == 0 && !a.new_slots) ? seq * a.H_k + g : -1;
@@ -637,6 +637,17 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
     }
 }
 
+// Which share a workgroup takes.  Workgroup ids are dealt to the 8 XCDs round-robin; this gives the
+// workgroups of XCD x the x-th contiguous eighth of the shares, so that neighbouring shares -- which
+// read neighbouring KV heads' scale rows (two to a 128-byte line), the same q rows and the same
+// block-table rows -- meet in one L2 instead of fetching those lines from HBM once per XCD.  Any
+// dealing of workgroups to XCDs gives correct results: this is a bijection on [0, n).
+__device__ __forceinline__ int share_of_workgroup(int wg, int n)
+{
+    const int x = wg & 7, k = wg >> 3, q = n >> 3, r = n & 7;
+    return x * q + min(x, r) + k;
+}
+
 // One wave per workgroup.  The block numbers of up to 32 groups come from one gathered vector load
 // (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
 template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
@@ -655,13 +666,14 @@ flat_stream_kernel(const FlatArgs a)
         return;
     }
     if (ctotal == 0) return;
-    if ((int)blockIdx.x >= cut.nwg) return;
-    const int x_begin = sched.real_before(cut.begin(blockIdx.x), ctotal);
-    const int x_end = sched.real_before(cut.begin(blockIdx.x + 1), ctotal);
+    const int share = share_of_workgroup(blockIdx.x, a.decode_wgs);
+    if (share >= cut.nwg) return;
+    const int x_begin = sched.real_before(cut.begin(share), ctotal);
+    const int x_end = sched.real_before(cut.begin(share + 1), ctotal);
     if (x_begin >= x_end) return;           // a share that lies inside one pair's extra units
 
     extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // see launch_flat_depth
-    LiveSource src(a, sched, cut, lane, x_begin, x_end);
+    LiveSource src(a, sched, cut, lane, share, x_begin, x_end);
     stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
 }
 
@@ -674,7 +686,8 @@ flat_stream_prepared_kernel(const FlatArgs a)
     const int lane = threadIdx.x;
     // the tag, the share's size and its first 32 records are loaded together: one round trip
     const bool attends = (int)blockIdx.x < a.decode_wgs;
-    const uint32_t* region = a.sched + a.sched_regions + (size_t)(attends ? blockIdx.x : 0) * a.sched_stride;
+    const int share = attends ? share_of_workgroup(blockIdx.x, a.decode_wgs) : 0;
+    const uint32_t* region = a.sched + a.sched_regions + (size_t)share * a.sched_stride;
     sched_rec_t first = {~0u, ~0u, 0u, 0u};
     if (attends && lane < 32) first = *reinterpret_cast<const sched_rec_t*>(region + 4 + 4 * lane);
     const int count = wave_uniform((int)region[0]);
@@ -730,7 +743,7 @@ flat_prepare_kernel(const FlatArgs a)
     const int count = min(max(x_end - x_begin, 0), (a.sched_stride - 4) / 4);
     if (lane == 0) region[0] = (uint32_t)count;
     if (count == 0) return;
-    LiveSource src(a, sched, cut, lane, x_begin, x_begin + count);
+    LiveSource src(a, sched, cut, lane, (int)blockIdx.x, x_begin, x_begin + count);   // region = share
     for (int c0 = 0; c0 < count; c0 += 32) {
         src.load_chunk(c0);
         const int tile_b = __shfl_down(src.tile_l, 1);
