@@ -63,7 +63,9 @@ enum { COOPT_KV_FP16 = 0, COOPT_KV_E4M3 = 1 };
  * Problem shape.  Supported: head_dim 64 or 128; block_size 16; num_q_heads a multiple of
  * num_kv_heads (Opt-GQA, Eq. 7 needs an integer group size H_g = H_q/H_k) with H_g <= 16.
  * Sizes are 32-bit inside the kernels' index arithmetic: num_seqs <= 2^20, num_q_heads <= 2^12,
- * max_blocks_per_seq <= 2^24 (268 M tokens a sequence), num_blocks * num_kv_heads < 2^31;
+ * num_seqs * num_q_heads <= 2^27, max_blocks_per_seq <= 2^24 (268 M tokens a sequence),
+ * num_blocks * num_kv_heads < 2^31 (and, for the partitioned call, num_seqs * num_kv_heads *
+ * max_parts < 2^31);
  * anything beyond is COOPT_ERR_SHAPE.
  */
 typedef struct coopt_shape {

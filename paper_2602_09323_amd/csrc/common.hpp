@@ -49,6 +49,7 @@ inline int check_shape(const coopt_shape* sh)
     // index arithmetic in the kernels is 32-bit where the products below fit
     if (sh->num_seqs > (1 << 20) || sh->num_q_heads > (1 << 12)) return COOPT_ERR_SHAPE;
     if (sh->max_blocks_per_seq > (1 << 24)) return COOPT_ERR_SHAPE;
+    if ((long long)sh->num_seqs * sh->num_q_heads > (1LL << 27)) return COOPT_ERR_SHAPE;
     if ((long long)sh->num_blocks * sh->num_kv_heads > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     if (sh->kv_dtype != COOPT_KV_FP16 && sh->kv_dtype != COOPT_KV_E4M3) return COOPT_ERR_SHAPE;
     return COOPT_OK;
