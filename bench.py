@@ -34,13 +34,8 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # 256 MiB device copy: FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  The summaries
 # with the commands are under profiles/; the figures belong to the default decode plan.
 PMC_TRAFFIC = {
-    # (workload, schedule) -> counters of the kernel that `roofline` times
-    ("llama13b_gqa_fp8_decode", "prepared"): {
-        "fetch_kib": 36581.7, "fetch_scale": 2.0, "write_kib": 3105.5, "write_scale": 1.0,
-        "source": "profiles/flat_stream_prepared_kernel_llama13b_gqa_fp8_decode.md"},
-    ("llama13b_gqa_fp8_decode", "live"): {
-        "fetch_kib": 36317.7, "fetch_scale": 2.0, "write_kib": 3106.7, "write_scale": 1.0,
-        "source": "profiles/flat_stream_kernel_llama13b_gqa_fp8_decode.md"},
+    # (workload, launch mode) -> counters of the kernel that `roofline` times, and the hash of the
+    # kernel sources they were measured on (kernel_sources_sha16): quoted only while that matches
 }
 
 
@@ -58,14 +53,27 @@ def algorithmic_bytes(w):
             "per_token": per_token}
 
 
-def main():
+def kernel_sources_sha16():
+    """Hash of the sources the decode kernels are built from: counter figures in PMC_TRAFFIC are
+    only quoted for the code they were measured on."""
+    import hashlib
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2602_09323_amd", "csrc")
+    h = hashlib.sha256()
+    for name in ("common.hpp", "attn_tile.hpp", "kv_quant.hpp", "decode_internal.hpp", "decode_flat.hip"):
+        with open(os.path.join(here, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--config", type=int, default=None, choices=[0, 1, 2, 3, 4],
                     help="workload (1 = LLaMa-13B GQA FP8 decode, the headline configuration; "
-                         "4 = chunked prefill)")
+                         "4 = chunked prefill).  Without it the line is the headline configuration "
+                         "and carries the other configurations under `all_configs`")
     ap.add_argument("--path", choices=["balanced", "partitioned"], default="balanced",
                     help="decode through coopt_paged_gqa_decode (balanced split + merge) or through "
                          "coopt_paged_gqa_decode_partitioned + coopt_paged_gqa_reduce with the "
@@ -86,12 +94,21 @@ def main():
                          "coopt_gather_cached_kv of every sequence's whole context (one launch per "
                          "sequence), reported in GB/s against the HBM peak.  stream-read: the "
                          "read-only streaming probe over 2 GiB, every launch shape it tries")
+    ap.add_argument("--preroll", type=int, default=300,
+                    help="untimed launches of the step before the warm-up steps, so that a short run "
+                         "is not timed while the clocks are still coming up (disclosed in the line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="headline configuration only (no `all_configs`)")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain device copies of 256 MiB instead of the workload (the known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: this build has no multi-GPU path "
                  "(run with --gpus 1; the path shards by sequence or by KV head with no exchange inside attention)")
@@ -99,18 +116,20 @@ def main():
     import torch
     import paper_2602_09323_amd as coopt
     import workloads
-    from paper_2602_09323_amd.build import build, needs_build
+    from paper_2602_09323_amd import probe
+    from paper_2602_09323_amd.build import build
 
-    if not os.path.exists(coopt.lib_path()):
+    if not os.path.exists(coopt.lib_path()) or not os.path.exists(probe.lib_path()):
         build(force=True)
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU: the HIP path has no CPU fallback")
     coopt.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    plan = None
     if args.plan:
         names = [f for f, _ in coopt.DecodePlan._fields_]
-        coopt.set_decode_plan(**dict(zip(names, [int(x) for x in args.plan.split(",")])))
+        plan = coopt.make_decode_plan(**dict(zip(names, [int(x) for x in args.plan.split(",")])))
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -122,13 +141,49 @@ def main():
         return
 
     if args.op == "stream-read":
-        print(json.dumps(stream_read_ceiling(coopt, torch, dev, detail=True)), flush=True)
+        print(json.dumps(stream_read_ceiling(probe, torch, dev, detail=True)), flush=True)
         return
-    w = workloads.make(args.config)
+    cfg = 1 if args.config is None else args.config
+    w = workloads.make(cfg)
     if args.op == "gather":
-        return bench_gather(args, w, coopt, torch, dev)
-    if args.config == 4:
-        return bench_prefill(args, w, coopt, torch, dev)
+        print(json.dumps(bench_gather(args, w, coopt, torch, dev)), flush=True)
+        return
+    if cfg == 4:
+        print(json.dumps(bench_prefill(args, w, coopt, torch, dev, args.steps, args.warmup,
+                                       not args.no_cpu_baseline)), flush=True)
+        return
+    result = bench_decode(args, w, coopt, probe, torch, dev, plan, args.path, args.steps, args.warmup,
+                          cpu=not args.no_cpu_baseline, stream=True)
+    if args.config is None and not args.no_all_configs:
+        # the other configurations, each for at least 200 steps: kernel, roofline fraction, step
+        steps = max(args.steps, 200)
+        rows = [compact(result, "balanced")]
+        for c, path in ((2, "balanced"), (3, "balanced"), (3, "partitioned")):
+            del w
+            torch.cuda.empty_cache()
+            w = workloads.make(c)
+            r = bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, max(args.warmup, 20),
+                             cpu=False, stream=False)
+            rows.append(compact(r, path))
+        del w
+        torch.cuda.empty_cache()
+        r = bench_prefill(args, workloads.make(4), coopt, torch, dev, steps, max(args.warmup, 20), False)
+        rows.append(compact(r, "prefill"))
+        result["all_configs"] = rows
+    print(json.dumps(result), flush=True)
+
+
+def compact(r, path):
+    rf = r["roofline"]
+    return {"workload": r["config"]["workload"], "path": path, "kernel": rf["kernel"].split(" ")[0],
+            "kernel_us": rf.get("kernel_us_mean", round(rf.get("kernel_ms_mean", 0.0) * 1e3, 3)),
+            "bound": rf["bound"], "achieved": rf["achieved"], "unit": rf["unit"], "frac": rf["frac"],
+            "step_us": round(r["ms_per_step"] * 1e3, 3), "steps": r["steps"]}
+
+
+def bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, warmup, cpu, stream):
+    """One decode workload: whole-step time over `steps` steps, the dominant kernel alone, and the
+    step's output against the oracle (`cpu` = time the oracle and compare)."""
     ab = algorithmic_bytes(w)
     e4m3 = w.kv_dtype == "e4m3"
     shape = coopt.Shape(w.S, w.H_q, w.H_k, w.d, w.B, w.NB, w.max_blocks,
@@ -148,7 +203,7 @@ def main():
     s_new = to_dev(w.slots[new])
     q, bt, lens = to_dev(w.q.view(np.uint16)), to_dev(w.block_tables), to_dev(w.context_lens)
     out = torch.zeros((w.S, w.H_q, w.d), dtype=torch.float16, device=dev)
-    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape, plan)), dtype=torch.uint8, device=dev)
 
     pools = []
     for _ in range(layers):
@@ -162,8 +217,9 @@ def main():
             coopt.kv_cache_write_fp16(k_hist, v_hist, s_hist, kc, vc, shape)
         pools.append((kc, vc, ks, vs))
     torch.cuda.synchronize()
+    del k_hist, v_hist, s_hist
 
-    partitioned = args.path == "partitioned"
+    partitioned = path == "partitioned"
     if partitioned:
         P = w.partition_size or 512
         max_parts = (w.max_blocks * w.B + P - 1) // P
@@ -174,48 +230,49 @@ def main():
     def attend(i, reduce=True):
         kc, vc, ks, vs = pools[i % layers]
         if not partitioned:
-            coopt.paged_gqa_decode(q, kc, vc, ks, vs, bt, lens, out, ws, shape)
+            coopt.paged_gqa_decode(q, kc, vc, ks, vs, bt, lens, out, ws, shape, plan)
             return
         coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens, P, tmp_out, max_logits,
-                                           exp_sums, max_parts, shape)
+                                           exp_sums, max_parts, shape, plan)
         if reduce:
             coopt.paged_gqa_reduce(tmp_out, max_logits, exp_sums, lens, P, max_parts, out, shape)
 
     fused = args.write == "fused" and not partitioned
     prepared = args.schedule == "prepared" and not partitioned
     if prepared:
-        sched = torch.zeros(coopt.decode_schedule_bytes(shape), dtype=torch.uint8, device=dev)
-        sched_split = torch.zeros_like(sched)            # plain-decode schedule for the kernel-alone timing
-        coopt.decode_schedule_prepare(bt, lens, None, sched_split, shape)
+        sched = torch.zeros(coopt.decode_schedule_bytes(shape, plan), dtype=torch.uint8, device=dev)
+        sched_plain = torch.zeros_like(sched)            # plain-decode schedule: the attention-only timing
+        coopt.decode_schedule_prepare(bt, lens, None, sched_plain, shape, plan)
+
+    def write_new(kc, vc, ks, vs):
+        if e4m3:
+            coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
+        else:
+            coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
 
     def step(i):
         kc, vc, ks, vs = pools[i % layers]
         if prepared:
             if i % layers == 0:                          # one decoding step of the model begins
-                coopt.decode_schedule_prepare(bt, lens, s_new if fused else None, sched, shape)
+                coopt.decode_schedule_prepare(bt, lens, s_new if fused else None, sched, shape, plan)
             if not fused:
-                if e4m3:
-                    coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
-                else:
-                    coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
+                write_new(kc, vc, ks, vs)
             coopt.paged_gqa_decode_scheduled(k_new if fused else None, v_new if fused else None,
                                              s_new if fused else None, q, kc, vc, ks, vs, lens, out,
-                                             ws, sched, shape)
+                                             ws, sched, shape, plan)
             return
         if fused:
-            coopt.paged_gqa_decode_step(k_new, v_new, s_new, q, kc, vc, ks, vs, bt, lens, out, ws, shape)
+            coopt.paged_gqa_decode_step(k_new, v_new, s_new, q, kc, vc, ks, vs, bt, lens, out, ws,
+                                        shape, plan)
             return
-        if e4m3:
-            coopt.kv_cache_write_fp8(k_new, v_new, s_new, kc, vc, ks, vs, shape)
-        else:
-            coopt.kv_cache_write_fp16(k_new, v_new, s_new, kc, vc, shape)
+        write_new(kc, vc, ks, vs)
         attend(i)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(fn, count):
         """Mean GPU time per call of fn(i), i = 0..count-1, in ms.  The calls are captured into HIP
-        graphs of one rotation over the pools each (the step is ~3 launches of a few us, so eager
+        graphs of one rotation over the pools each (the step is ~2 launches of a few us, so eager
         launches from Python would measure the host, not the GPU) and replayed back to back on the
         current stream between two events."""
         if args.no_graph:
@@ -250,60 +307,73 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / count
 
-    # ---- whole step: W warm-up steps, then exactly K steps between two synchronisations
-    for i in range(args.warmup):
+    # ---- untimed pre-roll (the first launches after idle run while the clocks come up), then W
+    # warm-up steps, then exactly K steps between two synchronisations
+    if args.preroll > 0:
+        timed(step, args.preroll)
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    step_ms = timed(step, args.steps)
+    step_ms = timed(step, steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
+    got = out.cpu().numpy().astype(np.float64)           # the last timed step's output rows
 
-    # ---- dominant kernel alone (the balanced split kernel of the decode call): the same rotation
-    # over pools, launches back to back on the stream, one event pair around them.
-    plan = coopt.get_decode_plan()
+    # ---- dominant kernel alone: the launch the step itself runs (with a fused write, the decode
+    # launch that also appends the new tokens), same rotation over pools, launches back to back on
+    # the stream, one event pair around them; and the attention-only launch beside it.
+    ksteps = max(steps, 200)
 
     def kern(i):
         if partitioned:
             return attend(i, reduce=False)
         kc, vc, ks, vs = pools[i % layers]
         if prepared:
-            coopt.paged_gqa_decode_scheduled(None, None, None, q, kc, vc, ks, vs, lens, None, ws,
-                                             sched_split, shape)
+            coopt.paged_gqa_decode_scheduled(k_new if fused else None, v_new if fused else None,
+                                             s_new if fused else None, q, kc, vc, ks, vs, lens, None,
+                                             ws, sched, shape, plan)
         else:
-            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape)
-    kern_us = timed(kern, args.steps) * 1e3
+            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens, ws, shape, plan)
+
+    def kern_plain(i):
+        kc, vc, ks, vs = pools[i % layers]
+        coopt.paged_gqa_decode_scheduled(None, None, None, q, kc, vc, ks, vs, lens, None, ws,
+                                         sched_plain, shape, plan)
+    kern_us = timed(kern, ksteps) * 1e3
+    plain_us = timed(kern_plain, ksteps) * 1e3 if (prepared and fused) else None
 
     # the same kernel on empty contexts: what one launch costs before any byte moves (the gap
     # between dependent launches in a stream plus the schedule prologue)
     lens_zero = torch.zeros_like(lens)
+    if prepared:
+        sched_empty = torch.zeros_like(sched)
+        coopt.decode_schedule_prepare(bt, lens_zero, None, sched_empty, shape, plan)
 
     def kern_empty(i):
         kc, vc, ks, vs = pools[i % layers]
         if partitioned:
             coopt.paged_gqa_decode_partitioned(q, kc, vc, ks, vs, bt, lens_zero, P, tmp_out,
-                                               max_logits, exp_sums, max_parts, shape)
+                                               max_logits, exp_sums, max_parts, shape, plan)
         elif prepared:
             coopt.paged_gqa_decode_scheduled(None, None, None, q, kc, vc, ks, vs, lens_zero, None, ws,
-                                             sched_empty, shape)
+                                             sched_empty, shape, plan)
         else:
-            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape)
-    if prepared:
-        sched_empty = torch.zeros_like(sched)
-        coopt.decode_schedule_prepare(bt, lens_zero, None, sched_empty, shape)
-    floor_us = timed(kern_empty, min(args.steps, 200)) * 1e3
+            coopt.paged_gqa_decode_split(q, kc, vc, ks, vs, bt, lens_zero, ws, shape, plan)
+    floor_us = timed(kern_empty, 200) * 1e3
 
     kv_gbs = ab["kv"] / (step_ms * 1e-3) / 1e9
+    plan_used = (plan or coopt.default_decode_plan()).as_dict()
     result = {
         "metric": "paged GQA decode: achieved KV HBM GB/s per step (us/step in ms_per_step)",
-        "value": round(kv_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(step_ms, 6),
+        "value": round(kv_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(step_ms, 6),
         "us_per_step": round(step_ms * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp8_e4m3 cache, f16 MFMA, f32 accumulate" if e4m3 else "f16",
         "data": "synthetic",
         "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
                    "head_dim": w.d, "block_size": w.B, "context_tokens": ab["tokens"],
                    "kv_pools_rotated": layers,
-                   "decode_plan": plan,
+                   "decode_plan": plan_used,
                    "step": ("kv_cache_write + paged_gqa_decode_partitioned (P=%d) + paged_gqa_reduce, "
                             "one layer" % P) if partitioned else
                            (("paged_gqa_decode_scheduled" if prepared else "paged_gqa_decode_step") +
@@ -314,40 +384,56 @@ def main():
                    "schedule": ("prepared once per %d steps (one per decoding step of a %d-layer model), "
                                 "inside the timed region" % (layers, layers)) if prepared else
                                ("fixed partitions" if partitioned else "derived inside every launch"),
-                   "launch": "eager" if args.no_graph else "hip_graph"},
+                   "launch": "eager" if args.no_graph else "hip_graph",
+                   "clock_preroll_launches": args.preroll},
         "pct_of_hbm_peak_step": round(100 * kv_gbs / HBM_PEAK_GBS, 2),
         "wall_ms_timed_region": round(wall_ms, 2),
     }
-    if kern_us:
-        # algorithmic bytes of one decode-kernel launch: KV codes + scales of the visible tokens,
-        # q, and the block-table entries used (partials are a by-product of the split, not counted)
-        alg = ab["kv"] + ab["q_out"] // 2 + ab["tables"]
-        pmc = PMC_TRAFFIC.get((w.name, args.schedule))
-        traffic = None
-        if pmc and not args.plan and not partitioned:
-            traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
-        achieved = alg / (kern_us * 1e-6) / 1e9
-        stream = stream_read_ceiling(coopt, torch, dev)
-        result["roofline"] = {"bound": "hbm",
-                              "kernel": "paged_decode_kernel (coopt_paged_gqa_decode_partitioned)"
-                              if partitioned else ("flat_stream_prepared_kernel (coopt_paged_gqa_decode_scheduled)"
-                                                   if prepared else "flat_stream_kernel (coopt_paged_gqa_decode_split)"),
-                              "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                              "algorithmic_bytes_per_launch": int(alg),
-                              "kernel_us_mean": round(kern_us, 3),
-                              "launch_floor_us": round(floor_us, 3),
-                              "stream_read_gbs": stream["gbs"],
-                              "frac_of_stream_read": round(achieved / stream["gbs"], 4),
-                              "timing": "HIP events around back-to-back launches on the launch "
-                                        "stream; includes the inter-launch gap (launch_floor_us), "
-                                        "which a kernel trace's begin-to-end duration does not"}
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, ab)
-    print(json.dumps(result), flush=True)
+    # algorithmic bytes of one decode-kernel launch: KV codes + scales of the visible tokens,
+    # q, and the block-table entries used (partials are a by-product of the split, not counted;
+    # nor are the new rows a fused launch also reads and writes)
+    alg = ab["kv"] + ab["q_out"] // 2 + ab["tables"]
+    mode = ("fused" if fused else "plain") if prepared else "live"
+    pmc = PMC_TRAFFIC.get((w.name, mode))
+    traffic = None
+    if pmc and not args.plan and not partitioned and pmc.get("sources_sha16") == kernel_sources_sha16():
+        traffic = int((pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024)
+    achieved = alg / (kern_us * 1e-6) / 1e9
+    kernel = ("paged_decode_kernel (coopt_paged_gqa_decode_partitioned)" if partitioned else
+              ("flat_stream_prepared_kernel (coopt_paged_gqa_decode_scheduled%s)"
+               % (", the launch of the step: attention and the new tokens' cache write" if fused else "")
+               if prepared else "flat_stream_kernel (coopt_paged_gqa_decode_split)"))
+    result["roofline"] = {"bound": "hbm", "kernel": kernel,
+                          "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                          "algorithmic_bytes_per_launch": int(alg),
+                          "kernel_us_mean": round(kern_us, 3), "kernel_launches_timed": ksteps,
+                          "launch_floor_us": round(floor_us, 3),
+                          "timing": "HIP events around back-to-back launches on the launch "
+                                    "stream; includes the inter-launch gap (launch_floor_us), "
+                                    "which a kernel trace's begin-to-end duration does not"}
+    if plain_us is not None:
+        result["roofline"]["attention_only_kernel_us_mean"] = round(plain_us, 3)
+        result["roofline"]["attention_only_frac"] = round(alg / (plain_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+    if stream:
+        sr = stream_read_ceiling(probe, torch, dev)
+        result["roofline"]["stream_read_gbs"] = sr["gbs"]
+        result["roofline"]["frac_of_stream_read"] = round(achieved / sr["gbs"], 4)
+    if cpu:
+        base, ref = cpu_baseline(w, ab)
+        result["cpu_baseline"] = base
+        # the step's output rows (last timed step) against the oracle's, on the sampled sequences
+        err = np.abs(got[:ref.shape[0]] - ref)
+        result["parity"] = {"against": "oracle (float64) on the cpu_baseline sample, same inputs",
+                            "sequences": int(ref.shape[0]), "elements": int(ref.size),
+                            "max_abs": float(err.max()), "max_abs_oracle": float(np.abs(ref).max()),
+                            "over_2e-3": int((err > 2e-3).sum()),
+                            "finite": bool(np.isfinite(got).all())}
+    del pools
+    return result
 
 
-def stream_read_ceiling(coopt, torch, dev, detail=False):
+def stream_read_ceiling(coopt, torch, dev, detail=False):      # `coopt`: the probe's binding
     """GB/s of coopt_stream_read_probe (a kernel that only reads, 16-byte streaming loads) over a
     2 GiB buffer, far beyond the memory-side cache: the best of a few launch shapes, 10 launches
     each between two events.  What this GPU delivers when nothing but the loads is in the way."""
@@ -372,7 +458,7 @@ def stream_read_ceiling(coopt, torch, dev, detail=False):
     return out
 
 
-def bench_prefill(args, w, coopt, torch, dev):
+def bench_prefill(args, w, coopt, torch, dev, steps, warmup, cpu):
     """Config 4: a step = cache write of every sequence's chunk (quantise-on-write) + causal
     attention of the chunk rows over history and chunk.  A dense contraction: the dominant kernel
     is priced against the fp16 matrix-core peak."""
@@ -420,10 +506,10 @@ def bench_prefill(args, w, coopt, torch, dev):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / count
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-    steps = min(args.steps, 200)
+    steps = min(steps, 200)
     t0 = time.perf_counter()
     step_ms = timed(step, steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -434,7 +520,7 @@ def bench_prefill(args, w, coopt, torch, dev):
     result = {
         "metric": "chunked prefill attention over the paged FP8 cache: TFLOP/s per step",
         "value": round(flops / step_ms / 1e9, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
-        "warmup": args.warmup, "ms_per_step": round(step_ms, 4), "higher_is_better": True,
+        "warmup": warmup, "ms_per_step": round(step_ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 cache, f16 MFMA, f32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
@@ -449,9 +535,18 @@ def bench_prefill(args, w, coopt, torch, dev):
                      "traffic": None, "algorithmic_flops_per_launch": flops,
                      "kernel_ms_mean": round(kern_ms, 4)},
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline_prefill(w, flops)
-    print(json.dumps(result), flush=True)
+    if cpu:
+        base, rows, ref = cpu_baseline_prefill(w, flops)
+        result["cpu_baseline"] = base
+        got = out.cpu().numpy().astype(np.float64)[rows]          # sequence 0 starts at row 0
+        err = np.abs(got - ref)
+        result["parity"] = {"against": "oracle (float64) on the cpu_baseline sample, same inputs",
+                            "rows": int(len(rows)), "elements": int(ref.size),
+                            "max_abs": float(err.max()), "max_abs_oracle": float(np.abs(ref).max()),
+                            "over_2e-3": int((err > 2e-3).sum()),
+                            "finite": bool(np.isfinite(got).all())}
+    del pools
+    return result
 
 
 def bench_gather(args, w, coopt, torch, dev):
@@ -549,7 +644,7 @@ def bench_gather(args, w, coopt, torch, dev):
         result["cpu_baseline"] = {"value": round(lens[0] * w.H_k * per_row / sec / 1e9, 3), "unit": "GB/s",
                                   "cores": 1, "kind": "oracle", "seconds": round(sec, 3),
                                   "sample": f"sequence 0 ({lens[0]} of {sum(lens)} tokens), all KV heads"}
-    print(json.dumps(result), flush=True)
+    return result
 
 
 def cpu_baseline_prefill(w, flops):
@@ -568,21 +663,23 @@ def cpu_baseline_prefill(w, flops):
                               np.ascontiguousarray(w.slots[idx]), kc, vc, ks, vs, H_k=w.H_k, d=w.d, B=w.B)
     rows = np.arange(0, C, 8, dtype=np.int32)               # 64 rows of sequence 0
     t0 = time.perf_counter()
-    oracle.paged_gqa_prefill_chunk(w.q, kc, vc, ks, vs, w.block_tables, w.context_lens, w.query_start,
-                                   H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B,
-                                   softmax_scale=w.softmax_scale, rows=rows)
+    ref = oracle.paged_gqa_prefill_chunk(w.q, kc, vc, ks, vs, w.block_tables, w.context_lens,
+                                         w.query_start, H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B,
+                                         softmax_scale=w.softmax_scale, rows=rows)
     sec = time.perf_counter() - t0
     t_ctx = int(w.context_lens[0]) - C
     sample_flops = 4.0 * w.d * w.H_q * sum(t_ctx + int(r) + 1 for r in rows)
-    return {"value": round(sample_flops / sec / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(sec, 3),
-            "sample": f"{len(rows)} of {C} chunk rows of sequence 0, all {w.H_q} query heads, "
-                      f"attention only ({sample_flops / flops:.2%} of the step's flops)"}
+    return ({"value": round(sample_flops / sec / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+             "kind": "oracle", "seconds": round(sec, 3),
+             "sample": f"{len(rows)} of {C} chunk rows of sequence 0, all {w.H_q} query heads, "
+                       f"attention only ({sample_flops / flops:.2%} of the step's flops)"},
+            rows, np.asarray(ref, dtype=np.float64))
 
 
 def cpu_baseline(w, ab):
     """The oracle as it stands, timed on the host cores: the same step (write of the new tokens +
-    attention) on a bounded sample of the workload's sequences (about 10-30 s of CPU work)."""
+    attention) on a bounded sample of the workload's sequences (about 10-30 s of CPU work).
+    Returns the baseline record and the oracle's output rows for the sampled sequences."""
     import oracle
     oracle.build()
     # sample: the whole batch when the oracle finishes it in about a second, else its first quarter
@@ -611,16 +708,16 @@ def cpu_baseline(w, ab):
     for _ in range(5):
         t0 = time.perf_counter()
         write(new)
-        oracle.paged_gqa_decode(np.ascontiguousarray(w.q[:n]), kc, vc, ks, vs,
+        ref = oracle.paged_gqa_decode(np.ascontiguousarray(w.q[:n]), kc, vc, ks, vs,
                                 np.ascontiguousarray(w.block_tables[:n]),
                                 np.ascontiguousarray(w.context_lens[:n]), H_q=w.H_q, H_k=w.H_k,
                                 d=w.d, B=w.B, softmax_scale=w.softmax_scale)
         best = min(best, time.perf_counter() - t0)
     kv = tok_end * ab["per_token"]
-    return {"value": round(kv / best / 1e9, 5), "unit": "GB/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(best, 3),
-            "sample": f"first {n} of {w.S} sequences ({tok_end} of {ab['tokens']} context tokens), "
-                      f"one layer, write + decode, best of 5"}
+    return ({"value": round(kv / best / 1e9, 5), "unit": "GB/s", "cores": oracle.num_threads(),
+             "kind": "oracle", "seconds": round(best, 3),
+             "sample": f"first {n} of {w.S} sequences ({tok_end} of {ab['tokens']} context tokens), "
+                       f"one layer, write + decode, best of 5"}, np.asarray(ref, dtype=np.float64))
 
 
 if __name__ == "__main__":

@@ -13,7 +13,11 @@
  *    (host) and `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
  *  - Unless a comment says otherwise the library allocates nothing, frees nothing, copies nothing
  *    to the host and never synchronises: kernels are enqueued on `hip_stream` and the call returns.
- *  - Return value: COOPT_OK (0) or a negative coopt_status.  On any error NOTHING was launched.
+ *  - Return value: COOPT_OK (0) or a negative coopt_status.  Arguments are validated before the
+ *    first launch: on COOPT_ERR_NULL, _SHAPE or _WORKSPACE nothing was launched.  COOPT_ERR_LAUNCH
+ *    means the HIP runtime refused a launch; for an entry point of two launches the first may
+ *    then already be enqueued.
+ *  - There is no process-wide state: every call takes what it depends on as arguments.
  *  - Indices: slots are int64, block numbers and lengths int32.  Floating point: q / new k,v /
  *    out are IEEE binary16; scales and partials are binary32.
  *
@@ -81,6 +85,41 @@ typedef struct coopt_shape {
 } coopt_shape;
 
 /*
+ * Launch plan of the decode entry points (tuning knobs).  Every entry point that depends on it
+ * takes a `const coopt_decode_plan* plan` (host memory, read during the call only); NULL means the
+ * default plan for the current device, which coopt_default_decode_plan writes out.  Calls that
+ * share a workspace or a schedule (split and merge; prepare and the scheduled decode; the size
+ * queries and the calls they size for) must be given the same plan: a schedule carries a tag of
+ * the plan it was prepared for and a workspace one of the plan its partial results were laid out
+ * for, and a launch that finds another tag writes nothing (see the entry points).
+ *
+ * coopt_paged_gqa_decode with a workspace flattens the batch's work and cuts it into shares that
+ * differ by at most one two-block group, one share per single-wavefront workgroup: at most
+ * `grid_waves` wavefronts in the whole grid (default: one per SIMD of the device, 4 x its
+ * compute-unit count = 1024 on MI355X), a share never smaller than `tokens_per_group` tokens (a
+ * positive multiple of 32; default 128) unless the whole batch is.
+ * coopt_paged_gqa_decode_partitioned runs `waves_per_group` (1, 2, 4 or 8; default 1) wavefronts
+ * per partition; the balanced kernel ignores that field.  In both, every wavefront keeps
+ * `pipeline_depth` (1, 2 or 3; default 2) two-block groups of the cache in flight.
+ * `softmax_reduction` selects how the balanced kernel keeps the softmax statistics: 0 (default) =
+ * a running reference max per lane that is raised only when a score exceeds it by a margin, sums
+ * reduced once at the end; 1 = the mechanism Opt-Pa states (Alg. 3, Eq. 10): max and sum of every
+ * group of blocks reduced through shared memory and the accumulator rescaled each time -- kept to
+ * compare the two on this hardware (pipeline_depth is then 2).
+ * A plan with a field out of range makes the call return COOPT_ERR_SHAPE (size queries: 0).
+ */
+typedef struct coopt_decode_plan {
+    int32_t tokens_per_group;
+    int32_t waves_per_group;
+    int32_t pipeline_depth;
+    int32_t grid_waves;
+    int32_t softmax_reduction;
+} coopt_decode_plan;
+
+/* Writes the default plan for the current HIP device into *plan (host memory). */
+void coopt_default_decode_plan(coopt_decode_plan* plan);
+
+/*
  * Quantise-on-write of new tokens into the paged cache (Opt-KV: Eq. 5 and Alg. 1 phase 1).
  * For token i: slot_mapping[i] < 0 means "skip, write nothing" (the filter of Eq. 5; any other
  * skip set is expressed by the caller passing a negative slot).  Otherwise, for every KV head and
@@ -130,14 +169,14 @@ int coopt_kv_cache_write_skipset(const void* k, const void* v, const int64_t* sl
  *     kernels: split attention into partial results, then their merge).  NULL (then
  *     workspace_bytes is ignored) runs one workgroup per (sequence, KV head) over the whole context
  *     instead, which is only adequate for small batches of short contexts.  Otherwise it must hold
- *     at least coopt_decode_workspace_bytes(shape) bytes and be 16-byte aligned; its contents are
+ *     at least coopt_decode_workspace_bytes(shape, plan) bytes and be 16-byte aligned; its contents are
  *     undefined afterwards.  Two calls that share a workspace must be ordered on one stream.
  */
 int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cache,
                            const float* k_scale, const float* v_scale,
                            const int32_t* block_tables, const int32_t* context_lens, void* out,
-                           void* workspace, size_t workspace_bytes, const coopt_shape* shape,
-                           void* hip_stream);
+                           void* workspace, size_t workspace_bytes, const coopt_decode_plan* plan,
+                           const coopt_shape* shape, void* hip_stream);
 
 /*
  * The two kernels of coopt_paged_gqa_decode as separate calls, for callers that time or schedule
@@ -145,40 +184,47 @@ int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cac
  * (reference max, exponential sum, normalised output) per share segment in the workspace; `merge`
  * combines the partials of each (sequence, query head) into the fp16 output row.  Arguments as in
  * coopt_paged_gqa_decode; the workspace is required, and shape, context_lens and the decode plan
- * must be the same for both calls.
+ * must be the same for both calls.  `split` leaves a tag of shape and plan in the workspace's
+ * first 16 bytes; a `merge` that expects another tag (its plan or shape differs) writes nothing
+ * and `out` keeps its old contents.
  */
 int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
                                  const float* k_scale, const float* v_scale,
                                  const int32_t* block_tables, const int32_t* context_lens,
-                                 void* workspace, size_t workspace_bytes, const coopt_shape* shape,
+                                 void* workspace, size_t workspace_bytes,
+                                 const coopt_decode_plan* plan, const coopt_shape* shape,
                                  void* hip_stream);
 int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* workspace,
-                                 size_t workspace_bytes, void* out, const coopt_shape* shape,
-                                 void* hip_stream);
+                                 size_t workspace_bytes, void* out, const coopt_decode_plan* plan,
+                                 const coopt_shape* shape, void* hip_stream);
 
 /*
  * One decode step in two launches instead of three: Opt-KV's write of each sequence's new token
  * (Eq. 5, Alg. 1 phase 1) fused with the attention of Opt-GQA / Opt-Pa (Eq. 6-10).  The result is
  * that of coopt_kv_cache_write_fp8 / _fp16 with num_tokens = num_seqs followed by
  * coopt_paged_gqa_decode with a workspace: the same bytes end up in the cache, and `out` agrees
- * within the attention tolerance (the new token enters as one more partial, computed from the
- * values just quantised, while the other workgroups of the same launch read the older tokens).
+ * within the attention tolerance.  The wavefront that reads the last cache blocks of a (sequence,
+ * KV head) pair quantises the pair's new row, attends over it from registers in place of whatever
+ * the cache holds at that position, and stores it; the launch has no other wavefronts than the
+ * plain decode's and nothing in it waits for anything else.
  *   k, v          device, fp16 [num_seqs][num_kv_heads][head_dim]: token s is the LAST token of
  *                 sequence s, i.e. position context_lens[s]-1
- *   slot_mapping  device, int64 [num_seqs]: its slot, which must be the one block_tables assigns
- *                 to that position (not checked); negative = write nothing for this sequence and
- *                 attend to whatever the cache holds at that position, as the two separate calls
- *                 would
+ *   slot_mapping  device, int64 [num_seqs]: negative = write nothing for this sequence and attend
+ *                 to whatever the cache holds at that position, as the two separate calls would.
+ *                 Otherwise the row is written where block_tables places position
+ *                 context_lens[s]-1; the slot must name that same place (not checked; only its
+ *                 sign is used)
  *   k_cache .. v_scale   as in coopt_paged_gqa_decode, but written to (scales NULL iff fp16 cache)
  *   context_lens  INCLUDES the new token; 0 = empty sequence (nothing written, zero output rows)
- *   workspace     required here; coopt_decode_workspace_bytes(shape) bytes, 16-byte aligned
- * Errors as for the two separate calls; nothing is launched on error.
+ *   workspace     required here; coopt_decode_workspace_bytes(shape, plan) bytes, 16-byte aligned
+ * Errors as for the two separate calls.
  */
 int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slot_mapping,
                                 const void* q, void* k_cache, void* v_cache, float* k_scale,
                                 float* v_scale, const int32_t* block_tables,
                                 const int32_t* context_lens, void* out, void* workspace,
-                                size_t workspace_bytes, const coopt_shape* shape, void* hip_stream);
+                                size_t workspace_bytes, const coopt_decode_plan* plan,
+                                const coopt_shape* shape, void* hip_stream);
 /*
  * The same decode with its schedule prepared ahead.  Block tables, context lengths and the slots of
  * the new tokens are the same for every layer of a model during one decoding step, so the schedule
@@ -188,7 +234,7 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  * runs any number of layers from it.  A scheduled launch reaches its first cache load one memory
  * round trip after it starts, without the schedule arithmetic and the block-table read.
  *
- *   schedule      device, coopt_decode_schedule_bytes(shape) bytes, 16-byte aligned, owned by the
+ *   schedule      device, coopt_decode_schedule_bytes(shape, plan) bytes, 16-byte aligned, owned by the
  *                 caller; opaque.  Valid for the shape, the decode plan and the mode (plain decode
  *                 or fused step) it was prepared with, and for as long as block_tables,
  *                 context_lens and slot_mapping keep their contents.
@@ -198,7 +244,7 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  *   scheduled decode:  k, v, slot_mapping all NULL = plain decode, all non-NULL = fused step
  *             (COOPT_ERR_NULL if mixed); the other arguments as in coopt_paged_gqa_decode_step,
  *             without block_tables.  out NULL = stop after the partial results (the workspace then
- *             holds what coopt_paged_gqa_decode_split leaves).
+ *             holds the partial results only; the pairs' partial counts stay in the schedule).
  * prepare only enqueues a kernel on hip_stream: the launches that use the schedule must be ordered
  * after it (same stream, or an event), and two launches that use one schedule may overlap.
  * A schedule prepared for another shape, plan or mode is recognised on the device by a tag: such a
@@ -209,50 +255,22 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  * misaligned, COOPT_ERR_SHAPE (bytes: 0) where a share or a pair's partial count would not fit the
  * record fields (more than 65 535 partials per pair).
  */
-size_t coopt_decode_schedule_bytes(const coopt_shape* shape);
+size_t coopt_decode_schedule_bytes(const coopt_shape* shape, const coopt_decode_plan* plan);
 int coopt_decode_schedule_prepare(const int32_t* block_tables, const int32_t* context_lens,
                                   const int64_t* slot_mapping, void* schedule, size_t schedule_bytes,
-                                  const coopt_shape* shape, void* hip_stream);
+                                  const coopt_decode_plan* plan, const coopt_shape* shape,
+                                  void* hip_stream);
 int coopt_paged_gqa_decode_scheduled(const void* k, const void* v, const int64_t* slot_mapping,
                                      const void* q, void* k_cache, void* v_cache, float* k_scale,
                                      float* v_scale, const int32_t* context_lens, void* out,
                                      void* workspace, size_t workspace_bytes, const void* schedule,
-                                     size_t schedule_bytes, const coopt_shape* shape,
-                                     void* hip_stream);
+                                     size_t schedule_bytes, const coopt_decode_plan* plan,
+                                     const coopt_shape* shape, void* hip_stream);
 
 
-/* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under the current decode plan
- * (0 if the shape is unsupported). */
-size_t coopt_decode_workspace_bytes(const coopt_shape* shape);
-
-/*
- * Launch plan (tuning knobs, process-wide, not thread-safe against concurrent decode calls).
- * coopt_paged_gqa_decode with a workspace flattens the batch's work and cuts it into shares that
- * differ by at most one two-block group, one share per single-wavefront workgroup: at most
- * `grid_waves` wavefronts in the whole grid, a share never smaller than `tokens_per_group` tokens
- * (a positive multiple of 32) unless the whole batch is.  coopt_paged_gqa_decode_partitioned runs
- * `waves_per_group` (1, 2, 4 or 8) wavefronts per partition; the balanced kernel ignores that
- * field.  In both, every wavefront keeps `pipeline_depth` (1, 2 or 3) two-block groups of the
- * cache in flight.  `softmax_reduction` selects how the balanced kernel keeps the softmax
- * statistics: 0 (default) = a running reference max per lane that is raised only when a score
- * exceeds it by a margin, sums reduced once at the end; 1 = the mechanism Opt-Pa states (Alg. 3,
- * Eq. 10): max and sum of every group of blocks reduced through shared memory and the accumulator
- * rescaled each time -- kept to compare the two on this hardware (pipeline_depth is then 2).
- * coopt_set_decode_plan validates every field and returns COOPT_ERR_SHAPE (changing nothing) if
- * one is out of range; tokens_per_group changes coopt_decode_workspace_bytes.
- */
-typedef struct coopt_decode_plan {
-    int32_t tokens_per_group;
-    int32_t waves_per_group;
-    int32_t pipeline_depth;
-    int32_t grid_waves;
-    int32_t softmax_reduction;
-} coopt_decode_plan;
-
-int coopt_set_decode_plan(const coopt_decode_plan* plan);
-
-/* Copies the current plan into *plan (host memory). */
-void coopt_get_decode_plan(coopt_decode_plan* plan);
+/* Bytes of workspace coopt_paged_gqa_decode needs for `shape` under `plan` (0 if the shape or the
+ * plan is unsupported).  tokens_per_group and grid_waves change it. */
+size_t coopt_decode_workspace_bytes(const coopt_shape* shape, const coopt_decode_plan* plan);
 
 /*
  * Partitioned decode for long contexts (the "partitioned parallel" reduction of the paper's
@@ -273,7 +291,8 @@ int coopt_paged_gqa_decode_partitioned(const void* q, const void* k_cache, const
                                        const int32_t* block_tables, const int32_t* context_lens,
                                        int32_t partition_size, float* tmp_out, float* max_logits,
                                        float* exp_sums, int32_t max_parts,
-                                       const coopt_shape* shape, void* hip_stream);
+                                       const coopt_decode_plan* plan, const coopt_shape* shape,
+                                       void* hip_stream);
 
 /*
  * Cross-partition merge: M = max_p m_p, w_p = l_p*exp(m_p - M),
@@ -312,17 +331,6 @@ int coopt_gather_cached_kv(const void* k_cache, const void* v_cache, const float
                            const float* v_scale, const int32_t* block_tables, int32_t seq,
                            int32_t tok_begin, int32_t tok_end, void* k_out, void* v_out,
                            const coopt_shape* shape, void* hip_stream);
-
-/*
- * Measurement aid (no part of the paper's method): reads `bytes` of device memory at `buf`
- * (16-byte aligned) once with 16-byte streaming loads from `workgroups` workgroups of 256 lanes
- * and writes nothing (one word of `sink`, device memory of at least 4 bytes, only if the XOR of
- * the data hits an arbitrary constant).  Timed by the caller, it gives the read rate this GPU
- * sustains for a kernel with no other work: the figure the decode kernels' bandwidth is quoted
- * beside.  COOPT_ERR_SHAPE for workgroups outside [1, 2^20] or a misaligned buffer.
- */
-int coopt_stream_read_probe(const void* buf, size_t bytes, int32_t workgroups, void* sink,
-                            void* hip_stream);
 
 /* Static, human-readable text for a coopt_status value. */
 const char* coopt_status_string(int status);

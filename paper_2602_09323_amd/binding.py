@@ -3,6 +3,12 @@
 Tensors are torch CUDA(HIP) tensors used purely as device memory; every step of the path runs in
 the library's own kernels on the current torch stream.  If the shared library is missing the
 binding raises: there is no fallback path.
+
+The C side takes raw pointers and cannot see a buffer's size, type or residence, so the binding
+checks what it can before anything is launched: every tensor is a contiguous device tensor, index
+tensors have the integer width the kernels read (int64 slots, int32 tables / lengths / row
+offsets), fp16 operands have 2-byte elements, and every buffer holds at least the bytes the shape
+implies.  A violation raises ``CooptError``.
 """
 from __future__ import annotations
 
@@ -19,12 +25,11 @@ COOPT_KV_E4M3 = 1
 
 EXPORTS = [
     "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_kv_cache_write_skipset",
-    "coopt_paged_gqa_decode",
-    "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split", "coopt_paged_gqa_decode_merge",
-    "coopt_decode_workspace_bytes", "coopt_set_decode_plan", "coopt_get_decode_plan", "coopt_paged_gqa_decode_partitioned",
-    "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk", "coopt_gather_cached_kv",
-    "coopt_decode_schedule_bytes", "coopt_decode_schedule_prepare", "coopt_paged_gqa_decode_scheduled",
-    "coopt_stream_read_probe", "coopt_status_string",
+    "coopt_paged_gqa_decode", "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split",
+    "coopt_paged_gqa_decode_merge", "coopt_decode_workspace_bytes", "coopt_default_decode_plan",
+    "coopt_paged_gqa_decode_partitioned", "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk",
+    "coopt_gather_cached_kv", "coopt_decode_schedule_bytes", "coopt_decode_schedule_prepare",
+    "coopt_paged_gqa_decode_scheduled", "coopt_status_string",
 ]
 
 
@@ -37,6 +42,9 @@ class DecodePlan(ctypes.Structure):
     _fields_ = [("tokens_per_group", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
                 ("pipeline_depth", ctypes.c_int32), ("grid_waves", ctypes.c_int32),
                 ("softmax_reduction", ctypes.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
 
 
 class Shape(ctypes.Structure):
@@ -60,36 +68,35 @@ def load_library():
         if not os.path.exists(path):
             raise CooptError(f"{path} is not built; run `python -m paper_2602_09323_amd.build`")
         lib = ctypes.CDLL(path)
-        vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
-        shp = ctypes.POINTER(Shape)
-        lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, i64p, i32, vp, vp, vp, vp, shp, vp]
-        lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, i64p, i32, vp, vp, shp, vp]
-        lib.coopt_kv_cache_write_skipset.argtypes = [vp, vp, i64p, vp, i32, vp, vp, vp, vp, shp, vp]
-        lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
-        lib.coopt_paged_gqa_decode_step.argtypes = [vp, vp, i64p, vp, vp, vp, vp, vp, vp, vp, vp, vp,
-                                                    ctypes.c_size_t, shp, vp]
-        lib.coopt_paged_gqa_decode_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, shp, vp]
-        lib.coopt_paged_gqa_decode_merge.argtypes = [vp, vp, ctypes.c_size_t, vp, shp, vp]
-        lib.coopt_decode_workspace_bytes.argtypes = [shp]
-        lib.coopt_decode_workspace_bytes.restype = ctypes.c_size_t
-        lib.coopt_set_decode_plan.argtypes = [ctypes.POINTER(DecodePlan)]
-        lib.coopt_get_decode_plan.argtypes = [ctypes.POINTER(DecodePlan)]
-        lib.coopt_get_decode_plan.restype = None
-        lib.coopt_paged_gqa_decode_partitioned.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, shp, vp]
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        shp, plp = ctypes.POINTER(Shape), ctypes.POINTER(DecodePlan)
+        lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, shp, vp]
+        lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, vp, i32, vp, vp, shp, vp]
+        lib.coopt_kv_cache_write_skipset.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, shp, vp]
+        lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, plp, shp, vp]
+        lib.coopt_paged_gqa_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                                                    plp, shp, vp]
+        lib.coopt_paged_gqa_decode_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, plp, shp, vp]
+        lib.coopt_paged_gqa_decode_merge.argtypes = [vp, vp, sz, vp, plp, shp, vp]
+        lib.coopt_decode_workspace_bytes.argtypes = [shp, plp]
+        lib.coopt_decode_workspace_bytes.restype = sz
+        lib.coopt_default_decode_plan.argtypes = [plp]
+        lib.coopt_default_decode_plan.restype = None
+        lib.coopt_paged_gqa_decode_partitioned.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp,
+                                                           i32, plp, shp, vp]
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_paged_gqa_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_gather_cached_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, shp, vp]
-        lib.coopt_decode_schedule_bytes.argtypes = [shp]
-        lib.coopt_decode_schedule_bytes.restype = ctypes.c_size_t
-        lib.coopt_decode_schedule_prepare.argtypes = [vp, vp, i64p, vp, ctypes.c_size_t, shp, vp]
-        lib.coopt_paged_gqa_decode_scheduled.argtypes = [vp, vp, i64p, vp, vp, vp, vp, vp, vp, vp, vp,
-                                                         ctypes.c_size_t, vp, ctypes.c_size_t, shp, vp]
-        lib.coopt_stream_read_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, vp]
+        lib.coopt_decode_schedule_bytes.argtypes = [shp, plp]
+        lib.coopt_decode_schedule_bytes.restype = sz
+        lib.coopt_decode_schedule_prepare.argtypes = [vp, vp, vp, vp, sz, plp, shp, vp]
+        lib.coopt_paged_gqa_decode_scheduled.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                                                         vp, sz, plp, shp, vp]
         lib.coopt_status_string.argtypes = [ctypes.c_int]
         lib.coopt_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name not in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes", "coopt_status_string",
-                            "coopt_get_decode_plan"):
+            if name not in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes",
+                            "coopt_status_string", "coopt_default_decode_plan"):
                 getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -104,8 +111,70 @@ def _check(status: int, what: str) -> None:
         raise CooptError(f"{what}: status {status} ({status_string(status)})")
 
 
-def _ptr(t) -> Optional[int]:
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+def _call(name: str, *args) -> None:
+    """Enter the library: every argument has been checked and marshalled by now."""
+    _check(getattr(load_library(), name)(*args), name)
+
+
+# ---------------------------------------------------------------- argument checks (host, no launch)
+
+def _nbytes(t) -> int:
+    return int(t.numel()) * int(t.element_size())
+
+
+def _dev(t, name: str, *, min_bytes: int = 0, elem: Optional[int] = None, dtype=None,
+         optional: bool = False):
+    """Pointer of a contiguous device tensor of at least ``min_bytes`` bytes, with ``elem``-byte
+    elements or exactly ``dtype`` where given.  None passes as NULL only if ``optional``."""
+    if t is None:
+        if optional:
+            return None
+        raise CooptError(f"{name}: required tensor is None")
+    if not getattr(t, "is_cuda", False):
+        raise CooptError(f"{name}: not a device tensor")
+    if not t.is_contiguous():
+        raise CooptError(f"{name}: not contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise CooptError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if elem is not None and int(t.element_size()) != elem:
+        raise CooptError(f"{name}: {t.element_size()}-byte elements, expected {elem}")
+    if _nbytes(t) < min_bytes:
+        raise CooptError(f"{name}: {_nbytes(t)} bytes, the shape needs {min_bytes}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _sizes(shape: Shape):
+    es = 1 if shape.kv_dtype == COOPT_KV_E4M3 else 2
+    tiles = shape.num_blocks * shape.num_kv_heads
+    return {"cache": tiles * shape.block_size * shape.head_dim * es,
+            "scale": tiles * shape.block_size * 4,
+            "q": shape.num_seqs * shape.num_q_heads * shape.head_dim * 2,
+            "tables": shape.num_seqs * shape.max_blocks_per_seq * 4,
+            "lens": shape.num_seqs * 4,
+            "row": shape.num_kv_heads * shape.head_dim * 2,
+            "e4m3": shape.kv_dtype == COOPT_KV_E4M3}
+
+
+def _cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape: Shape):
+    z = _sizes(shape)
+    scaled = z["e4m3"]
+    return (_dev(k_cache, "k_cache", min_bytes=z["cache"]), _dev(v_cache, "v_cache", min_bytes=z["cache"]),
+            _dev(k_scale, "k_scale", min_bytes=z["scale"], optional=not scaled),
+            _dev(v_scale, "v_scale", min_bytes=z["scale"], optional=not scaled))
+
+
+def _i32():
+    import torch
+    return torch.int32
+
+
+def _i64():
+    import torch
+    return torch.int64
+
+
+def _plan_ptr(plan: Optional[DecodePlan]):
+    return None if plan is None else ctypes.byref(plan)
 
 
 def _stream(stream=None):
@@ -114,145 +183,221 @@ def _stream(stream=None):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _new_rows(k, v, slot_mapping, shape: Shape, what: str):
+    """Pointers of new K/V rows [T][H_k][d] fp16 and their int64 slots; returns (pk, pv, ps, T)."""
+    z = _sizes(shape)
+    ps = _dev(slot_mapping, f"{what}: slot_mapping", dtype=_i64())
+    T = int(slot_mapping.numel())
+    return (_dev(k, f"{what}: k", elem=2, min_bytes=T * z["row"]),
+            _dev(v, f"{what}: v", elem=2, min_bytes=T * z["row"]), ps, T)
+
+
+# ---------------------------------------------------------------- plan
+
+def default_decode_plan() -> DecodePlan:
+    """The plan a call runs under when it is given none (``coopt_default_decode_plan``)."""
+    p = DecodePlan()
+    load_library().coopt_default_decode_plan(ctypes.byref(p))
+    return p
+
+
+def make_decode_plan(**fields) -> DecodePlan:
+    """The default plan with the named fields of ``coopt_decode_plan`` replaced."""
+    p = default_decode_plan()
+    for k, val in fields.items():
+        if k not in dict(DecodePlan._fields_):
+            raise KeyError(k)
+        setattr(p, k, int(val))
+    return p
+
+
+# ---------------------------------------------------------------- cache write
+
 def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, shape: Shape,
                        stream=None) -> None:
-    _check(load_library().coopt_kv_cache_write_fp8(
-        _ptr(k), _ptr(v), _ptr(slot_mapping), int(slot_mapping.numel()), _ptr(k_cache),
-        _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), ctypes.byref(shape), _stream(stream)),
-        "coopt_kv_cache_write_fp8")
+    pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, "kv_cache_write_fp8")
+    _call("coopt_kv_cache_write_fp8",
+          pk, pv, ps, T, *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape), ctypes.byref(shape),
+        _stream(stream))
 
 
 def kv_cache_write_skipset(k, v, slot_mapping, skip_set, k_cache, v_cache, k_scale, v_scale,
                            shape: Shape, stream=None) -> None:
     """skip_set: device uint32 bitmap over the call's token indices, or None."""
-    _check(load_library().coopt_kv_cache_write_skipset(
-        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(skip_set), int(slot_mapping.numel()),
-        _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), ctypes.byref(shape),
-        _stream(stream)), "coopt_kv_cache_write_skipset")
+    pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, "kv_cache_write_skipset")
+    pset = _dev(skip_set, "skip_set", min_bytes=(T + 31) // 32 * 4, elem=4, optional=True)
+    _call("coopt_kv_cache_write_skipset",
+          pk, pv, ps, pset, T, *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+        ctypes.byref(shape), _stream(stream))
 
 
 def kv_cache_write_fp16(k, v, slot_mapping, k_cache, v_cache, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_kv_cache_write_fp16(
-        _ptr(k), _ptr(v), _ptr(slot_mapping), int(slot_mapping.numel()), _ptr(k_cache),
-        _ptr(v_cache), ctypes.byref(shape), _stream(stream)), "coopt_kv_cache_write_fp16")
+    pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, "kv_cache_write_fp16")
+    pkc, pvc, _, _ = _cache_ptrs(k_cache, v_cache, None, None, shape)
+    _call("coopt_kv_cache_write_fp16",
+          pk, pv, ps, T, pkc, pvc, ctypes.byref(shape), _stream(stream))
 
 
-def decode_workspace_bytes(shape: Shape) -> int:
-    return int(load_library().coopt_decode_workspace_bytes(ctypes.byref(shape)))
+# ---------------------------------------------------------------- decode
+
+def decode_workspace_bytes(shape: Shape, plan: Optional[DecodePlan] = None) -> int:
+    return int(load_library().coopt_decode_workspace_bytes(ctypes.byref(shape), _plan_ptr(plan)))
 
 
-def get_decode_plan() -> dict:
-    """The plan currently in force, as a dict of the fields of ``coopt_decode_plan``."""
-    p = DecodePlan()
-    load_library().coopt_get_decode_plan(ctypes.byref(p))
-    return {name: int(getattr(p, name)) for name, _ in DecodePlan._fields_}
+def _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape: Shape,
+                   what: str):
+    z = _sizes(shape)
+    return (_dev(q, f"{what}: q", elem=2, min_bytes=z["q"]),
+            *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+            _dev(block_tables, f"{what}: block_tables", dtype=_i32(), min_bytes=z["tables"]),
+            _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]))
 
 
-def set_decode_plan(**fields) -> None:
-    """Update the named fields of the plan (see ``coopt_decode_plan``); the others keep their value."""
-    cur = get_decode_plan()
-    for k in fields:
-        if k not in cur:
-            raise KeyError(k)
-    cur.update(fields)
-    p = DecodePlan(*[cur[name] for name, _ in DecodePlan._fields_])
-    _check(load_library().coopt_set_decode_plan(ctypes.byref(p)), "coopt_set_decode_plan")
+def _workspace(workspace, shape: Shape, plan, what: str, optional: bool = False):
+    if workspace is None and optional:
+        return None, 0
+    need = decode_workspace_bytes(shape, plan)
+    return _dev(workspace, f"{what}: workspace", min_bytes=need), ctypes.c_size_t(_nbytes(workspace))
 
 
 def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, out,
-                     workspace, shape: Shape, stream=None) -> None:
-    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load_library().coopt_paged_gqa_decode(
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
-        _ptr(context_lens), _ptr(out), _ptr(workspace), ctypes.c_size_t(nbytes),
-        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode")
+                     workspace, shape: Shape, plan: Optional[DecodePlan] = None, stream=None) -> None:
+    what = "paged_gqa_decode"
+    ins = _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape, what)
+    pws, nws = _workspace(workspace, shape, plan, what, optional=True)
+    _call("coopt_paged_gqa_decode",
+          *ins, _dev(out, f"{what}: out", elem=2, min_bytes=_sizes(shape)["q"]), pws, nws,
+        _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_decode_step(k, v, slot_mapping, q, k_cache, v_cache, k_scale, v_scale, block_tables,
-                          context_lens, out, workspace, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_decode_step(
-        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
-        _ptr(v_scale), _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(workspace),
-        ctypes.c_size_t(workspace.numel() * workspace.element_size()), ctypes.byref(shape),
-        _stream(stream)), "coopt_paged_gqa_decode_step")
+                          context_lens, out, workspace, shape: Shape,
+                          plan: Optional[DecodePlan] = None, stream=None) -> None:
+    what = "paged_gqa_decode_step"
+    pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, what)
+    if T < shape.num_seqs:
+        raise CooptError(f"{what}: slot_mapping has {T} entries, the batch {shape.num_seqs} sequences")
+    ins = _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape, what)
+    pws, nws = _workspace(workspace, shape, plan, what)
+    _call("coopt_paged_gqa_decode_step",
+          pk, pv, ps, *ins, _dev(out, f"{what}: out", elem=2, min_bytes=_sizes(shape)["q"]), pws, nws,
+        _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_decode_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
-                           workspace, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_decode_split(
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
-        _ptr(context_lens), _ptr(workspace),
-        ctypes.c_size_t(workspace.numel() * workspace.element_size()), ctypes.byref(shape),
-        _stream(stream)), "coopt_paged_gqa_decode_split")
+                           workspace, shape: Shape, plan: Optional[DecodePlan] = None,
+                           stream=None) -> None:
+    what = "paged_gqa_decode_split"
+    ins = _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape, what)
+    pws, nws = _workspace(workspace, shape, plan, what)
+    _call("coopt_paged_gqa_decode_split",
+          *ins, pws, nws, _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
-def paged_gqa_decode_merge(context_lens, workspace, out, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_decode_merge(
-        _ptr(context_lens), _ptr(workspace),
-        ctypes.c_size_t(workspace.numel() * workspace.element_size()), _ptr(out),
-        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode_merge")
+def paged_gqa_decode_merge(context_lens, workspace, out, shape: Shape,
+                           plan: Optional[DecodePlan] = None, stream=None) -> None:
+    what = "paged_gqa_decode_merge"
+    z = _sizes(shape)
+    pws, nws = _workspace(workspace, shape, plan, what)
+    _call("coopt_paged_gqa_decode_merge",
+          _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]), pws, nws,
+        _dev(out, f"{what}: out", elem=2, min_bytes=z["q"]), _plan_ptr(plan), ctypes.byref(shape),
+        _stream(stream))
+
+
+def _partial_buffers(tmp_out, max_logits, exp_sums, max_parts: int, shape: Shape, what: str):
+    rows = shape.num_seqs * shape.num_q_heads * int(max_parts)
+    return (_dev(tmp_out, f"{what}: tmp_out", elem=4, min_bytes=rows * shape.head_dim * 4),
+            _dev(max_logits, f"{what}: max_logits", elem=4, min_bytes=rows * 4),
+            _dev(exp_sums, f"{what}: exp_sums", elem=4, min_bytes=rows * 4))
 
 
 def paged_gqa_decode_partitioned(q, k_cache, v_cache, k_scale, v_scale, block_tables,
                                  context_lens, partition_size: int, tmp_out, max_logits, exp_sums,
-                                 max_parts: int, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_decode_partitioned(
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
-        _ptr(context_lens), int(partition_size), _ptr(tmp_out), _ptr(max_logits), _ptr(exp_sums),
-        int(max_parts), ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_decode_partitioned")
+                                 max_parts: int, shape: Shape, plan: Optional[DecodePlan] = None,
+                                 stream=None) -> None:
+    what = "paged_gqa_decode_partitioned"
+    ins = _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape, what)
+    _call("coopt_paged_gqa_decode_partitioned",
+          *ins, int(partition_size), *_partial_buffers(tmp_out, max_logits, exp_sums, max_parts, shape, what),
+        int(max_parts), _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_reduce(tmp_out, max_logits, exp_sums, context_lens, partition_size: int,
                      max_parts: int, out, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_reduce(
-        _ptr(tmp_out), _ptr(max_logits), _ptr(exp_sums), _ptr(context_lens), int(partition_size),
-        int(max_parts), _ptr(out), ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_reduce")
+    what = "paged_gqa_reduce"
+    z = _sizes(shape)
+    _call("coopt_paged_gqa_reduce",
+          *_partial_buffers(tmp_out, max_logits, exp_sums, max_parts, shape, what),
+        _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]),
+        int(partition_size), int(max_parts), _dev(out, f"{what}: out", elem=2, min_bytes=z["q"]),
+        ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
                             query_start, num_query_rows: int, max_chunk_len: int, out,
                             shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_paged_gqa_prefill_chunk(
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables),
-        _ptr(context_lens), _ptr(query_start), int(num_query_rows), int(max_chunk_len), _ptr(out),
-        ctypes.byref(shape), _stream(stream)), "coopt_paged_gqa_prefill_chunk")
+    what = "paged_gqa_prefill_chunk"
+    z = _sizes(shape)
+    rows_bytes = int(num_query_rows) * shape.num_q_heads * shape.head_dim * 2
+    _call("coopt_paged_gqa_prefill_chunk",
+          _dev(q, f"{what}: q", elem=2, min_bytes=rows_bytes),
+        *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+        _dev(block_tables, f"{what}: block_tables", dtype=_i32(), min_bytes=z["tables"]),
+        _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]),
+        _dev(query_start, f"{what}: query_start", dtype=_i32(), min_bytes=z["lens"] + 4),
+        int(num_query_rows), int(max_chunk_len),
+        _dev(out, f"{what}: out", elem=2, min_bytes=rows_bytes), ctypes.byref(shape), _stream(stream))
 
 
-def decode_schedule_bytes(shape: Shape) -> int:
-    return int(load_library().coopt_decode_schedule_bytes(ctypes.byref(shape)))
+def decode_schedule_bytes(shape: Shape, plan: Optional[DecodePlan] = None) -> int:
+    return int(load_library().coopt_decode_schedule_bytes(ctypes.byref(shape), _plan_ptr(plan)))
 
 
 def decode_schedule_prepare(block_tables, context_lens, slot_mapping, schedule, shape: Shape,
-                            stream=None) -> None:
+                            plan: Optional[DecodePlan] = None, stream=None) -> None:
     """Write the decode schedule (``slot_mapping`` None: plain decode; else the fused step)."""
-    _check(load_library().coopt_decode_schedule_prepare(
-        _ptr(block_tables), _ptr(context_lens), _ptr(slot_mapping), _ptr(schedule),
-        schedule.numel() * schedule.element_size(), ctypes.byref(shape), _stream(stream)),
-        "coopt_decode_schedule_prepare")
+    what = "decode_schedule_prepare"
+    z = _sizes(shape)
+    _call("coopt_decode_schedule_prepare",
+          _dev(block_tables, f"{what}: block_tables", dtype=_i32(), min_bytes=z["tables"]),
+        _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]),
+        _dev(slot_mapping, f"{what}: slot_mapping", dtype=_i64(), min_bytes=2 * z["lens"], optional=True),
+        _dev(schedule, f"{what}: schedule", min_bytes=decode_schedule_bytes(shape, plan)),
+        _nbytes(schedule), _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_decode_scheduled(k, v, slot_mapping, q, k_cache, v_cache, k_scale, v_scale, context_lens,
-                               out, workspace, schedule, shape: Shape, stream=None) -> None:
+                               out, workspace, schedule, shape: Shape,
+                               plan: Optional[DecodePlan] = None, stream=None) -> None:
     """Decode (k, v, slot_mapping None) or fused step from a prepared schedule; ``out`` None stops
     after the partial results."""
-    _check(load_library().coopt_paged_gqa_decode_scheduled(
-        _ptr(k), _ptr(v), _ptr(slot_mapping), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
-        _ptr(v_scale), _ptr(context_lens), _ptr(out), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _ptr(schedule),
-        schedule.numel() * schedule.element_size(), ctypes.byref(shape), _stream(stream)),
-        "coopt_paged_gqa_decode_scheduled")
-
-
-def stream_read_probe(buf, workgroups: int, sink, stream=None) -> None:
-    """One streaming read of the whole tensor ``buf`` (measurement aid)."""
-    _check(load_library().coopt_stream_read_probe(
-        _ptr(buf), buf.numel() * buf.element_size(), int(workgroups), _ptr(sink), _stream(stream)),
-        "coopt_stream_read_probe")
+    what = "paged_gqa_decode_scheduled"
+    z = _sizes(shape)
+    if k is None and v is None and slot_mapping is None:
+        pk = pv = ps = None
+    else:
+        pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, what)
+        if T < shape.num_seqs:
+            raise CooptError(f"{what}: slot_mapping has {T} entries, the batch {shape.num_seqs} sequences")
+    pws, nws = _workspace(workspace, shape, plan, what)
+    _call("coopt_paged_gqa_decode_scheduled",
+          pk, pv, ps, _dev(q, f"{what}: q", elem=2, min_bytes=z["q"]),
+        *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+        _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]),
+        _dev(out, f"{what}: out", elem=2, min_bytes=z["q"], optional=True), pws, nws,
+        _dev(schedule, f"{what}: schedule", min_bytes=decode_schedule_bytes(shape, plan)),
+        _nbytes(schedule), _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
 
 
 def gather_cached_kv(k_cache, v_cache, k_scale, v_scale, block_tables, seq: int, tok_begin: int,
                      tok_end: int, k_out, v_out, shape: Shape, stream=None) -> None:
-    _check(load_library().coopt_gather_cached_kv(
-        _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale), _ptr(block_tables), int(seq),
-        int(tok_begin), int(tok_end), _ptr(k_out), _ptr(v_out), ctypes.byref(shape),
-        _stream(stream)), "coopt_gather_cached_kv")
+    what = "gather_cached_kv"
+    z = _sizes(shape)
+    rows = max(int(tok_end) - int(tok_begin), 0) * z["row"]
+    _call("coopt_gather_cached_kv",
+          *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+        _dev(block_tables, f"{what}: block_tables", dtype=_i32(), min_bytes=z["tables"]), int(seq),
+        int(tok_begin), int(tok_end), _dev(k_out, f"{what}: k_out", elem=2, min_bytes=rows),
+        _dev(v_out, f"{what}: v_out", elem=2, min_bytes=rows), ctypes.byref(shape),
+        _stream(stream))

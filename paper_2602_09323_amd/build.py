@@ -1,4 +1,4 @@
-"""Builds libcoopt_attn.so (HIP, gfx950 only) in-tree with hipcc.
+"""Builds libcoopt_attn.so and the benchmark's libcoopt_probe.so (HIP, gfx950 only) in-tree with hipcc.
 
     python -m paper_2602_09323_amd.build [--force]
 
@@ -17,10 +17,12 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcoopt_attn.so")
-SOURCES = ["kv_write.hip", "decode.hip", "decode_flat.hip", "prefill.hip", "gather.hip", "probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libcoopt_probe.so")      # measurement aid, not the product
+SOURCES = ["kv_write.hip", "decode.hip", "decode_flat.hip", "prefill.hip", "gather.hip"]
+PROBE_SOURCES = ["probe.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("common.hpp", "attn_tile.hpp", "kv_quant.hpp",
                                           "decode_internal.hpp")] + [
-    os.path.join(ROOT, "include", "coopt_attn.h")]
+    os.path.join(ROOT, "include", "coopt_attn.h"), os.path.join(ROOT, "include", "coopt_probe.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-I" + os.path.join(ROOT, "include"),
          # packed-FP32 VALU forms are kept out of the generated code on purpose
@@ -49,10 +51,11 @@ def _compile(src: str) -> str:
 
 
 def needs_build() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(PROBE_LIB):
         return True
-    newest = max(os.path.getmtime(p) for p in [os.path.join(CSRC, s) for s in SOURCES] + HEADERS)
-    return os.path.getmtime(LIB) < newest
+    newest = max(os.path.getmtime(p)
+                 for p in [os.path.join(CSRC, s) for s in SOURCES + PROBE_SOURCES] + HEADERS)
+    return min(os.path.getmtime(LIB), os.path.getmtime(PROBE_LIB)) < newest
 
 
 def build(force: bool = True) -> str:
@@ -60,12 +63,13 @@ def build(force: bool = True) -> str:
     if not force and not needs_build():
         return LIB
     os.makedirs(BUILD, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", LIB, *objs]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("link failed:\n" + res.stderr)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=6) as pool:
+        objs = list(pool.map(_compile, SOURCES + PROBE_SOURCES))
+    for lib, n in ((LIB, objs[:len(SOURCES)]), (PROBE_LIB, objs[len(SOURCES):])):
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", lib, *n]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stderr)
     return LIB
 
 

@@ -10,8 +10,8 @@
 //       Lane (n, grp) then holds the scores of column n for tokens 4grp..4grp+3 of each block.
 //   They are scaled by k_scale[token]*softmax_scale*log2(e), masked beyond the column's visible
 //   prefix (tail groups only), exponentiated against the running max of column n, multiplied by
-//   v_scale[token] and rounded to fp16.  The 8 values a lane holds are exactly its share of the
-//   B operand of
+//   v_scale[token] and split into an fp16 pair hi + lo.  The 8 values a lane holds are exactly
+//   its share of the B operand of
 //   O^T[dim][col] += V^T[dim][token] * P^T[token][col]     16x16x32 MFMAs over the 32 tokens, with
 //       k-slots 8grp..8grp+3 = tokens 4grp..4grp+3 of block A and 8grp+4..8grp+7 = the same tokens
 //       of block B; A operand = V tile rows (row n = dim 16c+n), c = 0 .. d/16-1.
@@ -20,9 +20,11 @@
 //   score (a wave-uniform branch).
 //
 // Numerics: E4M3 codes are exact in fp16, so both products are exact in the fp32 accumulators up
-// to accumulation order.  The weights are carried times a power of two (the reference max is
-// offset in the exponent, which costs nothing) so that P*v_scale stays out of the fp16 subnormal
-// range; the factor is common to the accumulator and the running sum and cancels in O/L.
+// to accumulation order, and the weights P*v_scale enter the second product as hi + lo (21
+// significant bits, two MFMAs against the same V operand).  The weights are carried times a power
+// of two (the reference max is offset in the exponent, which costs nothing) so that P*v_scale
+// stays out of the fp16 subnormal range; the factor is common to the accumulator and the running
+// sum and cancels in O/L.
 //
 // Cache tile layouts (one tile = 16 tokens x d dims of one KV head; E = elements per 16 bytes):
 //   K tile  [d/E chunks][16 tokens][E]             element (tok, dim) at ((dim/E)*16 + tok)*E + dim%E
@@ -261,7 +263,9 @@ __device__ __forceinline__ void token_masks(int cache_valid, uint32_t& m0, uint3
     }
 }
 
-// One online-softmax step of a 16-column tile against a group of two blocks.
+// The group's 2 x 4 scores of this lane in log2 units, z[i] for block A's tokens 4grp+i and
+// z[4+i] for block B's (Opt-KV Eq. 6 dequantisation folded into one multiply per token, Opt-GQA
+// Eq. 8's scaled dot products on the matrix cores), with the tail fix-ups applied.
 //   tail (wave-uniform) = false: every token of both blocks is in the cache and visible to every
 //                 column; the vis / cache arguments are ignored.
 //   tail = true:  visA / visB = how many of this lane's 4 tokens of block A / B column n may
@@ -269,17 +273,13 @@ __device__ __forceinline__ void token_masks(int cache_valid, uint32_t& m0, uint3
 //                 Scores of invisible tokens are capped to -inf (Opt-Pa Eq. 9 / causal limit) with
 //                 a min, which also discards NaN scores from stale keys or scales; V bytes and
 //                 v_scale of absent tokens are zeroed in place, so stale NaN codes or scales
-//                 cannot reach the accumulators.  The fix-ups sit in small branches that touch only temporaries
-//                 and the loaded tile, so the accumulators stay in place across the loop.
-//   m: reference max of column n in log2 units (within kRescaleSlack of the true running max),
-//      identical in the four lanes (n, 0..3).
-//   l: this lane's share of the running sum, acc[c][r] = O^T[16c + 4grp + r][n], both times 2^kPShift.
-// Requirement: whenever m is still -inf, the group holds a token visible to column n.
+//                 cannot reach the accumulators.  The fix-ups sit in small branches that touch only
+//                 temporaries and the loaded tile, so the accumulators stay in place across the loop.
 template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
-                                             const half8_t (&qop)[HEAD_DIM / 32], float& m, float& l,
-                                             floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA,
-                                             int visB, int cacheA, int cacheB, float scale_log2e)
+__device__ __forceinline__ void group_scores(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
+                                             const half8_t (&qop)[HEAD_DIM / 32], bool tail, int visA,
+                                             int visB, int cacheA, int cacheB, float scale_log2e,
+                                             float (&z)[8])
 {
     floatx4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -287,7 +287,6 @@ __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRe
         sA = mfma_16x16x32(k_operand<HEAD_DIM, KV>(A, jj), qop[jj], sA);
         sB = mfma_16x16x32(k_operand<HEAD_DIM, KV>(B, jj), qop[jj], sB);
     }
-    float z[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if constexpr (KV == COOPT_KV_E4M3) {
@@ -325,6 +324,71 @@ __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRe
             }
         }
     }
+}
+
+// Eight binary32 weights as an fp16 pair hi + lo (the B operand of the P.V products is fp16):
+// hi = w with its significand cut to fp16's 11 bits, which the convert then takes over exactly,
+// lo = the remainder, again cut.  hi + lo carries 21 significant bits of w, so the products lose
+// nothing that shows in an fp16 result; a single rounded fp16 weight (11 bits) moved outputs near
+// |x| = 3 by up to 1.3e-3 when one token carries the softmax.  Weights below fp16's normal range
+// (2^-14) keep an absolute error of at most 2^-24 each.
+__device__ __forceinline__ void split_weights(const float (&w)[8], half8_t& hi, half8_t& lo)
+{
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, w[i]) & 0xffffe000u);
+        const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, w[i + 1]) & 0xffffe000u);
+        const half2_t ph = __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(h0, h1));
+        const half2_t pl =
+            __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(w[i] - h0, w[i + 1] - h1));
+        hi[i] = ph.x;
+        hi[i + 1] = ph.y;
+        lo[i] = pl.x;
+        lo[i + 1] = pl.y;
+    }
+}
+
+// O^T += V^T . P^T for the group (Opt-Pa Alg. 3 phase 2): p[0..3] / p[4..7] = this lane's weights
+// of block A's / B's tokens, multiplied here by the tokens' v_scale (Opt-KV Eq. 6) and fed to the
+// matrix cores as an fp16 hi + lo pair against the same V operand.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void group_pv(const BlockRegs<HEAD_DIM, KV>& A,
+                                         const BlockRegs<HEAD_DIM, KV>& B, float (&p)[8],
+                                         floatx4 (&acc)[HEAD_DIM / 16])
+{
+    if constexpr (KV == COOPT_KV_E4M3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] *= A.vs[i];
+            p[4 + i] *= B.vs[i];
+        }
+    }
+    half8_t hi, lo;
+    split_weights(p, hi, lo);
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) {
+        const half4_t va = v_operand<HEAD_DIM, KV>(A, c);
+        const half4_t vb = v_operand<HEAD_DIM, KV>(B, c);
+        const half8_t vop = {va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
+        acc[c] = mfma_16x16x32(vop, hi, acc[c]);
+        acc[c] = mfma_16x16x32(vop, lo, acc[c]);
+    }
+}
+
+// One online-softmax step of a 16-column tile against a group of two blocks (Opt-Pa Eq. 10).
+// tail / vis / cache arguments as in group_scores.
+//   m: reference max of column n in log2 units (within kRescaleSlack of the true running max),
+//      identical in the four lanes (n, 0..3).
+//   l: this lane's share of the running sum, acc[c][r] = O^T[16c + 4grp + r][n], both times 2^kPShift.
+// Requirement: whenever m is still -inf, the group holds a token visible to column n.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
+                                             const half8_t (&qop)[HEAD_DIM / 32], float& m, float& l,
+                                             floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA,
+                                             int visB, int cacheA, int cacheB, float scale_log2e)
+{
+    float z[8];
+    group_scores<HEAD_DIM, KV>(A, B, qop, tail, visA, visB, cacheA, cacheB, scale_log2e, z);
     const float bm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
                            fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
     if (__builtin_amdgcn_ballot_w64(bm > m + kRescaleSlack) != 0) {   // wave-uniform, rare
@@ -344,22 +408,7 @@ __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRe
         p[i] = __builtin_amdgcn_exp2f(z[i] - mm);             // invisible: exp2(-inf) = 0
         l += p[i];
     }
-    if constexpr (KV == COOPT_KV_E4M3) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] *= A.vs[i];
-            p[4 + i] *= B.vs[i];
-        }
-    }
-    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
-                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
-#pragma unroll
-    for (int c = 0; c < HEAD_DIM / 16; ++c) {
-        const half4_t va = v_operand<HEAD_DIM, KV>(A, c);
-        const half4_t vb = v_operand<HEAD_DIM, KV>(B, c);
-        const half8_t vop = {va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
-        acc[c] = mfma_16x16x32(vop, pop, acc[c]);
-    }
+    group_pv<HEAD_DIM, KV>(A, B, p, acc);
 }
 
 // The same step with the softmax statistics reduced the way Opt-Pa states it (Alg. 3, Eq. 10): a
@@ -376,50 +425,8 @@ __device__ __forceinline__ void group_update_block_reduce(
     int cacheB, float scale_log2e, float* red, int lane)
 {
     const int n = lane & 15;
-    floatx4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int jj = 0; jj < HEAD_DIM / 32; ++jj) {
-        sA = mfma_16x16x32(k_operand<HEAD_DIM, KV>(A, jj), qop[jj], sA);
-        sB = mfma_16x16x32(k_operand<HEAD_DIM, KV>(B, jj), qop[jj], sB);
-    }
     float z[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if constexpr (KV == COOPT_KV_E4M3) {
-            z[i] = sA[i] * (A.ks[i] * scale_log2e);
-            z[4 + i] = sB[i] * (B.ks[i] * scale_log2e);
-        } else {
-            z[i] = sA[i] * scale_log2e;
-            z[4 + i] = sB[i] * scale_log2e;
-        }
-    }
-    if (tail) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);
-            z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
-        }
-        if constexpr (KV == COOPT_KV_E4M3) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                A.vs[i] = (i < cacheA) ? A.vs[i] : 0.0f;
-                B.vs[i] = (i < cacheB) ? B.vs[i] : 0.0f;
-            }
-        }
-        uint32_t a0, a1, b0, b1;
-        token_masks<KV>(cacheA, a0, a1);
-        token_masks<KV>(cacheB, b0, b1);
-#pragma unroll
-        for (int j = 0; j < BlockRegs<HEAD_DIM, KV>::NL; ++j) {
-            if constexpr (KV == COOPT_KV_E4M3) {
-                A.v[j] &= a0;
-                B.v[j] &= b0;
-            } else {
-                A.v[j] &= u32x4{a0, a1, a0, a1};
-                B.v[j] &= u32x4{b0, b1, b0, b1};
-            }
-        }
-    }
+    group_scores<HEAD_DIM, KV>(A, B, qop, tail, visA, visB, cacheA, cacheB, scale_log2e, z);
     // ---- max over the group's 32 tokens of column n, through shared memory
     red[lane] = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
                       fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
@@ -441,22 +448,7 @@ __device__ __forceinline__ void group_update_block_reduce(
     l = l * alpha + (lane < 16 ? bs : 0.0f);
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
-    if constexpr (KV == COOPT_KV_E4M3) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] *= A.vs[i];
-            p[4 + i] *= B.vs[i];
-        }
-    }
-    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
-                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
-#pragma unroll
-    for (int c = 0; c < HEAD_DIM / 16; ++c) {
-        const half4_t va = v_operand<HEAD_DIM, KV>(A, c);
-        const half4_t vb = v_operand<HEAD_DIM, KV>(B, c);
-        const half8_t vop = {va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
-        acc[c] = mfma_16x16x32(vop, pop, acc[c]);
-    }
+    group_pv<HEAD_DIM, KV>(A, B, p, acc);
 }
 
 }  // namespace coopt

@@ -13,6 +13,8 @@
 // VALU with one convert per two bytes plus the softmax of 4 scores per lane per block.
 //
 // The per-block arithmetic (two MFMA products around an in-register softmax) is in attn_tile.hpp.
+#include <atomic>
+
 #include "attn_tile.hpp"
 #include "decode_internal.hpp"
 
@@ -268,9 +270,6 @@ partition_reduce_kernel(const float* __restrict__ tmp_out, const float* __restri
 
 // ------------------------------------------------------------------ host side
 
-// tokens_per_group, waves per workgroup, depth, grid waves (one wavefront per SIMD of the 256 CUs)
-static coopt_decode_plan g_plan = {128, 1, 2, 1024, 0};
-
 template <int HEAD_DIM, int KV, bool BIG>
 static void launch_decode_depth(const DecodeArgs& a, int depth, dim3 grid, dim3 block, size_t lds,
                                 hipStream_t stream)
@@ -367,65 +366,124 @@ static int parts_for(const coopt_shape* sh, int tokens_per_part)
 
 using namespace coopt;
 
-extern "C" int coopt_set_decode_plan(const coopt_decode_plan* p)
+// Wavefronts that fill the current device once: one per SIMD, four SIMDs per compute unit.  The
+// compute-unit count is asked of the runtime once per device and kept (256 on MI355X; also the
+// answer where no device can be asked, e.g. size queries on a machine without a GPU).
+static int device_simd_count()
 {
-    if (!p) return COOPT_ERR_NULL;
+    static std::atomic<int> known[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 4 * 256;
+    }
+    const int slot = dev >= 0 && dev < 64 ? dev : 63;
+    int v = known[slot].load(std::memory_order_relaxed);
+    if (v == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        v = 4 * cus;
+        known[slot].store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
+
+static int check_plan(const coopt_decode_plan* p)
+{
     if (p->tokens_per_group <= 0 || p->tokens_per_group % (2 * kBlock) != 0) return COOPT_ERR_SHAPE;
     const int w = p->waves_per_group;
     if (w != 1 && w != 2 && w != 4 && w != 8) return COOPT_ERR_SHAPE;
     if (p->pipeline_depth < 1 || p->pipeline_depth > 3) return COOPT_ERR_SHAPE;
     if (p->grid_waves <= 0 || p->grid_waves > (1 << 20)) return COOPT_ERR_SHAPE;
     if (p->softmax_reduction != 0 && p->softmax_reduction != 1) return COOPT_ERR_SHAPE;
-    g_plan = *p;
     return COOPT_OK;
 }
 
-extern "C" void coopt_get_decode_plan(coopt_decode_plan* p)
+extern "C" void coopt_default_decode_plan(coopt_decode_plan* p)
 {
-    if (p) *p = g_plan;
+    if (!p) return;
+    p->tokens_per_group = 128;
+    p->waves_per_group = 1;
+    p->pipeline_depth = 2;
+    p->grid_waves = device_simd_count();
+    p->softmax_reduction = 0;
 }
 
-static FlatPlan flat_plan()
+// The plan a call runs under: the caller's (validated), or the default for the current device.
+static int resolve_plan(const coopt_decode_plan* given, coopt_decode_plan* plan)
 {
-    return FlatPlan{g_plan.tokens_per_group, g_plan.pipeline_depth, g_plan.grid_waves,
-                    g_plan.softmax_reduction};
+    if (given) {
+        *plan = *given;
+        return check_plan(plan);
+    }
+    coopt_default_decode_plan(plan);
+    return COOPT_OK;
 }
 
-extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh)
+static FlatPlan flat_plan(const coopt_decode_plan& p)
 {
-    if (check_shape(sh) != COOPT_OK) return 0;
-    return flat_workspace_bytes(sh, flat_plan());
+    return FlatPlan{p.tokens_per_group, p.pipeline_depth, p.grid_waves, p.softmax_reduction};
+}
+
+// Shape, plan and the workspace's size and alignment, for the entry points of the balanced path.
+static int check_balanced(const coopt_shape* sh, const coopt_decode_plan* given,
+                          coopt_decode_plan* plan, const void* workspace, size_t workspace_bytes)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    st = resolve_plan(given, plan);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    if (!workspace) return COOPT_ERR_NULL;
+    if (workspace_bytes < flat_workspace_bytes(sh, flat_plan(*plan))) return COOPT_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    return COOPT_OK;
+}
+
+extern "C" size_t coopt_decode_workspace_bytes(const coopt_shape* sh, const coopt_decode_plan* given)
+{
+    coopt_decode_plan plan;
+    if (check_shape(sh) != COOPT_OK || resolve_plan(given, &plan) != COOPT_OK) return 0;
+    return flat_workspace_bytes(sh, flat_plan(plan));
 }
 
 extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cache,
                                       const float* k_scale, const float* v_scale,
                                       const int32_t* block_tables, const int32_t* context_lens,
                                       void* out, void* workspace, size_t workspace_bytes,
-                                      const coopt_shape* sh, void* hip_stream)
+                                      const coopt_decode_plan* given, const coopt_shape* sh,
+                                      void* hip_stream)
 {
+    coopt_decode_plan plan;
     int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    st = resolve_plan(given, &plan);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
     st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
     if (st != COOPT_OK) return st;
     if (!out) return COOPT_ERR_NULL;
     hipStream_t stream = (hipStream_t)hip_stream;
-    DecodeArgs a = make_args(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
-    a.out = (half_t*)out;
     if (!workspace) {
         // one workgroup per (sequence, KV head) covers the whole context and writes `out`
+        DecodeArgs a = make_args(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
+        a.out = (half_t*)out;
         a.tokens_per_part = sh->max_blocks_per_seq * kBlock;
         a.max_parts = 1;
         a.direct = 1;
-        launch_decode(a, sh, 8, g_plan.pipeline_depth, stream);
+        launch_decode(a, sh, 8, plan.pipeline_depth, stream);
         return launch_status();
     }
-    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
-    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
-                           workspace, sh, flat_plan(), stream);
+    st = check_balanced(sh, given, &plan, workspace, workspace_bytes);
     if (st != COOPT_OK) return st;
-    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
+    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                           workspace, sh, flat_plan(plan), stream);
+    if (st != COOPT_OK) return st;
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream);
 }
 
 extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
@@ -433,46 +491,49 @@ extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
                                            void* k_cache, void* v_cache, float* k_scale,
                                            float* v_scale, const int32_t* block_tables,
                                            const int32_t* context_lens, void* out, void* workspace,
-                                           size_t workspace_bytes, const coopt_shape* sh,
-                                           void* hip_stream)
+                                           size_t workspace_bytes, const coopt_decode_plan* given,
+                                           const coopt_shape* sh, void* hip_stream)
 {
-    int st = check_shape(sh);
+    coopt_decode_plan plan;
+    int st = check_balanced(sh, given, &plan, workspace, workspace_bytes);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
     if (!k || !v || !slot_mapping) return COOPT_ERR_NULL;
     st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
     if (st != COOPT_OK) return st;
-    if (!out || !workspace) return COOPT_ERR_NULL;
-    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
+    if (!out) return COOPT_ERR_NULL;
     hipStream_t stream = (hipStream_t)hip_stream;
     const FlatAppend append{k, v, slot_mapping};
     st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
-                           workspace, sh, flat_plan(), stream, &append);
+                           workspace, sh, flat_plan(plan), stream, &append);
     if (st != COOPT_OK) return st;
-    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream);
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream);
 }
 
-extern "C" size_t coopt_decode_schedule_bytes(const coopt_shape* sh)
+extern "C" size_t coopt_decode_schedule_bytes(const coopt_shape* sh, const coopt_decode_plan* given)
 {
-    if (check_shape(sh) != COOPT_OK) return 0;
-    return flat_schedule_bytes(sh, flat_plan());
+    coopt_decode_plan plan;
+    if (check_shape(sh) != COOPT_OK || resolve_plan(given, &plan) != COOPT_OK) return 0;
+    return flat_schedule_bytes(sh, flat_plan(plan));
 }
 
 extern "C" int coopt_decode_schedule_prepare(const int32_t* block_tables,
                                              const int32_t* context_lens,
                                              const int64_t* slot_mapping, void* schedule,
-                                             size_t schedule_bytes, const coopt_shape* sh,
-                                             void* hip_stream)
+                                             size_t schedule_bytes, const coopt_decode_plan* given,
+                                             const coopt_shape* sh, void* hip_stream)
 {
+    coopt_decode_plan plan;
     int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    st = resolve_plan(given, &plan);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
     if (!block_tables || !context_lens || !schedule) return COOPT_ERR_NULL;
-    const size_t need = flat_schedule_bytes(sh, flat_plan());
+    const size_t need = flat_schedule_bytes(sh, flat_plan(plan));
     if (need == 0) return COOPT_ERR_SHAPE;
     if (schedule_bytes < need || ((uintptr_t)schedule & 15u) != 0) return COOPT_ERR_WORKSPACE;
-    return launch_flat_prepare(block_tables, context_lens, slot_mapping, schedule, sh, flat_plan(),
+    return launch_flat_prepare(block_tables, context_lens, slot_mapping, schedule, sh, flat_plan(plan),
                                (hipStream_t)hip_stream);
 }
 
@@ -482,9 +543,11 @@ extern "C" int coopt_paged_gqa_decode_scheduled(const void* k, const void* v,
                                                 float* v_scale, const int32_t* context_lens,
                                                 void* out, void* workspace, size_t workspace_bytes,
                                                 const void* schedule, size_t schedule_bytes,
+                                                const coopt_decode_plan* given,
                                                 const coopt_shape* sh, void* hip_stream)
 {
-    int st = check_shape(sh);
+    coopt_decode_plan plan;
+    int st = check_balanced(sh, given, &plan, workspace, workspace_bytes);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
     const bool fused = k || v || slot_mapping;
@@ -492,50 +555,46 @@ extern "C" int coopt_paged_gqa_decode_scheduled(const void* k, const void* v,
     // no block table here: the schedule's records name the tiles
     st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, context_lens, context_lens, sh);
     if (st != COOPT_OK) return st;
-    if (!workspace || !schedule) return COOPT_ERR_NULL;
-    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
-    const size_t need = flat_schedule_bytes(sh, flat_plan());
+    if (!schedule) return COOPT_ERR_NULL;
+    const size_t need = flat_schedule_bytes(sh, flat_plan(plan));
     if (need == 0) return COOPT_ERR_SHAPE;
     if (schedule_bytes < need || ((uintptr_t)schedule & 15u) != 0) return COOPT_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     const FlatAppend append{k, v, slot_mapping};
     st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, nullptr, context_lens, workspace,
-                           sh, flat_plan(), stream, fused ? &append : nullptr, schedule);
+                           sh, flat_plan(plan), stream, fused ? &append : nullptr, schedule);
     if (st != COOPT_OK || !out) return st;
-    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(), stream, schedule, fused);
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream, schedule, fused);
 }
 
 extern "C" int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,
                                             const float* k_scale, const float* v_scale,
                                             const int32_t* block_tables,
                                             const int32_t* context_lens, void* workspace,
-                                            size_t workspace_bytes, const coopt_shape* sh,
-                                            void* hip_stream)
+                                            size_t workspace_bytes, const coopt_decode_plan* given,
+                                            const coopt_shape* sh, void* hip_stream)
 {
-    int st = check_shape(sh);
+    coopt_decode_plan plan;
+    int st = check_balanced(sh, given, &plan, workspace, workspace_bytes);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
     st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
     if (st != COOPT_OK) return st;
-    if (!workspace) return COOPT_ERR_NULL;
-    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
     return launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
-                             workspace, sh, flat_plan(), (hipStream_t)hip_stream);
+                             workspace, sh, flat_plan(plan), (hipStream_t)hip_stream);
 }
 
 extern "C" int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* workspace,
                                             size_t workspace_bytes, void* out,
-                                            const coopt_shape* sh, void* hip_stream)
+                                            const coopt_decode_plan* given, const coopt_shape* sh,
+                                            void* hip_stream)
 {
-    int st = check_shape(sh);
+    coopt_decode_plan plan;
+    int st = check_balanced(sh, given, &plan, workspace, workspace_bytes);
     if (st != COOPT_OK) return st;
     if (sh->num_seqs == 0) return COOPT_OK;
-    if (!context_lens || !workspace || !out) return COOPT_ERR_NULL;
-    if (workspace_bytes < coopt_decode_workspace_bytes(sh)) return COOPT_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 15u) != 0) return COOPT_ERR_WORKSPACE;
-    return launch_flat_merge(context_lens, const_cast<void*>(workspace), out, sh, flat_plan(),
+    if (!context_lens || !out) return COOPT_ERR_NULL;
+    return launch_flat_merge(context_lens, const_cast<void*>(workspace), out, sh, flat_plan(plan),
                              (hipStream_t)hip_stream);
 }
 
@@ -543,9 +602,12 @@ extern "C" int coopt_paged_gqa_decode_partitioned(
     const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
     const float* v_scale, const int32_t* block_tables, const int32_t* context_lens,
     int32_t partition_size, float* tmp_out, float* max_logits, float* exp_sums, int32_t max_parts,
-    const coopt_shape* sh, void* hip_stream)
+    const coopt_decode_plan* given, const coopt_shape* sh, void* hip_stream)
 {
+    coopt_decode_plan plan;
     int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    st = resolve_plan(given, &plan);
     if (st != COOPT_OK) return st;
     if (partition_size <= 0 || partition_size % kBlock != 0 || max_parts <= 0)
         return COOPT_ERR_SHAPE;
@@ -562,7 +624,7 @@ extern "C" int coopt_paged_gqa_decode_partitioned(
     a.tokens_per_part = partition_size;
     a.max_parts = max_parts;
     a.direct = 0;
-    launch_decode(a, sh, g_plan.waves_per_group, g_plan.pipeline_depth, (hipStream_t)hip_stream);
+    launch_decode(a, sh, plan.waves_per_group, plan.pipeline_depth, (hipStream_t)hip_stream);
     return launch_status();
 }
 

@@ -64,15 +64,16 @@ struct FlatSchedule {
         return t > 0 ? H_k * (groups_of(t) + extra) : 0;
     }
 
-    // Tokens of sequence s that this launch reads from the cache: all of them, or -- in the fused
-    // step, for a sequence whose new token is being written by this same launch -- all but the last.
-    __device__ __forceinline__ int cached_len(int s) const
+    // Tokens of sequence s that this launch attends to.  In the fused step that includes the token
+    // the launch itself appends: the wavefront that streams the pair's last group takes it from
+    // the new rows (see take_new_token), not from the cache.
+    __device__ __forceinline__ int cached_len(int s) const { return lens[s]; }
+
+    // Fused step: does sequence s append a token in this launch (Opt-KV Eq. 5: a negative slot
+    // filters the token out; an empty sequence has none)?
+    __device__ __forceinline__ bool appends(int s, int t) const
     {
-        int t = lens[s];
-        int64_t slot = -1;
-        if (new_slots) slot = new_slots[s];      // not behind `t > 0`: the two loads overlap
-        if (t > 0 && slot >= 0) t -= 1;
-        return t;
+        return new_slots != nullptr && t > 0 && new_slots[s] >= 0;
     }
 
     __device__ __forceinline__ FlatSchedule(const int32_t* context_lens, const int64_t* appended,
@@ -168,6 +169,7 @@ struct FlatArgs {
     float* max_logits;    // [S*H_q][max_slots]
     float* exp_sums;
     int32_t* counts;      // [S*H_k] partials per (sequence, KV head), written by the split kernel
+    uint32_t* ws_header;  // first 16 bytes of the workspace: [0] ws_tag, left by the split kernel
     half_t* out;
     int32_t num_seqs, H_q, H_k, G;
     int32_t max_blocks;
@@ -175,8 +177,8 @@ struct FlatArgs {
     int32_t min_share;    // cost units (groups plus pair extras) per workgroup, lower bound
     int32_t pair_extra;   // cost units charged to a share for every pair that ends inside it
     int32_t pool_tiles;   // num_blocks * H_k
-    int32_t decode_wgs;   // workgroups that run attention; in the fused step the grid continues
-                          // with one workgroup per (sequence, KV head) that appends the new token
+    int32_t decode_wgs;   // workgroups (= wavefronts) of the attention launch
+    uint32_t ws_tag;      // names the plan the workspace's partials were laid out for (see ws_tag_of)
     float scale_log2e;
     // fused step only (new_slots != NULL): the token every sequence appends, and the cache as
     // written to
@@ -275,12 +277,6 @@ __device__ __forceinline__ void stage_q_operand(unsigned char* stage, const half
 #endif
 }
 
-// Fused step: one wavefront per (sequence, KV head) appends the sequence's new token to the cache
-// (Opt-KV Eq. 5 and Alg. 1 phase 1, exactly as the cache-write kernel does) and contributes that
-// token's share of the attention as one more partial of the pair, (m, l, o) = (z, 1, v~), from the
-// values it has just quantised -- the attention workgroups of the same launch read only the tokens
-// that were in the cache before, so nothing in the launch waits for anything else.  It also leaves
-// the pair's partial count (the attention workgroups' partials plus this one).
 // Partials the attention workgroups write for (sequence, KV head) pair `pair`, from the schedule.
 __device__ __forceinline__ int attention_partials_of(const FlatArgs& a, const FlatSchedule& sched,
                                                      const FlatCut& cut, int ctotal, int pair)
@@ -291,72 +287,6 @@ __device__ __forceinline__ int attention_partials_of(const FlatArgs& a, const Fl
     if (ng <= 0 || ctotal <= 0) return 0;
     const int pair_first = sched.cost_first_of(seq) + g * (ng + a.pair_extra) + a.pair_extra;
     return cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
-}
-
-// `count` = partials of the pair that come from the attention workgroups.  With `total` >= 0 (a
-// prepared schedule, whose count includes this token's partial) it is derived from that instead
-// and the pair's count is not written again.
-template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void append_and_attend(const FlatArgs& a, int pair, int lane, int count,
-                                                  int total)
-{
-    constexpr int E = HEAD_DIM / 64;
-    const int seq = pair / a.H_k;
-    const int g = pair - seq * a.H_k;
-    if (seq >= a.num_seqs) return;
-    const int64_t slot = a.new_slots[seq];
-    const bool appends = slot >= 0 && a.context_lens[seq] > 0;
-    if (total >= 0) count = total - (appends ? 1 : 0);
-    else if (lane == 0) a.counts[pair] = count + (appends ? 1 : 0);
-    count = min(max(count, 0), a.max_slots - 1);                // whatever the schedule says, stay inside
-    if (!appends) return;                                       // Eq. 5: filtered token
-
-    const int64_t blk = slot / kBlock;
-    const int off = (int)(slot - blk * kBlock);
-    const size_t tile = (size_t)(blk * a.H_k + g);
-    const half_t* k_row = a.k_new + (size_t)pair * HEAD_DIM;
-    const half_t* v_row = a.v_new + (size_t)pair * HEAD_DIM;
-    float kd[E], vd[E];                                         // the values attention will see
-    if constexpr (KV == COOPT_KV_E4M3) {
-        const QuantRow<HEAD_DIM> qr = quantise_row_to_cache<HEAD_DIM>(
-            k_row, v_row, tile, off, lane, a.k_cache_w, a.v_cache_w, a.k_scale_w, a.v_scale_w);
-        const half2_t kh = e4m3x2_to_half2<false>(qr.k_codes), vh = e4m3x2_to_half2<false>(qr.v_codes);
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            kd[e] = (float)kh[e] * qr.k_scale;
-            vd[e] = (float)vh[e] * qr.v_scale;
-        }
-    } else {
-        half_t* kc = reinterpret_cast<half_t*>(a.k_cache_w) + tile * (kBlock * HEAD_DIM);
-        half_t* vc = reinterpret_cast<half_t*>(a.v_cache_w) + tile * (kBlock * HEAD_DIM);
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int dim = lane * E + e;
-            const half_t kk = k_row[dim], vv = v_row[dim];
-            kc[k_tile_index<2>(off, dim)] = kk;
-            vc[v_tile_index<2>(off, dim)] = vv;
-            kd[e] = (float)kk;
-            vd[e] = (float)vv;
-        }
-    }
-    const int slot_idx = count;                                 // after the attention partials
-    for (int h = 0; h < a.G; ++h) {
-        const size_t row = (size_t)seq * a.H_q + g * a.G + h;
-        const half_t* q_row = a.q + row * HEAD_DIM + lane * E;
-        float dot = 0.0f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) dot += (float)q_row[e] * kd[e];
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) dot += __shfl_xor(dot, s);
-        const size_t at = row * a.max_slots + slot_idx;
-        float* dst = a.tmp_out + at * HEAD_DIM + lane * E;
-#pragma unroll
-        for (int e = 0; e < E; ++e) dst[e] = vd[e];
-        if (lane == 0) {
-            a.max_logits[at] = dot * a.scale_log2e * kLn2;      // natural-log units
-            a.exp_sums[at] = 1.0f;
-        }
-    }
 }
 
 // Where a wavefront's share comes from.  A source describes the share as entries 0 .. size()-1
@@ -375,7 +305,7 @@ struct LiveSource {
     int lane, share, x_begin, x_end;
     int nc = 0;
     int seq_l = 0, cfirst_l = 0, t_l = 0, g_l = 0, gi_l = 0, tile_l = -1;
-    unsigned long long last_mask = 0;
+    unsigned long long last_mask = 0, append_mask = 0;
 
     __device__ __forceinline__ LiveSource(const FlatArgs& args, const FlatSchedule& s, const FlatCut& c,
                                           int lane_id, int share_id, int xb, int xe)
@@ -407,6 +337,11 @@ struct LiveSource {
         // entries that end a segment: last group of their pair, or last group of the share
         last_mask = __builtin_amdgcn_ballot_w64(
             in_chunk && (lane & 1) == 0 && (gi_l == ng_l - 1 || xl == x_end - 1));
+        // entries that hold the token their sequence appends in this launch (the pair's last group)
+        append_mask = 0;
+        if (a.new_slots)
+            append_mask = __builtin_amdgcn_ballot_w64(in_chunk && (lane & 1) == 0 && gi_l == ng_l - 1 &&
+                                                      sched.appends(seq_l, t_l));
     }
     __device__ __forceinline__ void tiles(int e, int& tA, int& tB) const
     {
@@ -419,6 +354,11 @@ struct LiveSource {
         return __builtin_amdgcn_readlane(t_l, 2 * e) - 2 * kBlock * __builtin_amdgcn_readlane(gi_l, 2 * e);
     }
     __device__ __forceinline__ bool last(int e) const { return (last_mask >> (2 * e)) & 1; }
+    __device__ __forceinline__ bool appends(int e) const { return (append_mask >> (2 * e)) & 1; }
+    __device__ __forceinline__ int pair(int e) const
+    {
+        return __builtin_amdgcn_readlane(seq_l, 2 * e) * a.H_k + __builtin_amdgcn_readlane(g_l, 2 * e);
+    }
     // first entry of the segment after the one that contains entry e (nc if there is none)
     __device__ __forceinline__ int next_segment(int e) const
     {
@@ -443,8 +383,7 @@ struct LiveSource {
         ps.row0 = seq * a.H_q + g * a.G;
         ps.slot = share - cut.wg_of(pair_first);
         // the pair's first workgroup also counts the pair's partials
-        // (in the fused step the appending workgroups do the counting)
-        ps.count_at = (ps.slot == 0 && !a.new_slots) ? seq * a.H_k + g : -1;
+        ps.count_at = ps.slot == 0 ? seq * a.H_k + g : -1;
         ps.count = cut.wg_of(pair_first + ng - 1) - cut.wg_of(pair_first) + 1;
         return ps;
     }
@@ -455,11 +394,14 @@ struct LiveSource {
 //   counts[num_seqs * H_k]: partials per (sequence, KV head)       (rounded up to 4 words)
 //   one region per attention workgroup, `stride` words each:
 //     [0] entries in the share  [1..3] unused  then one 4-word record per entry:
-//     tile of block A, tile of block B (-1: absent), pair | last << 31, rem | slot << 16
-//   pair = sequence * H_k + KV head; rem as LiveSource::rem, capped at 0x7fff; slot = index of the
-//   partial this workgroup writes for the pair.
+//     tile of block A, tile of block B (-1: absent), pair | appends << 30 | last << 31,
+//     rem | slot << 16
+//   pair = sequence * H_k + KV head (< 2^27); appends = the entry is the pair's last group and its
+//   sequence appends a token in the launch (fused step); rem as LiveSource::rem, capped at 0x7fff;
+//   slot = index of the partial this workgroup writes for the pair.
 constexpr int kSchedHeaderWords = 16;
 constexpr int kSchedRemCap = 0x7fff;
+constexpr int kSchedPairMask = 0x3fffffff;
 
 typedef unsigned int sched_rec_t __attribute__((ext_vector_type(4)));
 
@@ -472,7 +414,7 @@ struct PreparedSource {
     sched_rec_t first;
     int nc = 0;
     uint32_t tA_l = ~0u, tB_l = ~0u, pair_l = 0, rs_l = 0;
-    unsigned long long last_mask = 0;
+    unsigned long long last_mask = 0, append_mask = 0;
 
     __device__ __forceinline__ PreparedSource(const FlatArgs& args, const uint32_t* reg, int lane_id, int n,
                                               sched_rec_t first_chunk)
@@ -490,6 +432,7 @@ struct PreparedSource {
         pair_l = have ? r.z : 0u;
         rs_l = have ? r.w : 0u;
         last_mask = __builtin_amdgcn_ballot_w64(have && (pair_l >> 31) != 0);
+        append_mask = __builtin_amdgcn_ballot_w64(have && ((pair_l >> 30) & 1u) != 0);
     }
     __device__ __forceinline__ void tiles(int e, int& tA, int& tB) const
     {
@@ -501,6 +444,11 @@ struct PreparedSource {
         return __builtin_amdgcn_readlane((int)rs_l, e) & 0xffff;
     }
     __device__ __forceinline__ bool last(int e) const { return (last_mask >> e) & 1; }
+    __device__ __forceinline__ bool appends(int e) const { return (append_mask >> e) & 1; }
+    __device__ __forceinline__ int pair(int e) const
+    {
+        return __builtin_amdgcn_readlane((int)pair_l, e) & kSchedPairMask;
+    }
     __device__ __forceinline__ int next_segment(int e) const
     {
         const unsigned long long rest = e < 32 ? last_mask >> e : 0ull;
@@ -508,13 +456,12 @@ struct PreparedSource {
     }
     __device__ __forceinline__ const half_t* q_rows(int e, int head_dim) const
     {
-        const int pair = __builtin_amdgcn_readlane((int)pair_l, e) & 0x7fffffff;
-        return a.q + (size_t)pair * a.G * head_dim;
+        return a.q + (size_t)pair(e) * a.G * head_dim;
     }
     __device__ __forceinline__ PartialSlot slot(int e) const
     {
         PartialSlot ps;
-        ps.row0 = (__builtin_amdgcn_readlane((int)pair_l, e) & 0x7fffffff) * a.G;
+        ps.row0 = pair(e) * a.G;
         ps.slot = (int)((uint32_t)__builtin_amdgcn_readlane((int)rs_l, e) >> 16);
         ps.count_at = -1;                  // the counts were written with the schedule
         ps.count = 0;
@@ -522,16 +469,174 @@ struct PreparedSource {
     }
 };
 
+// ---- fused step: the token a sequence appends in this launch (Opt-KV Eq. 5, Alg. 1 phase 1)
+//
+// The wavefront that streams a pair's last group also takes the pair's new token: it quantises the
+// row exactly as the cache-write kernel does (kv_quant.hpp), puts the row's cache elements into
+// the K and V operand registers of that group in place of whatever the cache held at that slot,
+// attends over it like over any other token, and stores the row into the cache when its share is
+// done.  No other wavefront reads that group, so nothing in the launch waits for anything else.
+
+// What lane i holds of the new row: cache elements i*E .. i*E+E-1 (E = HEAD_DIM/64) of the K row
+// and of the V row -- E4M3 codes or fp16 bit patterns -- and the row's scales (E4M3 only).
+struct NewToken {
+    uint32_t k, v;
+    float ks, vs;
+    int tile, off;      // destination: tile = physical block * H_k + KV head, token offset in it
+    bool have;
+};
+
+// Replaces token `pos` (wave-uniform, 0..31: block A holds 0..15, block B the rest) of a loaded
+// group by the row staged in LDS at `row` (K row, then V row, cache elements in dim order).
+// K: the four lanes (off, grp), off = pos % 16, take the 16-byte chunks 4j+grp of the row.  V: the
+// sixteen lanes (n, off/4) insert the row's element of dim 16*(W*j+cc)+n at element 4*cc + off%4 of
+// their 16 bytes.  Both blocks get whole-register selects with constant element indices (the block
+// is chosen by the masks, not by a branch: a branch over two tiles would make the compiler address
+// them through a pointer and move the whole pipeline's registers to scratch memory).
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void patch_token(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
+                                            int pos, const unsigned char* row, int lane, float ks,
+                                            float vs)
+{
+    constexpr int ES = BlockRegs<HEAD_DIM, KV>::ES;
+    constexpr int NL = BlockRegs<HEAD_DIM, KV>::NL;
+    constexpr int W = 4 / ES;                           // 16-dim groups per 16 bytes of a V tile
+    const int n = lane & 15, grp = lane >> 4;
+    const int off = pos & (kBlock - 1);
+    const bool in_a = pos < kBlock;
+    const bool k_lane = n == off;
+    const bool v_lane = grp == (off >> 2);
+    const unsigned char* vrow = row + HEAD_DIM * ES;
+    const uint32_t ka = (k_lane && in_a) ? 0xffffffffu : 0u;
+    const uint32_t kb = (k_lane && !in_a) ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        const u32x4 kk = *reinterpret_cast<const u32x4*>(row + 16 * (4 * j + grp));
+        A.k[j] = (A.k[j] & ~ka) | (kk & ka);
+        B.k[j] = (B.k[j] & ~kb) | (kk & kb);
+    }
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        u32x4 val, mask;
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) {
+            if constexpr (ES == 1) {          // dword dw = dim group cc = dw, byte off%4 of it
+                const uint32_t b = vrow[16 * (W * j + dw) + n];
+                const int sh = 8 * (off & 3);
+                val[dw] = b << sh;
+                mask[dw] = v_lane ? (0xffu << sh) : 0u;
+            } else {                          // dword dw = dim group cc = dw/2, tokens 2(dw%2), +1
+                const uint32_t h = *reinterpret_cast<const uint16_t*>(vrow + 2 * (16 * (W * j + (dw >> 1)) + n));
+                const int sh = 16 * (off & 1);
+                val[dw] = h << sh;
+                mask[dw] = (v_lane && ((off & 3) >> 1) == (dw & 1)) ? (0xffffu << sh) : 0u;
+            }
+        }
+        const u32x4 ma = in_a ? mask : u32x4{0u, 0u, 0u, 0u};
+        const u32x4 mb = in_a ? u32x4{0u, 0u, 0u, 0u} : mask;
+        A.v[j] = (A.v[j] & ~ma) | (val & ma);
+        B.v[j] = (B.v[j] & ~mb) | (val & mb);
+    }
+    if constexpr (KV == COOPT_KV_E4M3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool mine = v_lane && i == (off & 3);
+            A.ks[i] = (mine && in_a) ? ks : A.ks[i];
+            A.vs[i] = (mine && in_a) ? vs : A.vs[i];
+            B.ks[i] = (mine && !in_a) ? ks : B.ks[i];
+            B.vs[i] = (mine && !in_a) ? vs : B.vs[i];
+        }
+    }
+}
+
+// row_k / row_v: the lane's E fp16 values of the new K / V row as loaded (low bits first).  pos =
+// the token's position inside the group (0..31), tA / tB = the group's tiles.  `stage` is
+// 2 * HEAD_DIM cache elements of LDS private to the wavefront.
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ NewToken take_new_token(BlockRegs<HEAD_DIM, KV>& A,
+                                                   BlockRegs<HEAD_DIM, KV>& B, uint32_t row_k,
+                                                   uint32_t row_v, int pos, int tA, int tB,
+                                                   unsigned char* stage, int lane)
+{
+    constexpr int E = HEAD_DIM / 64;
+    constexpr int ES = BlockRegs<HEAD_DIM, KV>::ES;
+    NewToken nt;
+    if constexpr (KV == COOPT_KV_E4M3) {
+        float kx[E], vx[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            kx[e] = (float)__builtin_bit_cast(half_t, (uint16_t)(row_k >> (16 * e)));
+            vx[e] = (float)__builtin_bit_cast(half_t, (uint16_t)(row_v >> (16 * e)));
+        }
+        const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM>(kx, vx);
+        nt.k = qr.k_codes;
+        nt.v = qr.v_codes;
+        nt.ks = qr.k_scale;
+        nt.vs = qr.v_scale;
+    } else {
+        nt.k = row_k;
+        nt.v = row_v;
+        nt.ks = nt.vs = 1.0f;
+    }
+    constexpr int LB = E * ES;                          // bytes per lane and row
+    unsigned char* kd = stage + LB * lane;
+    unsigned char* vd = stage + HEAD_DIM * ES + LB * lane;
+    if constexpr (LB == 1) {
+        *kd = (unsigned char)nt.k;
+        *vd = (unsigned char)nt.v;
+    } else if constexpr (LB == 2) {
+        *reinterpret_cast<uint16_t*>(kd) = (uint16_t)nt.k;
+        *reinterpret_cast<uint16_t*>(vd) = (uint16_t)nt.v;
+    } else {
+        *reinterpret_cast<uint32_t*>(kd) = nt.k;
+        *reinterpret_cast<uint32_t*>(vd) = nt.v;
+    }
+    nt.off = pos & (kBlock - 1);
+    nt.tile = pos < kBlock ? tA : tB;
+    nt.have = true;
+    patch_token<HEAD_DIM, KV>(A, B, pos, stage, lane, nt.ks, nt.vs);
+    return nt;
+}
+
+// The new row into the cache (the same bytes the cache-write kernels store).
+template <int HEAD_DIM, int KV>
+__device__ __forceinline__ void store_new_token(const FlatArgs& a, const NewToken& nt, int lane)
+{
+    constexpr int E = HEAD_DIM / 64;
+    if constexpr (KV == COOPT_KV_E4M3) {
+        QuantRow<HEAD_DIM> qr;
+        qr.k_codes = nt.k;
+        qr.v_codes = nt.v;
+        qr.k_scale = nt.ks;
+        qr.v_scale = nt.vs;
+        store_quant_row<HEAD_DIM>(qr, (size_t)nt.tile, nt.off, lane, a.k_cache_w, a.v_cache_w,
+                                  a.k_scale_w, a.v_scale_w);
+    } else {
+        uint16_t* kc = reinterpret_cast<uint16_t*>(a.k_cache_w) + (size_t)nt.tile * (kBlock * HEAD_DIM);
+        uint16_t* vc = reinterpret_cast<uint16_t*>(a.v_cache_w) + (size_t)nt.tile * (kBlock * HEAD_DIM);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int dim = lane * E + e;
+            kc[k_tile_index<2>(nt.off, dim)] = (uint16_t)(nt.k >> (16 * e));
+            vc[v_tile_index<2>(nt.off, dim)] = (uint16_t)(nt.v >> (16 * e));
+        }
+    }
+}
+
 // The wave's share is ONE stream of groups that runs across the boundaries between (sequence, KV
 // head) pairs.  The loads of the next pair's first groups are in flight while the last groups of
 // the current pair are being consumed, and the pair's partial is stored from the accumulator
 // registers in between.
-template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, typename Source>
+// APPEND (fused step): entries flagged by the source also take their pair's new token.
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, bool APPEND, typename Source>
 __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, unsigned char* q_stage,
                                              int lane)
 {
-    // vector-memory loads per group: two blocks of K and V chunks plus, for FP8, their scales
-    constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (KV == COOPT_KV_E4M3 ? 2 : 0));
+    // vector-memory loads per group: two blocks of K and V chunks plus, for FP8, their scales;
+    // in the fused step also the two new rows (requested with every group, empty where the group
+    // appends nothing, so that the count is the same on every path)
+    constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (KV == COOPT_KV_E4M3 ? 2 : 0)) +
+                                (APPEND ? 2 : 0);
     // s_waitcnt immediates (gfx9 layout: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
     constexpr int kWaitStaged = (kGroupLoads & 15) | (7 << 4) | (15 << 8) | ((kGroupLoads >> 4) << 14);
     constexpr int kWaitLds = 15 | (7 << 4) | (0 << 8) | (3 << 14);
@@ -545,6 +650,10 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
     constexpr int kParkAcc = HEAD_DIM / 16 * 1024;               // parked o, then m and l per lane
     unsigned char* park = q_stage + HEAD_DIM / 32 * 1024;
     float* red = reinterpret_cast<float*>(park + kParkAcc + 512);  // BLOCK_REDUCE: 128 floats
+    unsigned char* row_stage = park + kParkAcc + 1024;             // APPEND: one new K row, one V row
+    uint32_t row_k[DEPTH], row_v[DEPTH];                           // APPEND: the rows in flight
+    NewToken pending;                                              // APPEND: a row not stored yet
+    pending.have = false;
     PartialSlot parked;
     parked.row0 = -1;
     half8_t q_cur[HEAD_DIM / 32];
@@ -567,8 +676,29 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
             loader.issue(r[0], max(tA, 0), e < nc && tA >= 0);
             loader.issue(r[1], max(tB, 0), e < nc && tB >= 0);
         };
+        // the lane's E fp16 values of the new K and V rows of entry e's pair (zeros unless flagged)
+        auto issue_rows = [&](uint32_t& rk, uint32_t& rv, int e) {
+            constexpr int E = HEAD_DIM / 64;
+            const int ee = min(e, 31);
+            const int extent = (e < nc && src.appends(ee)) ? HEAD_DIM * 2 : 0;
+            const size_t at = (size_t)src.pair(ee) * HEAD_DIM;
+            const __amdgpu_buffer_rsrc_t bk = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<half_t*>(a.k_new + at), 0, extent, 0x00020000);
+            const __amdgpu_buffer_rsrc_t bv = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<half_t*>(a.v_new + at), 0, extent, 0x00020000);
+            if constexpr (E == 2) {
+                rk = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(bk, 4 * lane, 0, 0);
+                rv = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(bv, 4 * lane, 0, 0);
+            } else {
+                rk = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bk, 2 * lane, 0, 0);
+                rv = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bv, 2 * lane, 0, 0);
+            }
+        };
 #pragma unroll
+        // (the new rows are requested ahead of their entry's tiles: loads return in order, so the
+        // rows are there -- and get quantised -- while the wave would only wait for the tiles)
         for (int u = 0; u < DEPTH; ++u) {
+            if constexpr (APPEND) issue_rows(row_k[u], row_v[u], u);
             issue_entry(regs[u], u);
             __builtin_amdgcn_sched_barrier(0);     // keep the stages' loads in program order
         }
@@ -579,6 +709,16 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                 if (e < nc) {
                     const int rem = src.rem(e);
                     const int visA = rem - 4 * grp;
+                    if constexpr (APPEND) {
+                        if (src.appends(e)) {        // the pair's new token is the group's last
+                            int tA, tB;
+                            src.tiles(e, tA, tB);
+                            if (pending.have) store_new_token<HEAD_DIM, KV>(a, pending, lane);
+                            pending = take_new_token<HEAD_DIM, KV>(regs[u][0], regs[u][1], row_k[u],
+                                                                   row_v[u], rem - 1, tA, tB,
+                                                                   row_stage, lane);
+                        }
+                    }
                     if constexpr (BLOCK_REDUCE)
                         group_update_block_reduce<HEAD_DIM, KV>(
                             regs[u][0], regs[u][1], q_cur, m, l, acc, rem < 2 * kBlock, visA,
@@ -630,10 +770,14 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                 }
                 // refill only after the stage's registers are dead, so the loads land in place
                 __builtin_amdgcn_sched_barrier(0);
+                if constexpr (APPEND) issue_rows(row_k[u], row_v[u], e + DEPTH);
                 issue_entry(regs[u], e + DEPTH);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+    }
+    if constexpr (APPEND) {
+        if (pending.have) store_new_token<HEAD_DIM, KV>(a, pending, lane);
     }
 }
 
@@ -650,7 +794,7 @@ __device__ __forceinline__ int share_of_workgroup(int wg, int n)
 
 // One wave per workgroup.  The block numbers of up to 32 groups come from one gathered vector load
 // (lane 2j+h = block h of the j-th group), whatever pairs they belong to.
-template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, bool APPEND>
 __global__ void __launch_bounds__(64)
 flat_stream_kernel(const FlatArgs a)
 {
@@ -658,13 +802,7 @@ flat_stream_kernel(const FlatArgs a)
     const FlatSchedule sched(a.context_lens, a.new_slots, a.num_seqs, a.H_k, a.pair_extra, lane);
     const int ctotal = sched.cost_total();
     const FlatCut cut(max(ctotal, 1), a.decode_wgs, a.min_share);   // shares of the cost axis
-    if ((int)blockIdx.x >= a.decode_wgs) {                           // fused step only
-        const int pair = blockIdx.x - a.decode_wgs;
-        int count = 0;
-        if (pair < a.num_seqs * a.H_k) count = attention_partials_of(a, sched, cut, ctotal, pair);
-        append_and_attend<HEAD_DIM, KV>(a, pair, lane, count, -1);
-        return;
-    }
+    if (blockIdx.x == 0 && lane == 0) a.ws_header[0] = a.ws_tag;
     if (ctotal == 0) return;
     const int share = share_of_workgroup(blockIdx.x, a.decode_wgs);
     if (share >= cut.nwg) return;
@@ -672,45 +810,39 @@ flat_stream_kernel(const FlatArgs a)
     const int x_end = sched.real_before(cut.begin(share + 1), ctotal);
     if (x_begin >= x_end) return;           // a share that lies inside one pair's extra units
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // see launch_flat_depth
+    extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];    // see launch_flat_kernel
     LiveSource src(a, sched, cut, lane, share, x_begin, x_end);
-    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
+    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE, APPEND>(a, src, q_stage, lane);
 }
 
 // The same stream from a prepared schedule: no schedule arithmetic and no block-table read stand
 // between the launch and the first tile load, only the load of the workgroup's records.
-template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE>
+template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, bool APPEND>
 __global__ void __launch_bounds__(64)
 flat_stream_prepared_kernel(const FlatArgs a)
 {
     const int lane = threadIdx.x;
     // the tag, the share's size and its first 32 records are loaded together: one round trip
-    const bool attends = (int)blockIdx.x < a.decode_wgs;
-    const int share = attends ? share_of_workgroup(blockIdx.x, a.decode_wgs) : 0;
+    const int share = share_of_workgroup(blockIdx.x, a.decode_wgs);
     const uint32_t* region = a.sched + a.sched_regions + (size_t)share * a.sched_stride;
     sched_rec_t first = {~0u, ~0u, 0u, 0u};
-    if (attends && lane < 32) first = *reinterpret_cast<const sched_rec_t*>(region + 4 + 4 * lane);
+    if (lane < 32) first = *reinterpret_cast<const sched_rec_t*>(region + 4 + 4 * lane);
     const int count = wave_uniform((int)region[0]);
     if (wave_uniform((int)a.sched[0]) != (int)a.sched_tag) {
         // not the schedule this launch was told to expect: do nothing, leave a mark
         if (blockIdx.x == 0 && lane == 0) a.sched_w[1] = 1u;
         return;
     }
-    if (!attends) {                                                  // fused step only
-        const int pair = blockIdx.x - a.decode_wgs;
-        const int total = pair < a.num_seqs * a.H_k ? (int)a.sched[kSchedHeaderWords + pair] : 0;
-        append_and_attend<HEAD_DIM, KV>(a, pair, lane, 0, total);
-        return;
-    }
     if (count <= 0) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char q_stage[];
     PreparedSource src(a, region, lane, min(count, (a.sched_stride - 4) / 4), first);
-    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>(a, src, q_stage, lane);
+    stream_share<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE, APPEND>(a, src, q_stage, lane);
 }
 
 // Writes the schedule that flat_stream_prepared_kernel reads: the same grid as the attention launch
-// it prepares (one wavefront per share, then one per (sequence, KV head) pair for the counts), each
-// wavefront deriving its share exactly as flat_stream_kernel does and leaving one record per entry.
+// it prepares (one wavefront per share) followed by one wavefront per (sequence, KV head) pair for
+// the pairs' partial counts, each wavefront deriving its share exactly as flat_stream_kernel does
+// and leaving one record per entry.
 __global__ void __launch_bounds__(64)
 flat_prepare_kernel(const FlatArgs a)
 {
@@ -722,10 +854,8 @@ flat_prepare_kernel(const FlatArgs a)
     if ((int)blockIdx.x >= a.decode_wgs) {
         const int pair = blockIdx.x - a.decode_wgs;
         if (pair < a.num_seqs * a.H_k) {
-            const int seq = pair / a.H_k;
             const int count = attention_partials_of(a, sched, cut, ctotal, pair);
-            const bool appends = a.new_slots && a.new_slots[seq] >= 0 && a.context_lens[seq] > 0;
-            if (lane == 0) out[kSchedHeaderWords + pair] = (uint32_t)(count + (appends ? 1 : 0));
+            if (lane == 0) out[kSchedHeaderWords + pair] = (uint32_t)count;
         }
         if (pair == 0 && lane == 0) {
             out[1] = 0u;
@@ -753,10 +883,11 @@ flat_prepare_kernel(const FlatArgs a)
         const int slot = min(max((int)blockIdx.x - cut.wg_of(pair_first), 0), a.max_slots - 1);
         const int rem = min(src.t_l - 2 * kBlock * src.gi_l, kSchedRemCap);
         const uint32_t last = (uint32_t)((src.last_mask >> lane) & 1);
+        const uint32_t app = (uint32_t)((src.append_mask >> lane) & 1);
         const uint32_t pair = (uint32_t)(src.seq_l * a.H_k + src.g_l);
         if ((lane & 1) == 0 && (lane >> 1) < src.nc) {
             *reinterpret_cast<sched_rec_t*>(region + 4 + 4 * (c0 + (lane >> 1))) =
-                sched_rec_t{(uint32_t)src.tile_l, (uint32_t)tile_b, pair | (last << 31),
+                sched_rec_t{(uint32_t)src.tile_l, (uint32_t)tile_b, pair | (app << 30) | (last << 31),
                       (uint32_t)rem | ((uint32_t)slot << 16)};
         }
     }
@@ -793,7 +924,8 @@ flat_merge_kernel(const FlatArgs a)
     const float* es = a.exp_sums + base;
     const float* po = a.tmp_out + base * HEAD_DIM + lane;
 
-    const uint32_t* tag_at = a.sched ? a.sched : reinterpret_cast<const uint32_t*>(a.counts);
+    // what the partials were laid out for: the schedule's tag, or the one the split kernel left
+    const uint32_t* tag_at = a.sched ? a.sched : a.ws_header;
     const uint32_t tag = *tag_at;
     const int t = a.context_lens[seq];
     int count = a.counts[seq * a.H_k + g];
@@ -809,8 +941,9 @@ flat_merge_kernel(const FlatArgs a)
     // (the three scalar loads are taken here, together: left to the compiler, each moves down to
     // its first use, behind a branch that waits for the one before)
     asm volatile("" : "+s"(count) : "s"(tag), "s"(t));
-    // a prepared schedule that is not the expected one: the split kernel wrote nothing, nor does this
-    if (a.sched && tag != a.sched_tag) return;
+    // a prepared schedule that is not the expected one (the split kernel wrote nothing), or partials
+    // that a split call with another plan or shape left: nothing is written
+    if (tag != (a.sched ? a.sched_tag : a.ws_tag)) return;
     if (row_id >= rows) return;                         // (WIDE: never, the grid is the row count)
     if (t <= 0) count = 0;
     count = wave_uniform(min(count, a.max_slots));
@@ -890,31 +1023,32 @@ flat_merge_kernel(const FlatArgs a)
     }
 }
 
-template <int HEAD_DIM, int KV, bool BIG, int DEPTH, bool BLOCK_REDUCE>
+template <int HEAD_DIM, int KV, bool BIG, int DEPTH, bool BLOCK_REDUCE, bool APPEND>
 static void launch_flat_kernel(const FlatArgs& a, dim3 grid, hipStream_t stream)
 {
     const dim3 block(64);
-    // staging area of one q operand + one parked partial (o, m, l per lane) + reduction scratch
-    const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512 + 512;
+    // staging area of one q operand + one parked partial (o, m, l per lane) + reduction scratch +
+    // the fused step's new K and V row
+    const size_t lds = HEAD_DIM / 32 * 1024 + HEAD_DIM / 16 * 1024 + 512 + 512 + 4 * HEAD_DIM;
     if (a.sched)
-        hipLaunchKernelGGL((flat_stream_prepared_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>), grid,
-                           block, lds, stream, a);
+        hipLaunchKernelGGL((flat_stream_prepared_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE, APPEND>),
+                           grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE>), grid, block,
-                           lds, stream, a);
+        hipLaunchKernelGGL((flat_stream_kernel<HEAD_DIM, KV, DEPTH, BIG, BLOCK_REDUCE, APPEND>), grid,
+                           block, lds, stream, a);
 }
 
-template <int HEAD_DIM, int KV, bool BIG>
+template <int HEAD_DIM, int KV, bool BIG, bool APPEND>
 static void launch_flat_depth(const FlatArgs& a, const FlatPlan& plan, dim3 grid, hipStream_t stream)
 {
     if (plan.block_reduce) {             // comparison variant: depth 2 only
-        launch_flat_kernel<HEAD_DIM, KV, BIG, 2, true>(a, grid, stream);
+        launch_flat_kernel<HEAD_DIM, KV, BIG, 2, true, APPEND>(a, grid, stream);
         return;
     }
     switch (plan.depth) {
-    case 1: launch_flat_kernel<HEAD_DIM, KV, BIG, 1, false>(a, grid, stream); break;
-    case 3: launch_flat_kernel<HEAD_DIM, KV, BIG, 3, false>(a, grid, stream); break;
-    default: launch_flat_kernel<HEAD_DIM, KV, BIG, 2, false>(a, grid, stream); break;
+    case 1: launch_flat_kernel<HEAD_DIM, KV, BIG, 1, false, APPEND>(a, grid, stream); break;
+    case 3: launch_flat_kernel<HEAD_DIM, KV, BIG, 3, false, APPEND>(a, grid, stream); break;
+    default: launch_flat_kernel<HEAD_DIM, KV, BIG, 2, false, APPEND>(a, grid, stream); break;
     }
 }
 
@@ -922,21 +1056,30 @@ template <int HEAD_DIM, int KV>
 static void launch_flat_pool(const FlatArgs& a, bool big, const FlatPlan& plan, dim3 grid,
                              hipStream_t stream)
 {
-    if (big) launch_flat_depth<HEAD_DIM, KV, true>(a, plan, grid, stream);
-    else launch_flat_depth<HEAD_DIM, KV, false>(a, plan, grid, stream);
+    const bool append = a.k_new != nullptr;
+    if (big) {
+        if (append) launch_flat_depth<HEAD_DIM, KV, true, true>(a, plan, grid, stream);
+        else launch_flat_depth<HEAD_DIM, KV, true, false>(a, plan, grid, stream);
+    } else {
+        if (append) launch_flat_depth<HEAD_DIM, KV, false, true>(a, plan, grid, stream);
+        else launch_flat_depth<HEAD_DIM, KV, false, false>(a, plan, grid, stream);
+    }
 }
 
 int flat_max_slots(const coopt_shape* sh, const FlatPlan& plan)
 {
     const int max_groups = (sh->max_blocks_per_seq + 1) / 2;
     const int min_share = plan.min_share_groups();
-    // a pair's groups span at most this many shares, plus the fused step's partial of the new token
-    return (max_groups + min_share - 1) / min_share + 2;
+    // a pair's groups span at most this many shares (of at least min_share cost units each)
+    return (max_groups + min_share - 1) / min_share + 1;
 }
+
+constexpr size_t kWsHeaderBytes = 16;
 
 size_t flat_workspace_bytes(const coopt_shape* sh, const FlatPlan& plan)
 {
-    return (size_t)sh->num_seqs * sh->num_q_heads * flat_max_slots(sh, plan) *
+    return kWsHeaderBytes +
+           (size_t)sh->num_seqs * sh->num_q_heads * flat_max_slots(sh, plan) *
                (sh->head_dim + 2) * sizeof(float) +
            (size_t)sh->num_seqs * sh->num_kv_heads * sizeof(int32_t);
 }
@@ -963,6 +1106,19 @@ static int flat_grid_groups(const coopt_shape* sh, const FlatPlan& plan)
     return (int)std::max(groups, 1LL);
 }
 
+// Names what the layout of the partials in a workspace depends on, so that a merge call can tell
+// partials that a split call with another shape or plan left.
+static uint32_t ws_tag_of(const coopt_shape* sh, const FlatPlan& plan)
+{
+    uint32_t h = 2166136261u;
+    const int fields[] = {0x57535031, sh->num_seqs, sh->num_q_heads, sh->num_kv_heads, sh->head_dim,
+                          sh->max_blocks_per_seq, flat_grid_groups(sh, plan), plan.min_share_groups(),
+                          kPairExtra, flat_max_slots(sh, plan)};
+    for (int f : fields)
+        for (int b = 0; b < 4; ++b) h = (h ^ ((uint32_t)f >> (8 * b) & 0xffu)) * 16777619u;
+    return h | 1u;
+}
+
 static FlatArgs flat_args(const coopt_shape* sh, const FlatPlan& plan, void* workspace)
 {
     FlatArgs a{};
@@ -977,7 +1133,9 @@ static FlatArgs flat_args(const coopt_shape* sh, const FlatPlan& plan, void* wor
     a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
     const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
-    a.tmp_out = (float*)workspace;
+    a.ws_header = (uint32_t*)workspace;
+    a.ws_tag = ws_tag_of(sh, plan);
+    a.tmp_out = (float*)((unsigned char*)workspace + kWsHeaderBytes);
     a.max_logits = a.tmp_out + rows * a.max_slots * sh->head_dim;
     a.exp_sums = a.max_logits + rows * a.max_slots;
     a.counts = reinterpret_cast<int32_t*>(a.exp_sums + rows * a.max_slots);
@@ -1067,7 +1225,6 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
         a.v_cache_w = (uint8_t*)const_cast<void*>(v_cache);
         a.k_scale_w = const_cast<float*>(k_scale);
         a.v_scale_w = const_cast<float*>(v_scale);
-        wgs += (long long)sh->num_seqs * sh->num_kv_heads;
     }
     if (schedule) {
         if (flat_schedule_bytes(sh, plan) == 0) return COOPT_ERR_SHAPE;

@@ -3,15 +3,29 @@
 // Shared by the cache-write kernel and the fused decode step.
 #pragma once
 
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace coopt {
 
+// Maximum over the 64 lanes, on the vector ALU: row shifts, then the two row broadcasts that carry
+// a row's result into the following rows, leave it in lane 63 (no LDS round trips).  Lanes a step
+// does not reach keep their own value.
 __device__ __forceinline__ float wave_max(float a)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
-    return a;
+    int v = __builtin_bit_cast(int, a);
+    auto step = [&](auto ctrl, auto rows) {
+        const int o = __builtin_amdgcn_update_dpp(v, v, decltype(ctrl)::value, decltype(rows)::value, 0xf, false);
+        v = __builtin_bit_cast(int, fmaxf(__builtin_bit_cast(float, v), __builtin_bit_cast(float, o)));
+    };
+    step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
+    step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
+    step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
+    step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8
+    step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15 -> rows 1, 3
+    step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31 -> rows 2, 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(v, 63));
 }
 
 // Dynamic per-row scale and the scaled, clamped values (binary32, correctly rounded divisions so
@@ -48,41 +62,57 @@ struct QuantRow {
 };
 
 // Quantises one K row and one V row (HEAD_DIM values each, lane i holding elements i*E .. i*E+E-1
-// as binary32) and stores codes and scales into tile `tile` (= physical block * H_k + KV head) at
-// token offset `off`.  Returns what it stored.
+// as binary32): the rows' scales and codes, nothing stored.
+template <int HEAD_DIM>
+__device__ __forceinline__ QuantRow<HEAD_DIM> quantise_values(const float (&kx)[HEAD_DIM / 64],
+                                                              const float (&vx)[HEAD_DIM / 64])
+{
+    constexpr int E = HEAD_DIM / 64;
+    QuantRow<HEAD_DIM> qr;
+    float y[E];
+    qr.k_scale = scale_row<E>(kx, y);
+    if constexpr (E == 2) qr.k_codes = encode_pair(y[0], y[1]);
+    else qr.k_codes = encode_pair(y[0], 0.0f) & 0xffu;
+    qr.v_scale = scale_row<E>(vx, y);
+    if constexpr (E == 2) qr.v_codes = encode_pair(y[0], y[1]);
+    else qr.v_codes = encode_pair(y[0], 0.0f) & 0xffu;
+    return qr;
+}
+
+// Stores a quantised row into tile `tile` (= physical block * H_k + KV head) at token offset `off`.
+template <int HEAD_DIM>
+__device__ __forceinline__ void store_quant_row(const QuantRow<HEAD_DIM>& qr, size_t tile, int off,
+                                                int lane, uint8_t* __restrict__ k_cache,
+                                                uint8_t* __restrict__ v_cache,
+                                                float* __restrict__ k_scale,
+                                                float* __restrict__ v_scale)
+{
+    constexpr int E = HEAD_DIM / 64;
+    // ---- K tile [d/16][16 tokens][16]: the lane's E dims are neighbours inside one 16-byte chunk
+    uint8_t* kdst = k_cache + tile * (kBlock * HEAD_DIM) + k_tile_index<1>(off, lane * E);
+    if constexpr (E == 2) *reinterpret_cast<uint16_t*>(kdst) = (uint16_t)qr.k_codes;
+    else *kdst = (uint8_t)qr.k_codes;
+    if (lane == 0) k_scale[tile * kBlock + off] = qr.k_scale;
+    // ---- V tile: token index innermost, one byte per (dim, token)
+    uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
+    if constexpr (E == 2) {
+        vtile[v_tile_index<1>(off, lane * E)] = (uint8_t)(qr.v_codes & 0xffu);
+        vtile[v_tile_index<1>(off, lane * E + 1)] = (uint8_t)(qr.v_codes >> 8);
+    } else {
+        vtile[v_tile_index<1>(off, lane)] = (uint8_t)qr.v_codes;
+    }
+    if (lane == 0) v_scale[tile * kBlock + off] = qr.v_scale;
+}
+
+// Both: quantises the rows and stores codes and scales.  Returns what it stored.
 template <int HEAD_DIM>
 __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_values_to_cache(
     const float (&kx)[HEAD_DIM / 64], const float (&vx)[HEAD_DIM / 64], size_t tile, int off, int lane,
     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache, float* __restrict__ k_scale,
     float* __restrict__ v_scale)
 {
-    constexpr int E = HEAD_DIM / 64;
-    QuantRow<HEAD_DIM> qr;
-    float y[E];
-    // ---- K tile [d/16][16 tokens][16]: the lane's E dims are neighbours inside one 16-byte chunk
-    qr.k_scale = scale_row<E>(kx, y);
-    uint8_t* kdst = k_cache + tile * (kBlock * HEAD_DIM) + k_tile_index<1>(off, lane * E);
-    if constexpr (E == 2) {
-        qr.k_codes = encode_pair(y[0], y[1]);
-        *reinterpret_cast<uint16_t*>(kdst) = (uint16_t)qr.k_codes;
-    } else {
-        qr.k_codes = encode_pair(y[0], 0.0f) & 0xffu;
-        *kdst = (uint8_t)qr.k_codes;
-    }
-    if (lane == 0) k_scale[tile * kBlock + off] = qr.k_scale;
-
-    // ---- V tile: token index innermost, one byte per (dim, token)
-    qr.v_scale = scale_row<E>(vx, y);
-    uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
-    if constexpr (E == 2) {
-        qr.v_codes = encode_pair(y[0], y[1]);
-        vtile[v_tile_index<1>(off, lane * E)] = (uint8_t)(qr.v_codes & 0xffu);
-        vtile[v_tile_index<1>(off, lane * E + 1)] = (uint8_t)(qr.v_codes >> 8);
-    } else {
-        qr.v_codes = encode_pair(y[0], 0.0f) & 0xffu;
-        vtile[v_tile_index<1>(off, lane)] = (uint8_t)qr.v_codes;
-    }
-    if (lane == 0) v_scale[tile * kBlock + off] = qr.v_scale;
+    const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM>(kx, vx);
+    store_quant_row<HEAD_DIM>(qr, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
     return qr;
 }
 

@@ -121,15 +121,34 @@ __device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
         p[i] = __builtin_amdgcn_exp2f(z[i] - mm);             // invisible: exp2(-inf) = 0
         l += p[i];
     }
+    // The weights enter the second product as fp16.  Where one token may carry a sizeable part of
+    // a row's softmax (some lane holds a weight above 1/16 of its running sum: the first groups of
+    // every row, peaked rows) they go in as the pair hi + lo of attn_tile.hpp, two products against
+    // the same V operand, because a single weight's fp16 rounding (2^-11 relative) would then show
+    // in the output; elsewhere no token contributes more than 1/16 of the row and the roundings of
+    // many small weights average out, so one rounded weight and one product do.  (A weight's share
+    // of the final sum is never above its share of the sum at the time: l only grows, apart from
+    // the rescale it shares with every weight before it.)
+    const bool precise = __builtin_amdgcn_ballot_w64(__builtin_amdgcn_exp2f(bm - mm) * 16.0f > l) != 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         p[i] *= vsA[i];
         p[4 + i] *= vsB[i];
     }
-    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
-                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+    if (precise) {
+        half8_t hi, lo;
+        split_weights(p, hi, lo);
 #pragma unroll
-    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
+        for (int c = 0; c < HEAD_DIM / 16; ++c) {
+            acc[c] = mfma_16x16x32(vop[c], hi, acc[c]);
+            acc[c] = mfma_16x16x32(vop[c], lo, acc[c]);
+        }
+    } else {
+        const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
+                             (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+#pragma unroll
+        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
+    }
 }
 
 template <int HEAD_DIM, int KV, int NR, bool BIG>

@@ -1,7 +1,9 @@
-// Measurement aid, not part of the method: a read-only streaming kernel that gives the rate at
-// which this GPU delivers HBM bytes to a kernel that does nothing else.  The decode kernels'
-// bandwidth is quoted against the nominal HBM peak and, beside it, against this figure.
+// Measurement aid, not part of the method and built into a library of its own
+// (libcoopt_probe.so): a read-only streaming kernel that gives the rate at which this GPU delivers
+// HBM bytes to a kernel that does nothing else.  The decode kernels' bandwidth is quoted against
+// the nominal HBM peak and, beside it, against this figure.
 #include "common.hpp"
+#include "coopt_probe.h"
 
 namespace coopt {
 

@@ -17,3 +17,13 @@ def oracle_mod():
     import oracle
     oracle.build()
     return oracle
+
+
+@pytest.fixture(autouse=True)
+def _default_decode_plan():
+    """Tests that change the decode plan of their calls do not leak it into the next test."""
+    yield
+    import sys
+    gpu_utils = sys.modules.get("gpu_utils")
+    if gpu_utils is not None:
+        gpu_utils.planned.reset()

@@ -7,7 +7,7 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import alloc_dev_cache, assert_close, dev, hip_decode, hip_write, shape_of
+from gpu_utils import planned, alloc_dev_cache, assert_close, dev, hip_decode, hip_write, shape_of
 from helpers import alloc_cache, oracle_fill
 
 pytestmark = pytest.mark.gpu
@@ -47,11 +47,11 @@ def test_decode_all_paths(big, oracle_mod):
         assert_close(hip_decode(w, dcache, q=q, split=split), ref, f"big pool split={split}")
     shape = shape_of(w)
     # the same decode from a prepared schedule
-    sched = torch.zeros(coopt.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
-    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    sched = torch.zeros(planned.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
     outs = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.decode_schedule_prepare(dev(w.block_tables), dev(w.context_lens), None, sched, shape)
-    coopt.paged_gqa_decode_scheduled(None, None, None, dev(q.view(np.uint16)), *dcache,
+    planned.decode_schedule_prepare(dev(w.block_tables), dev(w.context_lens), None, sched, shape)
+    planned.paged_gqa_decode_scheduled(None, None, None, dev(q.view(np.uint16)), *dcache,
                                      dev(w.context_lens), outs, ws, sched, shape)
     torch.cuda.synchronize()
     assert_close(outs.cpu().numpy().astype(np.float64), ref, "big pool, prepared schedule")
@@ -61,7 +61,7 @@ def test_decode_all_paths(big, oracle_mod):
     es = torch.empty_like(ml)
     out = torch.zeros((w.S, w.H_q, w.d), dtype=torch.float16, device="cuda")
     dq, dbt, dlen = dev(q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
-    coopt.paged_gqa_decode_partitioned(dq, *dcache, dbt, dlen, P, tmp_out, ml, es, max_parts, shape)
+    planned.paged_gqa_decode_partitioned(dq, *dcache, dbt, dlen, P, tmp_out, ml, es, max_parts, shape)
     coopt.paged_gqa_reduce(tmp_out, ml, es, dlen, P, max_parts, out, shape)
     torch.cuda.synchronize()
     assert_close(out.cpu().numpy().astype(np.float64), ref, "big pool partitioned")
@@ -105,8 +105,8 @@ def test_fused_step(oracle_mod):
     shape = shape_of(w)
     new = w.new_index()
     out = torch.zeros((w.S, w.H_q, w.d), dtype=torch.float16, device="cuda")
-    ws = torch.empty(coopt.decode_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
-    coopt.paged_gqa_decode_step(dev(w.k_ctx[new].view(np.uint16)), dev(w.v_ctx[new].view(np.uint16)),
+    ws = torch.empty(planned.decode_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    planned.paged_gqa_decode_step(dev(w.k_ctx[new].view(np.uint16)), dev(w.v_ctx[new].view(np.uint16)),
                                 dev(w.slots[new]), dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables),
                                 dev(w.context_lens), out, ws, shape)
     torch.cuda.synchronize()

@@ -6,7 +6,7 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import (alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host,
+from gpu_utils import (planned, alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host,
                        hip_decode, hip_write, shape_of)
 from helpers import alloc_cache, oracle_fill
 
@@ -18,13 +18,6 @@ def _oracle_decode(oracle, w, cache, q=None, lens=None, tables=None):
                                    w.block_tables if tables is None else tables,
                                    w.context_lens if lens is None else lens,
                                    H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B, softmax_scale=w.softmax_scale)
-
-
-@pytest.fixture(autouse=True)
-def _default_plan():
-    saved = coopt.get_decode_plan()
-    yield
-    coopt.set_decode_plan(**saved)
 
 
 def test_tiny_config(oracle_mod):
@@ -48,7 +41,7 @@ def test_ragged_lengths_and_group_sizes(oracle_mod, kv_dtype, H_q, H_k, d):
     for split in (False, True):
         got = hip_decode(w, dcache, split=split)
         assert_close(got, ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} split={split}")
-    coopt.set_decode_plan(softmax_reduction=1)      # Opt-Pa's shared-memory max / block_sum form
+    planned.set_plan(softmax_reduction=1)      # Opt-Pa's shared-memory max / block_sum form
     assert_close(hip_decode(w, dcache, split=True), ref, f"ragged {kv_dtype} {H_q}/{H_k}/{d} block reduce")
 
 
@@ -68,7 +61,7 @@ def test_every_launch_plan_gives_the_same_answer(oracle_mod, plan):
                               context_lens=lens, max_blocks=80)
     cache = oracle_fill(oracle_mod, w)
     ref = _oracle_decode(oracle_mod, w, cache)
-    coopt.set_decode_plan(**_plan(*plan))
+    planned.set_plan(**_plan(*plan))
     dcache = cache_to_dev(cache)
     got = hip_decode(w, dcache, split=True)
     assert_close(got, ref, f"plan {plan}")
@@ -143,7 +136,7 @@ def test_many_short_sequences(oracle_mod, S):
     ref = _oracle_decode(oracle_mod, w, cache, lens=lens)
     dcache = cache_to_dev(cache)
     for plan in [(128, 1, 2, 1024), (32, 1, 1, 4096), (256, 4, 2, 64), (64, 1, 2, 96)]:
-        coopt.set_decode_plan(**_plan(*plan))
+        planned.set_plan(**_plan(*plan))
         got = hip_decode(w, dcache, lens=lens, split=True)
         assert np.all(got[lens == 0] == 0)
         assert_close(got, ref, f"S={S} plan={plan}")
@@ -156,11 +149,11 @@ def test_split_and_merge_as_separate_calls(oracle_mod):
     ref = _oracle_decode(oracle_mod, w, cache)
     shape = shape_of(w)
     dcache = cache_to_dev(cache)
-    ws = torch.empty(coopt.decode_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(planned.decode_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
     out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
     dlen = dev(w.context_lens)
-    coopt.paged_gqa_decode_split(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables), dlen, ws, shape)
-    coopt.paged_gqa_decode_merge(dlen, ws, out, shape)
+    planned.paged_gqa_decode_split(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables), dlen, ws, shape)
+    planned.paged_gqa_decode_merge(dlen, ws, out, shape)
     torch.cuda.synchronize()
     assert_close(out.cpu().numpy().astype(np.float64), ref, "split+merge")
 

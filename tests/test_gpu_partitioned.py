@@ -6,7 +6,7 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import assert_close, cache_to_dev, dev, shape_of
+from gpu_utils import planned, assert_close, cache_to_dev, dev, shape_of
 from helpers import oracle_fill
 
 pytestmark = pytest.mark.gpu
@@ -20,7 +20,7 @@ def _hip_partitioned(w, dcache, P, max_parts, lens=None):
     ml = torch.full((w.S, w.H_q, max_parts), float("nan"), dtype=torch.float32, device="cuda")
     es = torch.full((w.S, w.H_q, max_parts), float("nan"), dtype=torch.float32, device="cuda")
     out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.paged_gqa_decode_partitioned(dq, *dcache, dbt, dlen, P, tmp, ml, es, max_parts, shape)
+    planned.paged_gqa_decode_partitioned(dq, *dcache, dbt, dlen, P, tmp, ml, es, max_parts, shape)
     coopt.paged_gqa_reduce(tmp, ml, es, dlen, P, max_parts, out, shape)
     torch.cuda.synchronize()
     return (out.cpu().numpy().astype(np.float64), tmp.cpu().numpy().astype(np.float64),

@@ -2,7 +2,7 @@
 import pytest
 import torch
 
-import paper_2602_09323_amd as coopt
+from paper_2602_09323_amd import probe
 
 pytestmark = pytest.mark.gpu
 
@@ -14,7 +14,7 @@ def test_probe_reads_and_leaves_memory_alone(nbytes, wgs):
     whole[:256] = 0x5A
     whole[-256:] = 0x5A
     sink = torch.full((8,), 77, dtype=torch.int32, device="cuda")
-    coopt.stream_read_probe(whole[256:-256], wgs, sink[4:5])
+    probe.stream_read_probe(whole[256:-256], wgs, sink[4:5])
     torch.cuda.synchronize()
     assert bool((whole[:256] == 0x5A).all()) and bool((whole[-256:] == 0x5A).all())
     assert bool((whole[256:-256] == 0).all())

@@ -10,7 +10,7 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host, hip_write, shape_of
+from gpu_utils import planned, alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host, hip_write, shape_of
 from helpers import oracle_fill
 
 pytestmark = pytest.mark.gpu
@@ -19,15 +19,8 @@ PLANS = [(128, 1, 2, 1024, 0), (32, 1, 1, 5, 0), (64, 1, 3, 64, 0), (128, 1, 2, 
          (256, 1, 2, 333, 0), (32, 1, 3, 2048, 0), (512, 1, 2, 16, 0)]
 
 
-@pytest.fixture(autouse=True)
-def _default_plan():
-    saved = coopt.get_decode_plan()
-    yield
-    coopt.set_decode_plan(**saved)
-
-
 def _set_plan(plan):
-    coopt.set_decode_plan(tokens_per_group=plan[0], waves_per_group=plan[1], pipeline_depth=plan[2],
+    planned.set_plan(tokens_per_group=plan[0], waves_per_group=plan[1], pipeline_depth=plan[2],
                           grid_waves=plan[3], softmax_reduction=plan[4])
 
 
@@ -77,7 +70,7 @@ def _decode_case(orc, seed):
     ref = orc.paged_gqa_decode(w.q, *cache, w.block_tables, w.context_lens, H_q=H_q, H_k=H_k, d=d,
                                B=16, softmax_scale=w.softmax_scale)
     shape = shape_of(w)
-    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
     q, bt, dl = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
 
     def new_out():
@@ -92,12 +85,12 @@ def _decode_case(orc, seed):
     hip_write(w, full)
     for workspace in (ws, None):
         out = new_out()
-        coopt.paged_gqa_decode(q, *full, bt, dl, out, workspace, shape)
+        planned.paged_gqa_decode(q, *full, bt, dl, out, workspace, shape)
         assert_close(host(out), ref, f"decode, workspace={workspace is not None}, {what}")
-    sched = torch.zeros(coopt.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
-    coopt.decode_schedule_prepare(bt, dl, None, sched, shape)
+    sched = torch.zeros(planned.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
+    planned.decode_schedule_prepare(bt, dl, None, sched, shape)
     out = new_out()
-    coopt.paged_gqa_decode_scheduled(None, None, None, q, *full, dl, out, ws, sched, shape)
+    planned.paged_gqa_decode_scheduled(None, None, None, q, *full, dl, out, ws, sched, shape)
     assert_close(host(out), ref, f"decode from a schedule, {what}")
 
     # ---- fused step; some sequences append nothing (their last token is already in the cache)
@@ -116,10 +109,10 @@ def _decode_case(orc, seed):
         hip_write(w, dcache, idx=before)
         out = new_out()
         if prepared:
-            coopt.decode_schedule_prepare(bt, dl, dslots, sched, shape)
-            coopt.paged_gqa_decode_scheduled(k_new, v_new, dslots, q, *dcache, dl, out, ws, sched, shape)
+            planned.decode_schedule_prepare(bt, dl, dslots, sched, shape)
+            planned.paged_gqa_decode_scheduled(k_new, v_new, dslots, q, *dcache, dl, out, ws, sched, shape)
         else:
-            coopt.paged_gqa_decode_step(k_new, v_new, dslots, q, *dcache, bt, dl, out, ws, shape)
+            planned.paged_gqa_decode_step(k_new, v_new, dslots, q, *dcache, bt, dl, out, ws, shape)
         assert_close(host(out), ref, f"step, prepared={prepared}, {what}")
         _same_bytes(dev_cache_to_host(w, dcache), want_bytes, f"step, prepared={prepared}, {what}")
 
@@ -130,7 +123,7 @@ def _decode_case(orc, seed):
     ml = torch.full((S, H_q, max_parts), float("nan"), dtype=torch.float32, device="cuda")
     es = torch.full((S, H_q, max_parts), float("nan"), dtype=torch.float32, device="cuda")
     out = new_out()
-    coopt.paged_gqa_decode_partitioned(q, *full, bt, dl, P, tmp, ml, es, max_parts, shape)
+    planned.paged_gqa_decode_partitioned(q, *full, bt, dl, P, tmp, ml, es, max_parts, shape)
     coopt.paged_gqa_reduce(tmp, ml, es, dl, P, max_parts, out, shape)
     assert_close(host(out), ref, f"partitioned P={P}, {what}")
 

@@ -7,7 +7,7 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import alloc_dev_cache, assert_close, dev, dev_cache_to_host, hip_write, shape_of
+from gpu_utils import planned, alloc_dev_cache, assert_close, dev, dev_cache_to_host, hip_write, shape_of
 from helpers import alloc_cache, oracle_fill
 
 pytestmark = pytest.mark.gpu
@@ -15,15 +15,8 @@ pytestmark = pytest.mark.gpu
 PLANS = [(128, 1, 2, 1024, 0), (32, 1, 1, 5, 0), (64, 1, 3, 64, 0), (128, 1, 2, 1024, 1)]
 
 
-@pytest.fixture(autouse=True)
-def _default_plan():
-    saved = coopt.get_decode_plan()
-    yield
-    coopt.set_decode_plan(**saved)
-
-
 def _set_plan(plan):
-    coopt.set_decode_plan(tokens_per_group=plan[0], waves_per_group=plan[1], pipeline_depth=plan[2],
+    planned.set_plan(tokens_per_group=plan[0], waves_per_group=plan[1], pipeline_depth=plan[2],
                           grid_waves=plan[3], softmax_reduction=plan[4])
 
 
@@ -43,12 +36,12 @@ def _same_cache(w, dcache, cache, what):
 
 def _prepare(w, slots=None, lens=None, fill=0):
     shape = shape_of(w)
-    n = coopt.decode_schedule_bytes(shape)
+    n = planned.decode_schedule_bytes(shape)
     assert n > 0 and n % 4 == 0
     sched = torch.full((n + 64,), fill, dtype=torch.uint8, device="cuda")      # 64 guard bytes
     sched[n:] = 0xC3
     dslots = None if slots is None else dev(np.asarray(slots, dtype=np.int64))
-    coopt.decode_schedule_prepare(dev(w.block_tables), dev(w.context_lens if lens is None else lens),
+    planned.decode_schedule_prepare(dev(w.block_tables), dev(w.context_lens if lens is None else lens),
                                   dslots, sched[:n], shape)
     torch.cuda.synchronize()
     assert bool((sched[n:] == 0xC3).all()), "prepare wrote past the schedule"
@@ -67,8 +60,8 @@ def _run(w, dcache, sched, slots=None, k_new=None, v_new=None, lens=None, out=No
         k = v = s = None
     if out is None:
         out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
-    coopt.paged_gqa_decode_scheduled(k, v, s, dev(w.q.view(np.uint16)), *dcache,
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    planned.paged_gqa_decode_scheduled(k, v, s, dev(w.q.view(np.uint16)), *dcache,
                                      dev(w.context_lens if lens is None else lens), out, ws, sched, shape)
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64)
@@ -159,7 +152,7 @@ def test_many_sequences(oracle_mod):
     ref = _oracle_decode(oracle_mod, w, cache)
     new_slots = w.slots[w.new_index()]
     for grid in (1024, 96):
-        coopt.set_decode_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=grid)
+        planned.set_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=grid)
         dcache = alloc_dev_cache(w, fill_byte=0)
         hip_write(w, dcache, idx=w.history_index())
         got = _run(w, dcache, _prepare(w, slots=new_slots), slots=new_slots)
@@ -190,12 +183,12 @@ def test_schedule_that_does_not_fit_is_refused_on_the_device(oracle_mod):
     untouched(decode_sched, slots=new_slots)                     # ... used for the fused step
     step_sched = _prepare(w, slots=new_slots)
     untouched(step_sched)                                        # and the other way round
-    n = coopt.decode_schedule_bytes(shape_of(w))
+    n = planned.decode_schedule_bytes(shape_of(w))
     for fill in (0, 0xFF):
         untouched(torch.full((n,), fill, dtype=torch.uint8, device="cuda"))   # never prepared
     fresh = _prepare(w)
-    coopt.set_decode_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=1024)
-    if coopt.decode_schedule_bytes(shape_of(w)) <= fresh.numel():
+    planned.set_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=1024)
+    if planned.decode_schedule_bytes(shape_of(w)) <= fresh.numel():
         untouched(fresh)                                         # prepared under another plan
     # prepared again, it works again (and the status word is back to 0)
     again = _prepare(w)

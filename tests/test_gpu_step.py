@@ -8,18 +8,11 @@ import torch
 
 import paper_2602_09323_amd as coopt
 import workloads
-from gpu_utils import (alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host,
+from gpu_utils import (planned, alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host,
                        hip_write, shape_of)
 from helpers import oracle_fill
 
 pytestmark = pytest.mark.gpu
-
-
-@pytest.fixture(autouse=True)
-def _default_plan():
-    saved = coopt.get_decode_plan()
-    yield
-    coopt.set_decode_plan(**saved)
 
 
 def _oracle_decode(oracle, w, cache, lens=None):
@@ -35,8 +28,8 @@ def _hip_step(w, dcache, slots, k_new=None, v_new=None, lens=None):
     k = w.k_ctx[new] if k_new is None else k_new
     v = w.v_ctx[new] if v_new is None else v_new
     out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
-    coopt.paged_gqa_decode_step(dev(k.view(np.uint16)), dev(v.view(np.uint16)),
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    planned.paged_gqa_decode_step(dev(k.view(np.uint16)), dev(v.view(np.uint16)),
                                 dev(np.asarray(slots, dtype=np.int64)), dev(w.q.view(np.uint16)),
                                 *dcache, dev(w.block_tables),
                                 dev(w.context_lens if lens is None else lens), out, ws, shape)
@@ -61,7 +54,7 @@ def test_step_equals_write_then_decode(oracle_mod, kv_dtype, H_q, H_k, d):
     cache = oracle_fill(oracle_mod, w)                      # history and new tokens
     ref = _oracle_decode(oracle_mod, w, cache)
     for plan in [(128, 1, 2, 1024), (32, 1, 1, 5), (64, 1, 3, 64)]:
-        coopt.set_decode_plan(tokens_per_group=plan[0], waves_per_group=plan[1],
+        planned.set_plan(tokens_per_group=plan[0], waves_per_group=plan[1],
                               pipeline_depth=plan[2], grid_waves=plan[3])
         dcache = alloc_dev_cache(w, fill_byte=0)
         hip_write(w, dcache, idx=w.history_index())
@@ -107,7 +100,7 @@ def test_many_sequences_step(oracle_mod):
     cache = oracle_fill(oracle_mod, w)
     ref = _oracle_decode(oracle_mod, w, cache)
     for grid in (1024, 96):
-        coopt.set_decode_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=grid)
+        planned.set_plan(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=grid)
         dcache = alloc_dev_cache(w, fill_byte=0)
         hip_write(w, dcache, idx=w.history_index())
         got = _hip_step(w, dcache, w.slots[w.new_index()])
