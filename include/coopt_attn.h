@@ -179,6 +179,28 @@ int coopt_paged_gqa_decode(const void* q, const void* k_cache, const void* v_cac
                            const coopt_shape* shape, void* hip_stream);
 
 /*
+ * coopt_paged_gqa_decode for callers that can neither allocate device memory nor hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and result as coopt_paged_gqa_decode with a workspace (the same two kernels),
+ * but the partial results go to a device array built into the library,
+ * coopt_decode_builtin_workspace_bytes() = 32 MiB per GPU, held from the library's first use on
+ * that GPU until the process ends.  The call allocates and frees nothing (the first call on a
+ * device asks the runtime for the array's address, once).
+ *   COOPT_ERR_WORKSPACE  coopt_decode_workspace_bytes(shape, plan) exceeds the built-in array
+ *                        (e.g. 4 sequences of 32 k tokens with 40 query heads under the default
+ *                        plan need 21 MB and fit; 16 such sequences do not): nothing is launched
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents; nothing in it
+ * has to be cleared between calls.  Calls on one GPU must be ordered (one stream, or events):
+ * two that overlap race on the array and both results are undefined.
+ */
+int coopt_paged_gqa_decode_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                                   const float* k_scale, const float* v_scale,
+                                   const int32_t* block_tables, const int32_t* context_lens,
+                                   void* out, const coopt_decode_plan* plan,
+                                   const coopt_shape* shape, void* hip_stream);
+size_t coopt_decode_builtin_workspace_bytes(void);
+
+/*
  * The two kernels of coopt_paged_gqa_decode as separate calls, for callers that time or schedule
  * them apart: `split` runs attention over equal shares of the batch's work and leaves one partial
  * (reference max, exponential sum, normalised output) per share segment in the workspace; `merge`

@@ -6,8 +6,8 @@ only.  There is no CPU fallback: importing works anywhere, calling needs the bui
 """
 from .binding import (  # noqa: F401
     COOPT_KV_E4M3, COOPT_KV_FP16, CooptError, DecodePlan, Shape, decode_schedule_bytes,
-    decode_schedule_prepare, decode_workspace_bytes, default_decode_plan, gather_cached_kv,
+    decode_builtin_workspace_bytes, decode_schedule_prepare, decode_workspace_bytes, default_decode_plan, gather_cached_kv,
     kv_cache_write_fp16, kv_cache_write_fp8, kv_cache_write_skipset, lib_path, load_library,
-    make_decode_plan, paged_gqa_decode, paged_gqa_decode_merge, paged_gqa_decode_partitioned,
+    make_decode_plan, paged_gqa_decode, paged_gqa_decode_merge, paged_gqa_decode_noalloc, paged_gqa_decode_partitioned,
     paged_gqa_decode_scheduled, paged_gqa_decode_split, paged_gqa_decode_step,
     paged_gqa_prefill_chunk, paged_gqa_reduce, status_string)

@@ -30,6 +30,7 @@ EXPORTS = [
     "coopt_paged_gqa_decode_partitioned", "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk",
     "coopt_gather_cached_kv", "coopt_decode_schedule_bytes", "coopt_decode_schedule_prepare",
     "coopt_paged_gqa_decode_scheduled", "coopt_status_string",
+    "coopt_paged_gqa_decode_noalloc", "coopt_decode_builtin_workspace_bytes",
 ]
 
 
@@ -92,11 +93,15 @@ def load_library():
         lib.coopt_decode_schedule_prepare.argtypes = [vp, vp, vp, vp, sz, plp, shp, vp]
         lib.coopt_paged_gqa_decode_scheduled.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                                          vp, sz, plp, shp, vp]
+        lib.coopt_paged_gqa_decode_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, plp, shp, vp]
+        lib.coopt_decode_builtin_workspace_bytes.argtypes = []
+        lib.coopt_decode_builtin_workspace_bytes.restype = sz
         lib.coopt_status_string.argtypes = [ctypes.c_int]
         lib.coopt_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
             if name not in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes",
-                            "coopt_status_string", "coopt_default_decode_plan"):
+                            "coopt_status_string", "coopt_default_decode_plan",
+                            "coopt_decode_builtin_workspace_bytes"):
                 getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -268,6 +273,20 @@ def paged_gqa_decode(q, k_cache, v_cache, k_scale, v_scale, block_tables, contex
     _call("coopt_paged_gqa_decode",
           *ins, _dev(out, f"{what}: out", elem=2, min_bytes=_sizes(shape)["q"]), pws, nws,
         _plan_ptr(plan), ctypes.byref(shape), _stream(stream))
+
+
+def decode_builtin_workspace_bytes() -> int:
+    return int(load_library().coopt_decode_builtin_workspace_bytes())
+
+
+def paged_gqa_decode_noalloc(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, out,
+                             shape: Shape, plan: Optional[DecodePlan] = None, stream=None) -> None:
+    """``paged_gqa_decode`` through the library's built-in workspace (no allocation anywhere)."""
+    what = "paged_gqa_decode_noalloc"
+    ins = _decode_inputs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, shape, what)
+    _call("coopt_paged_gqa_decode_noalloc",
+          *ins, _dev(out, f"{what}: out", elem=2, min_bytes=_sizes(shape)["q"]), _plan_ptr(plan),
+          ctypes.byref(shape), _stream(stream))
 
 
 def paged_gqa_decode_step(k, v, slot_mapping, q, k_cache, v_cache, k_scale, v_scale, block_tables,

@@ -486,6 +486,67 @@ extern "C" int coopt_paged_gqa_decode(const void* q, const void* k_cache, const 
     return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream);
 }
 
+// ---- a decode entry point that allocates nothing and takes no workspace
+//
+// The partial results of the balanced split live in a file-scope device array.  In host code the
+// array's name is only a stand-in: its device address is asked of the runtime once per device
+// (each GPU holds its own copy at its own address) and that pointer is what the kernels get.
+constexpr size_t kBuiltinWorkspaceBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kBuiltinWorkspaceBytes];
+
+static int builtin_workspace(void** workspace)
+{
+    static std::atomic<void*> known[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return COOPT_ERR_LAUNCH;
+    }
+    if (dev < 0 || dev >= 64) return COOPT_ERR_SHAPE;
+    void* p = known[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return COOPT_ERR_LAUNCH;
+        }
+        known[dev].store(p, std::memory_order_release);
+    }
+    *workspace = p;
+    return COOPT_OK;
+}
+
+extern "C" size_t coopt_decode_builtin_workspace_bytes(void) { return kBuiltinWorkspaceBytes; }
+
+extern "C" int coopt_paged_gqa_decode_noalloc(const void* q, const void* k_cache, const void* v_cache,
+                                              const float* k_scale, const float* v_scale,
+                                              const int32_t* block_tables,
+                                              const int32_t* context_lens, void* out,
+                                              const coopt_decode_plan* given, const coopt_shape* sh,
+                                              void* hip_stream)
+{
+    coopt_decode_plan plan;
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    st = resolve_plan(given, &plan);
+    if (st != COOPT_OK) return st;
+    if (sh->num_seqs == 0) return COOPT_OK;
+    st = check_decode_ptrs(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, sh);
+    if (st != COOPT_OK) return st;
+    if (!out) return COOPT_ERR_NULL;
+    // the partials of this shape and plan must fit the array
+    if (flat_workspace_bytes(sh, flat_plan(plan)) > kBuiltinWorkspaceBytes) return COOPT_ERR_WORKSPACE;
+    void* workspace = nullptr;
+    st = builtin_workspace(&workspace);
+    if (st != COOPT_OK) return st;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // nothing in the workspace has to start at zero: the split kernel writes the tag, every count
+    // and every partial that the merge kernel reads
+    st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                           workspace, sh, flat_plan(plan), stream);
+    if (st != COOPT_OK) return st;
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream);
+}
+
 extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
                                            const int64_t* slot_mapping, const void* q,
                                            void* k_cache, void* v_cache, float* k_scale,
