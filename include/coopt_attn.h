@@ -225,10 +225,11 @@ int coopt_paged_gqa_decode_merge(const int32_t* context_lens, const void* worksp
  * (Eq. 5, Alg. 1 phase 1) fused with the attention of Opt-GQA / Opt-Pa (Eq. 6-10).  The result is
  * that of coopt_kv_cache_write_fp8 / _fp16 with num_tokens = num_seqs followed by
  * coopt_paged_gqa_decode with a workspace: the same bytes end up in the cache, and `out` agrees
- * within the attention tolerance.  The wavefront that reads the last cache blocks of a (sequence,
- * KV head) pair quantises the pair's new row, attends over it from registers in place of whatever
- * the cache holds at that position, and stores it; the launch has no other wavefronts than the
- * plain decode's and nothing in it waits for anything else.
+ * within the attention tolerance.  In the first launch the wavefront that reads the last cache
+ * blocks of a (sequence, KV head) pair quantises the pair's new row and attends over it from
+ * registers, in place of whatever the cache holds at that position; that launch has no other
+ * wavefronts than the plain decode's, reads the cache only, and nothing in it waits for anything
+ * else.  The rows are stored into the cache by extra wavefronts of the second (merge) launch.
  *   k, v          device, fp16 [num_seqs][num_kv_heads][head_dim]: token s is the LAST token of
  *                 sequence s, i.e. position context_lens[s]-1
  *   slot_mapping  device, int64 [num_seqs]: negative = write nothing for this sequence and attend
@@ -265,8 +266,10 @@ int coopt_paged_gqa_decode_step(const void* k, const void* v, const int64_t* slo
  *             with a non-negative slot append their last token in the same launch).
  *   scheduled decode:  k, v, slot_mapping all NULL = plain decode, all non-NULL = fused step
  *             (COOPT_ERR_NULL if mixed); the other arguments as in coopt_paged_gqa_decode_step,
- *             without block_tables.  out NULL = stop after the partial results (the workspace then
- *             holds the partial results only; the pairs' partial counts stay in the schedule).
+ *             without block_tables.  out NULL = the first launch only (a tuning and timing aid):
+ *             the workspace then holds the partial results (the pairs' partial counts stay in
+ *             the schedule), and in a fused step the new rows are NOT stored, because that is
+ *             the second launch's work.
  * prepare only enqueues a kernel on hip_stream: the launches that use the schedule must be ordered
  * after it (same stream, or an event), and two launches that use one schedule may overlap.
  * A schedule prepared for another shape, plan or mode is recognised on the device by a tag: such a

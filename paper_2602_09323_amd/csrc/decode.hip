@@ -565,10 +565,12 @@ extern "C" int coopt_paged_gqa_decode_step(const void* k, const void* v,
     if (!out) return COOPT_ERR_NULL;
     hipStream_t stream = (hipStream_t)hip_stream;
     const FlatAppend append{k, v, slot_mapping};
+    const FlatCacheW cache{k_cache, v_cache, k_scale, v_scale};
     st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
                            workspace, sh, flat_plan(plan), stream, &append);
     if (st != COOPT_OK) return st;
-    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream);
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream, nullptr, false,
+                             &append, &cache);
 }
 
 extern "C" size_t coopt_decode_schedule_bytes(const coopt_shape* sh, const coopt_decode_plan* given)
@@ -625,7 +627,9 @@ extern "C" int coopt_paged_gqa_decode_scheduled(const void* k, const void* v,
     st = launch_flat_split(q, k_cache, v_cache, k_scale, v_scale, nullptr, context_lens, workspace,
                            sh, flat_plan(plan), stream, fused ? &append : nullptr, schedule);
     if (st != COOPT_OK || !out) return st;
-    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream, schedule, fused);
+    const FlatCacheW cache{k_cache, v_cache, k_scale, v_scale};
+    return launch_flat_merge(context_lens, workspace, out, sh, flat_plan(plan), stream, schedule, fused,
+                             fused ? &append : nullptr, &cache);
 }
 
 extern "C" int coopt_paged_gqa_decode_split(const void* q, const void* k_cache, const void* v_cache,

@@ -178,6 +178,9 @@ struct FlatArgs {
     int32_t pair_extra;   // cost units charged to a share for every pair that ends inside it
     int32_t pool_tiles;   // num_blocks * H_k
     int32_t decode_wgs;   // workgroups (= wavefronts) of the attention launch
+    int32_t append_wgs;   // fused step: workgroups at the head of the merge launch's grid whose
+                          // wavefronts store one new row each (0 otherwise)
+    int32_t kv_e4m3;      // cache type, for the merge launch's row stores
     uint32_t ws_tag;      // names the plan the workspace's partials were laid out for (see ws_tag_of)
     float scale_log2e;
     // fused step only (new_slots != NULL): the token every sequence appends, and the cache as
@@ -469,22 +472,16 @@ struct PreparedSource {
     }
 };
 
-// ---- fused step: the token a sequence appends in this launch (Opt-KV Eq. 5, Alg. 1 phase 1)
+// ---- fused step: the token a sequence appends in this step (Opt-KV Eq. 5, Alg. 1 phase 1)
 //
 // The wavefront that streams a pair's last group also takes the pair's new token: it quantises the
-// row exactly as the cache-write kernel does (kv_quant.hpp), puts the row's cache elements into
-// the K and V operand registers of that group in place of whatever the cache held at that slot,
-// attends over it like over any other token, and stores the row into the cache when its share is
-// done.  No other wavefront reads that group, so nothing in the launch waits for anything else.
-
-// What lane i holds of the new row: cache elements i*E .. i*E+E-1 (E = HEAD_DIM/64) of the K row
-// and of the V row -- E4M3 codes or fp16 bit patterns -- and the row's scales (E4M3 only).
-struct NewToken {
-    uint32_t k, v;
-    float ks, vs;
-    int tile, off;      // destination: tile = physical block * H_k + KV head, token offset in it
-    bool have;
-};
+// row exactly as the cache-write kernel does (kv_quant.hpp) and puts the row's cache elements into
+// the K and V operand registers of that group in place of whatever the cache holds at that slot,
+// so that the attention launch sees the token without anything in it waiting for a store.  The
+// row itself is stored into the cache by extra wavefronts of the MERGE launch that follows (same
+// quantiser, same bytes): stores into the cache pool from the attention launch cost it 0.8 us
+// at the LLaMa-13B decode shape wherever they were issued (at once, at the end of a share, as
+// whole tiles), while the merge launch has the time.
 
 // Replaces token `pos` (wave-uniform, 0..31: block A holds 0..15, block B the rest) of a loaded
 // group by the row staged in LDS at `row` (K row, then V row, cache elements in dim order).
@@ -550,17 +547,17 @@ __device__ __forceinline__ void patch_token(BlockRegs<HEAD_DIM, KV>& A, BlockReg
 }
 
 // row_k / row_v: the lane's E fp16 values of the new K / V row as loaded (low bits first).  pos =
-// the token's position inside the group (0..31), tA / tB = the group's tiles.  `stage` is
-// 2 * HEAD_DIM cache elements of LDS private to the wavefront.
+// the token's position inside the group (0..31).  `stage` is 2 * HEAD_DIM cache elements of LDS
+// private to the wavefront.
 template <int HEAD_DIM, int KV>
-__device__ __forceinline__ NewToken take_new_token(BlockRegs<HEAD_DIM, KV>& A,
-                                                   BlockRegs<HEAD_DIM, KV>& B, uint32_t row_k,
-                                                   uint32_t row_v, int pos, int tA, int tB,
-                                                   unsigned char* stage, int lane)
+__device__ __forceinline__ void take_new_token(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
+                                               uint32_t row_k, uint32_t row_v, int pos,
+                                               unsigned char* stage, int lane)
 {
     constexpr int E = HEAD_DIM / 64;
     constexpr int ES = BlockRegs<HEAD_DIM, KV>::ES;
-    NewToken nt;
+    uint32_t ck = row_k, cv = row_v;                    // the row's cache elements of this lane
+    float ks = 1.0f, vs = 1.0f;
     if constexpr (KV == COOPT_KV_E4M3) {
         float kx[E], vx[E];
 #pragma unroll
@@ -569,64 +566,27 @@ __device__ __forceinline__ NewToken take_new_token(BlockRegs<HEAD_DIM, KV>& A,
             vx[e] = (float)__builtin_bit_cast(half_t, (uint16_t)(row_v >> (16 * e)));
         }
         const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM>(kx, vx);
-        nt.k = qr.k_codes;
-        nt.v = qr.v_codes;
-        nt.ks = qr.k_scale;
-        nt.vs = qr.v_scale;
-    } else {
-        nt.k = row_k;
-        nt.v = row_v;
-        nt.ks = nt.vs = 1.0f;
+        ck = qr.k_codes;
+        cv = qr.v_codes;
+        ks = qr.k_scale;
+        vs = qr.v_scale;
     }
     constexpr int LB = E * ES;                          // bytes per lane and row
     unsigned char* kd = stage + LB * lane;
     unsigned char* vd = stage + HEAD_DIM * ES + LB * lane;
     if constexpr (LB == 1) {
-        *kd = (unsigned char)nt.k;
-        *vd = (unsigned char)nt.v;
+        *kd = (unsigned char)ck;
+        *vd = (unsigned char)cv;
     } else if constexpr (LB == 2) {
-        *reinterpret_cast<uint16_t*>(kd) = (uint16_t)nt.k;
-        *reinterpret_cast<uint16_t*>(vd) = (uint16_t)nt.v;
+        *reinterpret_cast<uint16_t*>(kd) = (uint16_t)ck;
+        *reinterpret_cast<uint16_t*>(vd) = (uint16_t)cv;
     } else {
-        *reinterpret_cast<uint32_t*>(kd) = nt.k;
-        *reinterpret_cast<uint32_t*>(vd) = nt.v;
+        *reinterpret_cast<uint32_t*>(kd) = ck;
+        *reinterpret_cast<uint32_t*>(vd) = cv;
     }
-    nt.off = pos & (kBlock - 1);
-    nt.tile = pos < kBlock ? tA : tB;
-    nt.have = true;
-    patch_token<HEAD_DIM, KV>(A, B, pos, stage, lane, nt.ks, nt.vs);
-    return nt;
+    patch_token<HEAD_DIM, KV>(A, B, pos, stage, lane, ks, vs);
 }
 
-// The new row into the cache (the same bytes the cache-write kernels store).
-template <int HEAD_DIM, int KV>
-__device__ __forceinline__ void store_new_token(const FlatArgs& a, const NewToken& nt, int lane)
-{
-    constexpr int E = HEAD_DIM / 64;
-    if constexpr (KV == COOPT_KV_E4M3) {
-        QuantRow<HEAD_DIM> qr;
-        qr.k_codes = nt.k;
-        qr.v_codes = nt.v;
-        qr.k_scale = nt.ks;
-        qr.v_scale = nt.vs;
-        store_quant_row<HEAD_DIM>(qr, (size_t)nt.tile, nt.off, lane, a.k_cache_w, a.v_cache_w,
-                                  a.k_scale_w, a.v_scale_w);
-    } else {
-        uint16_t* kc = reinterpret_cast<uint16_t*>(a.k_cache_w) + (size_t)nt.tile * (kBlock * HEAD_DIM);
-        uint16_t* vc = reinterpret_cast<uint16_t*>(a.v_cache_w) + (size_t)nt.tile * (kBlock * HEAD_DIM);
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int dim = lane * E + e;
-            kc[k_tile_index<2>(nt.off, dim)] = (uint16_t)(nt.k >> (16 * e));
-            vc[v_tile_index<2>(nt.off, dim)] = (uint16_t)(nt.v >> (16 * e));
-        }
-    }
-}
-
-// The wave's share is ONE stream of groups that runs across the boundaries between (sequence, KV
-// head) pairs.  The loads of the next pair's first groups are in flight while the last groups of
-// the current pair are being consumed, and the pair's partial is stored from the accumulator
-// registers in between.
 // APPEND (fused step): entries flagged by the source also take their pair's new token.
 template <int HEAD_DIM, int KV, int DEPTH, bool BIG, bool BLOCK_REDUCE, bool APPEND, typename Source>
 __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, unsigned char* q_stage,
@@ -652,8 +612,6 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
     float* red = reinterpret_cast<float*>(park + kParkAcc + 512);  // BLOCK_REDUCE: 128 floats
     unsigned char* row_stage = park + kParkAcc + 1024;             // APPEND: one new K row, one V row
     uint32_t row_k[DEPTH], row_v[DEPTH];                           // APPEND: the rows in flight
-    NewToken pending;                                              // APPEND: a row not stored yet
-    pending.have = false;
     PartialSlot parked;
     parked.row0 = -1;
     half8_t q_cur[HEAD_DIM / 32];
@@ -711,12 +669,8 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                     const int visA = rem - 4 * grp;
                     if constexpr (APPEND) {
                         if (src.appends(e)) {        // the pair's new token is the group's last
-                            int tA, tB;
-                            src.tiles(e, tA, tB);
-                            if (pending.have) store_new_token<HEAD_DIM, KV>(a, pending, lane);
-                            pending = take_new_token<HEAD_DIM, KV>(regs[u][0], regs[u][1], row_k[u],
-                                                                   row_v[u], rem - 1, tA, tB,
-                                                                   row_stage, lane);
+                            take_new_token<HEAD_DIM, KV>(regs[u][0], regs[u][1], row_k[u], row_v[u],
+                                                         rem - 1, row_stage, lane);
                         }
                     }
                     if constexpr (BLOCK_REDUCE)
@@ -727,6 +681,14 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                         group_update<HEAD_DIM, KV>(regs[u][0], regs[u][1], q_cur, m, l, acc,
                                                    rem < 2 * kBlock, visA, visA - kBlock, visA,
                                                    visA - kBlock, a.scale_log2e);
+                }
+                // refill only after the stage's registers are dead, so the loads land in place --
+                // and before the work at a segment's end, so that this does not delay them
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (APPEND) issue_rows(row_k[u], row_v[u], e + DEPTH);
+                issue_entry(regs[u], e + DEPTH);
+                __builtin_amdgcn_sched_barrier(0);
+                if (e < nc) {
                     if (src.last(e)) {
                         // ---- the segment ends: its partial is (m, l, acc / l)
                         const PartialSlot ps = src.slot(e);
@@ -768,16 +730,8 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                         }
                     }
                 }
-                // refill only after the stage's registers are dead, so the loads land in place
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (APPEND) issue_rows(row_k[u], row_v[u], e + DEPTH);
-                issue_entry(regs[u], e + DEPTH);
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
-    if constexpr (APPEND) {
-        if (pending.have) store_new_token<HEAD_DIM, KV>(a, pending, lane);
     }
 }
 
@@ -901,24 +855,83 @@ flat_prepare_kernel(const FlatArgs a)
 //   WIDE = false: one wavefront per row, four rows per workgroup.
 //   WIDE = true (long contexts, tens of partials per row): one workgroup per row; wavefront w takes
 //   partials w, w + 4, ... -- 4 * kSpec in the first round trip -- and the four sums meet in LDS.
+// Fused step: the merge launch begins with one wavefront per (sequence, KV head) pair (four to a
+// workgroup, ahead of the row workgroups: their stores take the longest, so they start first)
+// that stores the pair's new row into the cache --
+// Opt-KV Eq. 5 and Alg. 1 phase 1, the arithmetic and the bytes of the cache-write kernels.  The
+// attention launch before it has already attended over the row from registers.
+template <int HEAD_DIM>
+__device__ __forceinline__ void append_new_row(const FlatArgs& a, int pair, int lane,
+                                               const uint16_t (&kb)[HEAD_DIM / 64],
+                                               const uint16_t (&vb)[HEAD_DIM / 64], int64_t slot, int t)
+{
+    constexpr int E = HEAD_DIM / 64;
+    if (pair >= a.num_seqs * a.H_k) return;
+    const int seq = pair / a.H_k;
+    const int g = pair - seq * a.H_k;
+    if (slot < 0 || t <= 0) return;                             // Eq. 5: filtered token
+    // where the block table places position t - 1 (the slot names the same place)
+    const int64_t blk = slot / kBlock;
+    const int off = (int)(slot - blk * kBlock);
+    const size_t tile = (size_t)(blk * a.H_k + g);
+    if (a.kv_e4m3) {
+        float kx[E], vx[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            kx[e] = (float)__builtin_bit_cast(half_t, kb[e]);
+            vx[e] = (float)__builtin_bit_cast(half_t, vb[e]);
+        }
+        quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, a.k_cache_w, a.v_cache_w,
+                                           a.k_scale_w, a.v_scale_w);
+    } else {
+        uint16_t* kc = reinterpret_cast<uint16_t*>(a.k_cache_w) + tile * (kBlock * HEAD_DIM);
+        uint16_t* vc = reinterpret_cast<uint16_t*>(a.v_cache_w) + tile * (kBlock * HEAD_DIM);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int dim = lane * E + e;
+            kc[k_tile_index<2>(off, dim)] = kb[e];
+            vc[v_tile_index<2>(off, dim)] = vb[e];
+        }
+    }
+}
+
 template <int HEAD_DIM, bool WIDE>
 __global__ void __launch_bounds__(256)
 flat_merge_kernel(const FlatArgs a)
 {
     constexpr int E = HEAD_DIM / 64;
     constexpr int kSpec = 8;
+
     constexpr int kStep = WIDE ? 4 : 1;                 // distance between a wavefront's partials
     // Every load whose address does not depend on loaded data is issued before the first branch --
     // the schedule's tag, the pair's count, the length, the first 64 (max, sum) pairs and the first
     // kSpec partial rows -- so that the kernel is two memory round trips long, not one per check.
     const int wave = wave_uniform((int)(threadIdx.x >> 6));
     const int rows = a.num_seqs * a.H_q;
-    const int row_id = WIDE ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;   // seq * H_q + head
-    const int row = min(row_id, rows - 1);              // (a surplus wavefront reads the last row)
+    // (fused step: the first append_wgs workgroups store the new rows, see below)
+    const int wg = (int)blockIdx.x - a.append_wgs;
+    const int row_id = WIDE ? wg : wg * 4 + wave;                              // seq * H_q + head
+    const int row = min(max(row_id, 0), rows - 1);      // (a surplus wavefront reads the last row,
+                                                        // an appending one the first)
     const int first = WIDE ? wave : 0;                  // this wavefront's first partial
     const int lane = threadIdx.x & 63;
     const int seq = row / a.H_q;
     const int g = (row - seq * a.H_q) / a.G;
+    // an appending wavefront's row, slot and length are asked for here, with everything else and
+    // ahead of it in program order (loads return in order: its wait then covers nothing more)
+    const int app_pair = (int)blockIdx.x * 4 + wave;
+    const int app_seq = min(app_pair, a.num_seqs * a.H_k - 1) / a.H_k;
+    uint16_t app_k[E] = {}, app_v[E] = {};
+    int64_t app_slot = -1;
+    if (wg < 0) {
+        const size_t at = (size_t)min(app_pair, a.num_seqs * a.H_k - 1) * HEAD_DIM + lane * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            app_k[e] = reinterpret_cast<const uint16_t*>(a.k_new)[at + e];
+            app_v[e] = reinterpret_cast<const uint16_t*>(a.v_new)[at + e];
+        }
+        app_slot = a.new_slots[app_seq];
+    }
     const size_t base = (size_t)row * a.max_slots;
     const float* ml = a.max_logits + base;
     const float* es = a.exp_sums + base;
@@ -927,7 +940,7 @@ flat_merge_kernel(const FlatArgs a)
     // what the partials were laid out for: the schedule's tag, or the one the split kernel left
     const uint32_t* tag_at = a.sched ? a.sched : a.ws_header;
     const uint32_t tag = *tag_at;
-    const int t = a.context_lens[seq];
+    const int t = a.context_lens[wg < 0 ? app_seq : seq];
     int count = a.counts[seq * a.H_k + g];
     float o_spec[kSpec][E];
 #pragma unroll
@@ -944,6 +957,10 @@ flat_merge_kernel(const FlatArgs a)
     // a prepared schedule that is not the expected one (the split kernel wrote nothing), or partials
     // that a split call with another plan or shape left: nothing is written
     if (tag != (a.sched ? a.sched_tag : a.ws_tag)) return;
+    if (wg < 0) {                                        // fused step only: the grid's head
+        append_new_row<HEAD_DIM>(a, app_pair, lane, app_k, app_v, app_slot, t);
+        return;
+    }
     if (row_id >= rows) return;                         // (WIDE: never, the grid is the row count)
     if (t <= 0) count = 0;
     count = wave_uniform(min(count, a.max_slots));
@@ -1221,10 +1238,6 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
         a.new_slots = append->slot_mapping;
         a.k_new = (const half_t*)append->k;
         a.v_new = (const half_t*)append->v;
-        a.k_cache_w = (uint8_t*)const_cast<void*>(k_cache);
-        a.v_cache_w = (uint8_t*)const_cast<void*>(v_cache);
-        a.k_scale_w = const_cast<float*>(k_scale);
-        a.v_scale_w = const_cast<float*>(v_scale);
     }
     if (schedule) {
         if (flat_schedule_bytes(sh, plan) == 0) return COOPT_ERR_SHAPE;
@@ -1249,7 +1262,8 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
 }
 
 int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
-                      const FlatPlan& plan, hipStream_t stream, const void* schedule, bool fused)
+                      const FlatPlan& plan, hipStream_t stream, const void* schedule, bool fused,
+                      const FlatAppend* append, const FlatCacheW* cache)
 {
     FlatArgs a = flat_args(sh, plan, workspace);
     a.context_lens = context_lens;
@@ -1260,15 +1274,28 @@ int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, c
         a.sched_tag = sched_layout(sh, plan, fused).tag;
     }
     const size_t rows = (size_t)sh->num_seqs * sh->num_q_heads;
-    const dim3 rblock(256);
-    if (a.max_slots > 32) {      // rows may have tens of partials: a workgroup per row
-        const dim3 rgrid((unsigned)rows);
+    const bool wide = a.max_slots > 32;      // rows may have tens of partials: a workgroup per row
+    long long wgs = wide ? (long long)rows : (long long)((rows + 3) / 4);
+    if (append) {
+        a.new_slots = append->slot_mapping;
+        a.k_new = (const half_t*)append->k;
+        a.v_new = (const half_t*)append->v;
+        a.k_cache_w = (uint8_t*)cache->k_cache;
+        a.v_cache_w = (uint8_t*)cache->v_cache;
+        a.k_scale_w = cache->k_scale;
+        a.v_scale_w = cache->v_scale;
+        a.kv_e4m3 = sh->kv_dtype == COOPT_KV_E4M3;
+        a.append_wgs = (int32_t)(((long long)sh->num_seqs * sh->num_kv_heads + 3) / 4);
+        wgs += a.append_wgs;
+    }
+    if (wgs > 0x7fffffffLL) return COOPT_ERR_SHAPE;
+    const dim3 rblock(256), rgrid((unsigned)wgs);
+    if (wide) {
         if (sh->head_dim == 128)
             hipLaunchKernelGGL((flat_merge_kernel<128, true>), rgrid, rblock, 0, stream, a);
         else
             hipLaunchKernelGGL((flat_merge_kernel<64, true>), rgrid, rblock, 0, stream, a);
     } else {
-        const dim3 rgrid((unsigned)((rows + 3) / 4));
         if (sh->head_dim == 128)
             hipLaunchKernelGGL((flat_merge_kernel<128, false>), rgrid, rblock, 0, stream, a);
         else

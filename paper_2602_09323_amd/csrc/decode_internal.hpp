@@ -26,9 +26,18 @@ struct FlatAppend {
     const int64_t* slot_mapping;
 };
 
+// The cache as the fused step writes to it (scales NULL for fp16 caches).
+struct FlatCacheW {
+    void* k_cache;
+    void* v_cache;
+    float* k_scale;
+    float* v_scale;
+};
+
 // Enqueue the balanced split kernel (attention -> partial results in the workspace; with `append`
 // also the cache write of one new token per sequence and that token's partial) and the merge
-// kernel (partials -> fp16 output rows).  Both derive the same schedule from the context lengths
+// kernel (partials -> fp16 output rows; with `append` and `cache` it also stores the new rows,
+// which the split kernel only attended over).  Both derive the same schedule from the context lengths
 // and the plan, so the plan must not change between them.  With `schedule` (written by
 // launch_flat_prepare for the same shape, plan and mode) the split kernel reads its shares from
 // there instead of deriving them (block_tables is then unused), and the merge kernel the counts
@@ -41,7 +50,8 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
                       const void* schedule = nullptr);
 int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, const coopt_shape* sh,
                       const FlatPlan& plan, hipStream_t stream, const void* schedule = nullptr,
-                      bool fused = false);
+                      bool fused = false, const FlatAppend* append = nullptr,
+                      const FlatCacheW* cache = nullptr);
 
 // Bytes of a prepared schedule for this shape and plan (0: the shape is out of range), and the
 // launch that writes one: slot_mapping NULL for plain decode, else the fused step's new tokens.
