@@ -57,7 +57,8 @@ struct PrefillStage {
     static constexpr int kK = 0;                        // [2 blocks][kKOps][64 lanes] 8 halves
     static constexpr int kV = 2 * kKOps * 1024;         // [kVOps][64 lanes] 4 halves of A, 4 of B
     static constexpr int kS = kV + kVOps * 1024;        // 16 floats each: k_scale*c A, B; v_scale A, B
-    static constexpr int kBytes = kS + 256;
+    static constexpr int kR = kS + 256;                 // [64 lanes] 8 halves: 1/v_scale rows (below)
+    static constexpr int kBytes = kR + 1024;
 };
 
 // One online-softmax step of a 16-column tile against a group whose operands are ready, in two
@@ -82,12 +83,24 @@ __device__ __forceinline__ void tile_scores(const half8_t (&kA)[HEAD_DIM / 32],
     }
 }
 
+// The weights enter the second product rounded to fp16, w~ = fp16(P * v_scale): one token's weight
+// is then off by up to 2^-11 relative, which shows in the output when that token carries the row
+// (an fp16 output near |x| = 3 moves by 1.5e-3).  So the row sum is taken from the SAME rounded
+// weights, l = sum_j w~_j / v_scale_j: numerator and denominator then describe one softmax with
+// weights perturbed by 2^-11 relative, whose result differs from the exact one by at most 2^-11
+// times the weighted mean deviation of the value rows from the result -- nothing for one token or
+// a dominant one.  The sum runs on the matrix cores: `rop` is a 16-row operand whose row 0 holds
+// 2^-8 / v_scale of the group's 32 tokens cut to fp16 and row 1 the remainder (the producers
+// write it), so one more 16x16x32 product per tile accumulates it in rows 0 and 1 of `lacc`,
+// which replaces eight vector additions.  2^-8 keeps the reciprocals inside fp16 for every
+// v_scale a finite fp16 row can have down to 2^-24.
 template <int HEAD_DIM>
 __device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
-                                                const half8_t (&vop)[HEAD_DIM / 16], floatx4 kscA,
-                                                floatx4 kscB, floatx4 vsA, floatx4 vsB, float& m,
-                                                float& l, floatx4 (&acc)[HEAD_DIM / 16], bool tail,
-                                                int visA, int visB)
+                                                const half8_t (&vop)[HEAD_DIM / 16], half8_t rop,
+                                                floatx4 kscA, floatx4 kscB, floatx4 vsA, floatx4 vsB,
+                                                float& m, floatx4& lacc,
+                                                floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA,
+                                                int visB)
 {
     float z[8];
 #pragma unroll
@@ -109,7 +122,7 @@ __device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
         nm = fmaxf(nm, __shfl_xor(nm, 32));
         nm = fmaxf(nm, m);
         const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = -inf at the start gives 0
-        l *= alpha;
+        lacc *= alpha;
 #pragma unroll
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
         m = nm;
@@ -117,38 +130,15 @@ __device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
     const float mm = m - kPShift;
     float p[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(z[i] - mm);             // invisible: exp2(-inf) = 0
-        l += p[i];
-    }
-    // The weights enter the second product as fp16.  Where one token may carry a sizeable part of
-    // a row's softmax (some lane holds a weight above 1/16 of its running sum: the first groups of
-    // every row, peaked rows) they go in as the pair hi + lo of attn_tile.hpp, two products against
-    // the same V operand, because a single weight's fp16 rounding (2^-11 relative) would then show
-    // in the output; elsewhere no token contributes more than 1/16 of the row and the roundings of
-    // many small weights average out, so one rounded weight and one product do.  (A weight's share
-    // of the final sum is never above its share of the sum at the time: l only grows, apart from
-    // the rescale it shares with every weight before it.)
-    const bool precise = __builtin_amdgcn_ballot_w64(__builtin_amdgcn_exp2f(bm - mm) * 16.0f > l) != 0;
-#pragma unroll
     for (int i = 0; i < 4; ++i) {
-        p[i] *= vsA[i];
-        p[4 + i] *= vsB[i];
+        p[i] = __builtin_amdgcn_exp2f(z[i] - mm) * vsA[i];    // invisible: exp2(-inf) = 0
+        p[4 + i] = __builtin_amdgcn_exp2f(z[4 + i] - mm) * vsB[i];
     }
-    if (precise) {
-        half8_t hi, lo;
-        split_weights(p, hi, lo);
+    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
+                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+    lacc = mfma_16x16x32(rop, pop, lacc);
 #pragma unroll
-        for (int c = 0; c < HEAD_DIM / 16; ++c) {
-            acc[c] = mfma_16x16x32(vop[c], hi, acc[c]);
-            acc[c] = mfma_16x16x32(vop[c], lo, acc[c]);
-        }
-    } else {
-        const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
-                             (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
-#pragma unroll
-        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
-    }
+    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
 }
 
 template <int HEAD_DIM, int KV, int NR, bool BIG>
@@ -217,12 +207,13 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int num_groups = (nblk + 1) >> 1;
     const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks;
 
-    float m[NR], l[NR];
+    float m[NR];
+    floatx4 lacc[NR];       // rows 0 and 1 (lanes of group 0, registers 0 and 1): the row sums / 2^8
     floatx4 acc[NR][HEAD_DIM / 16];
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         m[r] = -INFINITY;
-        l[r] = 0.0f;
+        lacc[r] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
@@ -326,13 +317,25 @@ prefill_chunk_kernel(const PrefillArgs a)
                     }
                 }
             }
-            if constexpr (FP8) {
-                const int cache = wave == 2 ? cacheA : cacheB;
-                floatx4 vs;
+            // v_scale of this wave's block (wave 2: A, wave 3: B), zero for tokens not in the cache
+            // (a stale scale), and the operand of the row-sum product: row 0 = 2^-8 / v_scale cut
+            // to fp16, row 1 = the remainder, rows 2..15 zero; block A's tokens are the lane's
+            // first four halves, block B's the other four
+            const int cache = wave == 2 ? cacheA : cacheB;
+            floatx4 vs;
+            half4_t rr;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vs[i] = (i < cache) ? psc[i] : 0.0f;   // a stale scale
+            for (int i = 0; i < 4; ++i) {
+                vs[i] = FP8 ? ((i < cache) ? psc[i] : 0.0f) : 1.0f;
+                // (the hardware reciprocal, 1 ulp: far inside what the fp16 pair keeps)
+                const float r = fminf(vs[i] > 0.0f ? 0.00390625f * __builtin_amdgcn_rcpf(vs[i]) : 0.0f, 65504.0f);
+                const float hi = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, r) & 0xffffe000u);
+                rr[i] = n == 0 ? (half_t)hi : (n == 1 ? (half_t)(r - hi) : (half_t)0.0f);
+            }
+            if constexpr (FP8) {
                 if (n == 0) *reinterpret_cast<floatx4*>(st + St::kS + 64 * wave + 16 * grp) = vs;
             }
+            *reinterpret_cast<half4_t*>(st + St::kR + 16 * lane + 8 * (wave - 2)) = rr;
         }
     };
 
@@ -348,6 +351,7 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int c = 0; c < St::kVOps; ++c)
             vop[c] = *reinterpret_cast<const half8_t*>(st + St::kV + c * 1024 + 16 * lane);
+        const half8_t rop = *reinterpret_cast<const half8_t*>(st + St::kR + 16 * lane);
         floatx4 kscA, kscB, vsA, vsB;
         if constexpr (FP8) {
             kscA = *reinterpret_cast<const floatx4*>(st + St::kS + 16 * grp);
@@ -368,8 +372,8 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             const int visA = limit[r] - tokA;
-            tile_softmax_pv<HEAD_DIM>(sA[r], sB[r], vop, kscA, kscB, vsA, vsB, m[r], l[r], acc[r],
-                                      tail, visA, hasB ? visA - kBlock : 0);
+            tile_softmax_pv<HEAD_DIM>(sA[r], sB[r], vop, rop, kscA, kscB, vsA, vsB, m[r], lacc[r],
+                                      acc[r], tail, visA, hasB ? visA - kBlock : 0);
         }
     };
 
@@ -432,9 +436,8 @@ prefill_chunk_kernel(const PrefillArgs a)
     if (!active) return;
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-        float L = l[r];
-        L += __shfl_xor(L, 16);
-        L += __shfl_xor(L, 32);
+        // column n's sum sits in rows 0 and 1 of lacc: lane (n, 0), registers 0 and 1
+        const float L = __shfl(lacc[r][0] + lacc[r][1], n) * 256.0f;
         const float inv = 1.0f / L;                       // the common power of two of acc and l cancels
         const int row = row0[r] + n;
         if (first_tile + r < end_tile && row < C) {
