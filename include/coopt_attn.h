@@ -24,7 +24,7 @@
  * Tensor layouts (NB = physical blocks, H_k = KV heads, B = block_size = 16, d = head_dim)
  * ---------------------------------------------------------------------------------------
  * The cache is a pool of tiles; one tile holds the B tokens x d dims of one (physical block, KV
- * head), as u8 OCP-E4M3 codes or as fp16, in the order the matrix-core operands consume them, so
+ * head), as u8 OCP-E4M3 (or E5M2) codes or as fp16, in the order the matrix-core operands consume them, so
  * that every wavefront load is 64 x 16 contiguous bytes.  With E = elements per 16 bytes (16 for
  * E4M3, 8 for fp16), tile index = block * H_k + head, and element indices within a tile:
  *   k_cache  [NB*H_k][d/E][B][E]            (tok, dim) -> ((dim/E)*B + tok)*E + dim%E
@@ -32,7 +32,7 @@
  *   v_cache  [NB*H_k][d/(4E)][B/4][16][E/4][4]   with c = dim/16, n = dim%16, W = E/4:
  *                                           (tok, dim) -> ((((c/W)*(B/4) + tok/4)*16 + n)*W + c%W)*4 + tok%4
  *                                           (token index innermost in runs of 4, then W dim groups)
- *   k_scale  [NB*H_k][B]   binary32, E4M3 caches only: value = code * scale
+ *   k_scale  [NB*H_k][B]   binary32, one-byte caches only: value = code * scale
  *   v_scale  [NB*H_k][B]
  *   block_tables [S][max_blocks_per_seq]   logical block -> physical block; only entries
  *                                          b < ceil(context_len/B) are ever used (Opt-Pa, Eq. 9)
@@ -61,7 +61,13 @@ typedef enum coopt_status {
     COOPT_ERR_LAUNCH = -4       /* the HIP runtime refused the launch */
 } coopt_status;
 
-enum { COOPT_KV_FP16 = 0, COOPT_KV_E4M3 = 1 };
+/* Cache element type.  E4M3 is the method as this library reads it (Opt-KV says "FP8"); E5M2 and
+ * the scale modes below are the alternatives that choice stands against, built so that they can be
+ * measured on the same kernels. */
+enum { COOPT_KV_FP16 = 0, COOPT_KV_E4M3 = 1, COOPT_KV_E5M2 = 2 };
+
+/* How a written row gets its scale (coopt_kv_cache_write_fp8_scaled). */
+enum { COOPT_SCALE_TOKEN = 0, COOPT_SCALE_BLOCK = 1, COOPT_SCALE_STATIC = 2 };
 
 /*
  * Problem shape.  Supported: head_dim 64 or 128; block_size 16; num_q_heads a multiple of
@@ -80,7 +86,7 @@ typedef struct coopt_shape {
     int32_t block_size;          /* B */
     int32_t num_blocks;          /* NB */
     int32_t max_blocks_per_seq;  /* row stride of block_tables */
-    int32_t kv_dtype;            /* COOPT_KV_FP16 or COOPT_KV_E4M3 */
+    int32_t kv_dtype;            /* COOPT_KV_FP16, COOPT_KV_E4M3 or COOPT_KV_E5M2 */
     float softmax_scale;         /* multiplies q.k before the softmax; 1/sqrt(d) in Eq. 1 */
 } coopt_shape;
 
@@ -128,12 +134,35 @@ void coopt_default_decode_plan(coopt_decode_plan* plan);
  *   k, v           [num_tokens][H_k][d] fp16, contiguous            (read)
  *   slot_mapping   [num_tokens] int64                               (read)
  *   k_cache, v_cache, k_scale, v_scale                              (written at the named slots only)
- * shape->kv_dtype must be COOPT_KV_E4M3.  num_tokens == 0 is a no-op.
+ * shape->kv_dtype must be COOPT_KV_E4M3, or COOPT_KV_E5M2 (OCP E5M2: 1-5-2, bias 15, max finite
+ * 57344; the same rule with 57344 in place of 448).  num_tokens == 0 is a no-op.
  */
 int coopt_kv_cache_write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
                              int32_t num_tokens, uint8_t* k_cache, uint8_t* v_cache,
                              float* k_scale, float* v_scale, const coopt_shape* shape,
                              void* hip_stream);
+
+/*
+ * The same write with another scale rule: what Opt-KV's FP8 compression looks like under the
+ * scale granularities the paper leaves open (it says only "FP8"), kept to measure the dynamic
+ * per-token scale against them on the same cache layout and the same read kernels -- the scale
+ * arrays keep one entry per (token, KV head) in every mode, so all read entry points serve all
+ * modes unchanged.
+ *   scale_mode  COOPT_SCALE_TOKEN   as coopt_kv_cache_write_fp8
+ *               COOPT_SCALE_BLOCK   one scale for all rows of THIS CALL that land in the same
+ *                                   cache block and KV head: (largest absmax among them) / max
+ *                                   code; rows written to the block by other calls keep theirs
+ *               COOPT_SCALE_STATIC  k_static[head] / v_static[head] (device, float [H_k], > 0),
+ *                                   fixed by the caller in advance; values beyond scale * max
+ *                                   code saturate
+ *   k_static, v_static  NULL unless COOPT_SCALE_STATIC
+ * kv_dtype COOPT_KV_E4M3 or COOPT_KV_E5M2.  COOPT_ERR_SHAPE for another scale_mode.
+ */
+int coopt_kv_cache_write_fp8_scaled(const void* k, const void* v, const int64_t* slot_mapping,
+                                    int32_t num_tokens, uint8_t* k_cache, uint8_t* v_cache,
+                                    float* k_scale, float* v_scale, int32_t scale_mode,
+                                    const float* k_static, const float* v_static,
+                                    const coopt_shape* shape, void* hip_stream);
 
 /*
  * The same scatter without compression: fp16 bit patterns are stored unchanged (the unquantised

@@ -24,6 +24,13 @@
  * The two divisions of the write path are done in binary32 so that the cache
  * bytes and the scales are *defined* bit for bit; everything else is float64.
  *
+ * The alternatives that reading stands against are here too, for comparison on
+ * the same cache layout (orc_kv_cache_write_fp8_scaled): OCP E5M2 codes (1-5-2,
+ * bias 15, max finite 57344, S.11111.00 = infinity, other S.11111.xx = NaN),
+ * and a scale that is not the row's own: one per cache block (the largest absmax
+ * among the call's rows that land in the block) or a static one per KV head.
+ * kv_dtype: 0 = fp16 cache, 1 = E4M3 codes, 2 = E5M2 codes.
+ *
  * Tensor layouts (the oracle owns one index function per tensor):
  *   k, v (new tokens) ... [T, H_k, d]        fp16 bit patterns
  *   k_cache ............. [NB*H_k tiles][d/E][B][E]            E = elements per 16 bytes
@@ -115,6 +122,75 @@ void orc_f32_to_e4m3_array(const float *y, uint8_t *out, size_t n)
         out[i] = orc_f32_to_e4m3(y[i]);
 }
 
+/* OCP E5M2 code -> double.  exponent field 0: (m/4)*2^-14; 31: infinity (m = 0) or NaN;
+ * else (1+m/4)*2^(e-15). */
+double orc_e5m2_to_f64(uint8_t c)
+{
+    int sign = (c >> 7) & 1;
+    int e = (c >> 2) & 0x1f;
+    int m = c & 3;
+    double v;
+    if (e == 31)
+        v = m ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)m / 4.0, -14);
+    else
+        v = ldexp(1.0 + (double)m / 4.0, e - 15);
+    return sign ? -v : v;
+}
+
+/*
+ * binary32 -> OCP E5M2, round to nearest, ties to even mantissa, saturating at
+ * +-57344 (never an infinity).  The sign bit is kept.  NaN -> 0x7F.
+ */
+uint8_t orc_f32_to_e5m2(float y)
+{
+    uint8_t sign = signbit(y) ? 0x80 : 0x00;
+    double a = fabs((double)y);
+    if (isnan(y))
+        return 0x7f;
+    if (a >= 57344.0)
+        return sign | 0x7b;
+    if (a < ldexp(1.0, -14)) {
+        /* subnormal grid, spacing 2^-16; a result of 4 is the code 0x04 = 2^-14, the first normal */
+        int r = (int)rint(ldexp(a, 16));
+        return sign | (uint8_t)r;
+    }
+    int ex;
+    double fr = frexp(a, &ex);      /* a = fr * 2^ex, fr in [0.5,1) */
+    double mant = fr * 2.0;         /* in [1,2) */
+    int e = ex - 1;
+    int r = (int)rint((mant - 1.0) * 4.0);   /* 0..4, ties to even r */
+    if (r == 4) {
+        r = 0;
+        e += 1;
+    }
+    int field = e + 15;
+    if (field >= 31)
+        return sign | 0x7b;         /* cannot happen for a < 57344, kept for safety */
+    return sign | (uint8_t)((field << 2) | r);
+}
+
+void orc_f32_to_e5m2_array(const float *y, uint8_t *out, size_t n)
+{
+    for (size_t i = 0; i < n; i++)
+        out[i] = orc_f32_to_e5m2(y[i]);
+}
+
+/* Largest finite value of a one-byte code, and its decode / encode, by kv_dtype (1 or 2). */
+static float code_max(int kv_dtype)
+{
+    return kv_dtype == 2 ? 57344.0f : 448.0f;
+}
+static double code_to_f64(uint8_t c, int kv_dtype)
+{
+    return kv_dtype == 2 ? orc_e5m2_to_f64(c) : orc_e4m3_to_f64(c);
+}
+static uint8_t f32_to_code(float y, int kv_dtype)
+{
+    return kv_dtype == 2 ? orc_f32_to_e5m2(y) : orc_f32_to_e4m3(y);
+}
+
 /* ------------------------------------------------------------ index functions */
 
 /* E = elements per 16 bytes: 16 for one-byte codes, 8 for fp16.
@@ -139,25 +215,44 @@ static size_t idx_scale(int blk, int head, int off, int H_k, int B)
 
 /* ------------------------------------------------------------------- write */
 
-/* One row (one token, one KV head, K or V): dynamic scale and codes. */
-static void quantise_row(const uint16_t *x16, int d, float *scale_out, uint8_t *codes)
+/* Absmax of one row (fp16 is exact in binary32). */
+static float row_absmax(const uint16_t *x16, int d)
 {
     float amax = 0.0f;
     for (int i = 0; i < d; i++) {
-        float a = fabsf((float)orc_f16_to_f64(x16[i]));     /* fp16 is exact in binary32 */
+        float a = fabsf((float)orc_f16_to_f64(x16[i]));
         if (a > amax)
             amax = a;
     }
-    float scale = (amax == 0.0f) ? 1.0f : amax / 448.0f;     /* binary32 division */
+    return amax;
+}
+
+/* The scale that maps absmax amax to the code's largest value; an all-zero row gets 1. */
+static float scale_of_absmax(float amax, int kv_dtype)
+{
+    return (amax == 0.0f) ? 1.0f : amax / code_max(kv_dtype);      /* binary32 division */
+}
+
+/* One row (one token, one KV head, K or V) under a given scale: the codes. */
+static void quantise_row_scaled(const uint16_t *x16, int d, float scale, int kv_dtype, uint8_t *codes)
+{
+    float cmax = code_max(kv_dtype);
     for (int i = 0; i < d; i++) {
         float x = (float)orc_f16_to_f64(x16[i]);
         float y = x / scale;                                   /* binary32 division */
-        if (y > 448.0f)
-            y = 448.0f;
-        if (y < -448.0f)
-            y = -448.0f;
-        codes[i] = orc_f32_to_e4m3(y);
+        if (y > cmax)
+            y = cmax;
+        if (y < -cmax)
+            y = -cmax;
+        codes[i] = f32_to_code(y, kv_dtype);
     }
+}
+
+/* One row with its own (dynamic) scale = absmax / 448: scale and E4M3 codes. */
+static void quantise_row(const uint16_t *x16, int d, float *scale_out, uint8_t *codes)
+{
+    float scale = scale_of_absmax(row_absmax(x16, d), 1);
+    quantise_row_scaled(x16, d, scale, 1, codes);
     *scale_out = scale;
 }
 
@@ -198,6 +293,65 @@ void orc_kv_cache_write_fp8(const uint16_t *k, const uint16_t *v, const int64_t 
     free(codes);
 }
 
+/*
+ * The same write under another code and another scale rule (the schemes the dynamic per-token
+ * E4M3 scale stands against).  kv_dtype 1 = E4M3, 2 = E5M2.  scale_mode:
+ *   0  every row's own scale, absmax / max code (with kv_dtype 1 this is orc_kv_cache_write_fp8);
+ *   1  one scale per (cache block, KV head) for the rows of THIS call: the largest absmax among
+ *      the call's written tokens whose slot lies in the block, / max code;
+ *   2  static: k_static[h] / v_static[h], whatever the rows hold (larger values saturate).
+ * The scale arrays keep one entry per (token, head) in every mode.
+ */
+void orc_kv_cache_write_fp8_scaled(const uint16_t *k, const uint16_t *v, const int64_t *slot_mapping,
+                                   const uint32_t *skip_set, int T, uint8_t *k_cache,
+                                   uint8_t *v_cache, float *k_scale, float *v_scale, int H_k, int d,
+                                   int B, int kv_dtype, int scale_mode, const float *k_static,
+                                   const float *v_static)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)d);
+    for (int i = 0; i < T; i++) {
+        int64_t slot = slot_mapping[i];
+        if (slot < 0 || in_skip_set(skip_set, i))
+            continue;
+        int blk = (int)(slot / B);
+        int off = (int)(slot % B);
+        for (int h = 0; h < H_k; h++) {
+            const uint16_t *krow = k + ((size_t)i * H_k + h) * d;
+            const uint16_t *vrow = v + ((size_t)i * H_k + h) * d;
+            float ks, vs;
+            if (scale_mode == 2) {
+                ks = k_static[h];
+                vs = v_static[h];
+            } else {
+                float ka = row_absmax(krow, d), va = row_absmax(vrow, d);
+                if (scale_mode == 1)
+                    for (int i2 = 0; i2 < T; i2++) {           /* the call's other rows of this block */
+                        int64_t s2 = slot_mapping[i2];
+                        if (s2 < 0 || in_skip_set(skip_set, i2) || s2 / B != blk)
+                            continue;
+                        float a = row_absmax(k + ((size_t)i2 * H_k + h) * d, d);
+                        if (a > ka)
+                            ka = a;
+                        a = row_absmax(v + ((size_t)i2 * H_k + h) * d, d);
+                        if (a > va)
+                            va = a;
+                    }
+                ks = scale_of_absmax(ka, kv_dtype);
+                vs = scale_of_absmax(va, kv_dtype);
+            }
+            quantise_row_scaled(krow, d, ks, kv_dtype, codes);
+            k_scale[idx_scale(blk, h, off, H_k, B)] = ks;
+            for (int x = 0; x < d; x++)
+                k_cache[idx_kcache(blk, h, off, x, H_k, B, d, 16)] = codes[x];
+            quantise_row_scaled(vrow, d, vs, kv_dtype, codes);
+            v_scale[idx_scale(blk, h, off, H_k, B)] = vs;
+            for (int x = 0; x < d; x++)
+                v_cache[idx_vcache(blk, h, off, x, H_k, B, d, 16)] = codes[x];
+        }
+    }
+    free(codes);
+}
+
 /* Same scatter with the fp16 pattern stored unchanged (the unquantised comparison case). */
 void orc_kv_cache_write_fp16(const uint16_t *k, const uint16_t *v, const int64_t *slot_mapping,
                              const uint32_t *skip_set, int T, uint16_t *k_cache, uint16_t *v_cache,
@@ -219,14 +373,15 @@ void orc_kv_cache_write_fp16(const uint16_t *k, const uint16_t *v, const int64_t
 
 /* ------------------------------------------------------------- cache reads */
 
-/* Dequantised key element of logical token j of sequence s (Eq. 6, Eq. 9). kv_dtype 1 = E4M3. */
+/* Dequantised key element of logical token j of sequence s (Eq. 6, Eq. 9).
+ * kv_dtype 0 = fp16 cache, 1 = E4M3 codes, 2 = E5M2 codes (both with scales). */
 static double load_k(const void *k_cache, const float *k_scale, const int32_t *bt_row, int j,
                      int g, int x, int H_k, int d, int B, int kv_dtype)
 {
     int pb = bt_row[j / B];
     int off = j % B;
-    if (kv_dtype == 1)
-        return orc_e4m3_to_f64(((const uint8_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d, 16)]) *
+    if (kv_dtype != 0)
+        return code_to_f64(((const uint8_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d, 16)], kv_dtype) *
                (double)k_scale[idx_scale(pb, g, off, H_k, B)];
     return orc_f16_to_f64(((const uint16_t *)k_cache)[idx_kcache(pb, g, off, x, H_k, B, d, 8)]);
 }
@@ -235,8 +390,8 @@ static double load_v(const void *v_cache, const float *v_scale, const int32_t *b
 {
     int pb = bt_row[j / B];
     int off = j % B;
-    if (kv_dtype == 1)
-        return orc_e4m3_to_f64(((const uint8_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d, 16)]) *
+    if (kv_dtype != 0)
+        return code_to_f64(((const uint8_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d, 16)], kv_dtype) *
                (double)v_scale[idx_scale(pb, g, off, H_k, B)];
     return orc_f16_to_f64(((const uint16_t *)v_cache)[idx_vcache(pb, g, off, x, H_k, B, d, 8)]);
 }

@@ -22,9 +22,14 @@ _lib = None
 
 COOPT_KV_FP16 = 0
 COOPT_KV_E4M3 = 1
+COOPT_KV_E5M2 = 2
+COOPT_SCALE_TOKEN = 0
+COOPT_SCALE_BLOCK = 1
+COOPT_SCALE_STATIC = 2
 
 EXPORTS = [
     "coopt_kv_cache_write_fp8", "coopt_kv_cache_write_fp16", "coopt_kv_cache_write_skipset",
+    "coopt_kv_cache_write_fp8_scaled",
     "coopt_paged_gqa_decode", "coopt_paged_gqa_decode_step", "coopt_paged_gqa_decode_split",
     "coopt_paged_gqa_decode_merge", "coopt_decode_workspace_bytes", "coopt_default_decode_plan",
     "coopt_paged_gqa_decode_partitioned", "coopt_paged_gqa_reduce", "coopt_paged_gqa_prefill_chunk",
@@ -72,6 +77,7 @@ def load_library():
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         shp, plp = ctypes.POINTER(Shape), ctypes.POINTER(DecodePlan)
         lib.coopt_kv_cache_write_fp8.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, shp, vp]
+        lib.coopt_kv_cache_write_fp8_scaled.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, shp, vp]
         lib.coopt_kv_cache_write_fp16.argtypes = [vp, vp, vp, i32, vp, vp, shp, vp]
         lib.coopt_kv_cache_write_skipset.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, shp, vp]
         lib.coopt_paged_gqa_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, plp, shp, vp]
@@ -149,7 +155,7 @@ def _dev(t, name: str, *, min_bytes: int = 0, elem: Optional[int] = None, dtype=
 
 
 def _sizes(shape: Shape):
-    es = 1 if shape.kv_dtype == COOPT_KV_E4M3 else 2
+    es = 2 if shape.kv_dtype == COOPT_KV_FP16 else 1
     tiles = shape.num_blocks * shape.num_kv_heads
     return {"cache": tiles * shape.block_size * shape.head_dim * es,
             "scale": tiles * shape.block_size * 4,
@@ -157,12 +163,12 @@ def _sizes(shape: Shape):
             "tables": shape.num_seqs * shape.max_blocks_per_seq * 4,
             "lens": shape.num_seqs * 4,
             "row": shape.num_kv_heads * shape.head_dim * 2,
-            "e4m3": shape.kv_dtype == COOPT_KV_E4M3}
+            "scaled": shape.kv_dtype != COOPT_KV_FP16}
 
 
 def _cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape: Shape):
     z = _sizes(shape)
-    scaled = z["e4m3"]
+    scaled = z["scaled"]
     return (_dev(k_cache, "k_cache", min_bytes=z["cache"]), _dev(v_cache, "v_cache", min_bytes=z["cache"]),
             _dev(k_scale, "k_scale", min_bytes=z["scale"], optional=not scaled),
             _dev(v_scale, "v_scale", min_bytes=z["scale"], optional=not scaled))
@@ -224,6 +230,20 @@ def kv_cache_write_fp8(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, s
     _call("coopt_kv_cache_write_fp8",
           pk, pv, ps, T, *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape), ctypes.byref(shape),
         _stream(stream))
+
+
+def kv_cache_write_fp8_scaled(k, v, slot_mapping, k_cache, v_cache, k_scale, v_scale, shape: Shape,
+                              scale_mode: int, k_static=None, v_static=None, stream=None) -> None:
+    """The write under another scale rule (COOPT_SCALE_*); k_static / v_static: device float32
+    [H_k], required for COOPT_SCALE_STATIC only."""
+    pk, pv, ps, T = _new_rows(k, v, slot_mapping, shape, "kv_cache_write_fp8_scaled")
+    static = int(scale_mode) == COOPT_SCALE_STATIC
+    hk = shape.num_kv_heads * 4
+    _call("coopt_kv_cache_write_fp8_scaled",
+          pk, pv, ps, T, *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape), int(scale_mode),
+          _dev(k_static, "k_static", elem=4, min_bytes=hk, optional=not static),
+          _dev(v_static, "v_static", elem=4, min_bytes=hk, optional=not static),
+          ctypes.byref(shape), _stream(stream))
 
 
 def kv_cache_write_skipset(k, v, slot_mapping, skip_set, k_cache, v_cache, k_scale, v_scale,

@@ -50,16 +50,20 @@ struct CacheView {
 // = 2^8: times a v_scale of at most 65504/448 that is still inside fp16.  Raising m lazily makes
 // the rescale branch rare after the first group (a later score must beat the running max by a
 // factor of 4), and any reference works: it cancels in O/L and in the merge of partials.
-constexpr float kPShift = 6.0f;
+// An E5M2 cache's scales are 2^-7 of an E4M3 cache's (largest code 57344 against 448), so its
+// weights are carried 2^7 higher: P * 2^13 * v_scale then lies where the E4M3 weights lie, well
+// inside fp16's normal range for value rows of ordinary magnitude, and at most 2^15 * 65504/57344.
+constexpr float kPShift = 6.0f;                     // (chunked prefill: it normalises the scales itself)
 constexpr float kRescaleSlack = 2.0f;
-constexpr float kPUnshift = 1.0f / 64.0f;
+template <int KV> constexpr float kPShiftOf = KV == COOPT_KV_E5M2 ? 13.0f : 6.0f;
+template <int KV> constexpr float kPUnshiftOf = KV == COOPT_KV_E5M2 ? 1.0f / 8192.0f : 1.0f / 64.0f;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // Raw bytes of one tile as loaded by lane (n, grp): NL 16-byte pieces of K and of V, 4 + 4 scales.
 template <int HEAD_DIM, int KV>
 struct BlockRegs {
-    static constexpr int ES = (KV == COOPT_KV_E4M3) ? 1 : 2;
+    static constexpr int ES = kIsFp8<KV> ? 1 : 2;
     static constexpr int NL = HEAD_DIM * ES / 64;     // 16-byte loads per lane for K (and for V)
     u32x4 k[NL];
     u32x4 v[NL];
@@ -79,7 +83,7 @@ struct BlockRegs {
 // Tile loads carry the non-temporal hint: every byte of the cache is read once per step.
 template <int HEAD_DIM, int KV, bool BIG>
 struct TileLoader {
-    static constexpr int ES = (KV == COOPT_KV_E4M3) ? 1 : 2;
+    static constexpr int ES = kIsFp8<KV> ? 1 : 2;
     static constexpr int kTileBytes = kBlock * HEAD_DIM * ES;
     static constexpr int kRsrcFlags = 0x00020000;      // gfx9 raw buffer, 32-bit data format
     static constexpr int kAuxStream = 2;               // nt
@@ -142,7 +146,7 @@ struct TileLoader {
 #pragma unroll
             for (int j = 0; j < NL; ++j)
                 r.v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, lane_off + 1024 * j, 0, kAuxStream);
-            if constexpr (KV == COOPT_KV_E4M3) {
+            if constexpr (kIsFp8<KV>) {
                 const size_t soff = (size_t)(uint32_t)tile * kBlock;
                 const int sext = valid ? kBlock * 4 : 0;
                 const __amdgpu_buffer_rsrc_t rks = rsrc(cv.k_scale + soff, sext);
@@ -161,7 +165,7 @@ struct TileLoader {
 #pragma unroll
             for (int j = 0; j < NL; ++j)
                 r.v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, lane_off + 1024 * j, so, kAuxStream);
-            if constexpr (KV == COOPT_KV_E4M3) {
+            if constexpr (kIsFp8<KV>) {
                 const int sext = valid ? scale_pool_bytes : 0;
                 const __amdgpu_buffer_rsrc_t rks = rsrc(cv.k_scale, sext);
                 const __amdgpu_buffer_rsrc_t rvs = rsrc(cv.v_scale, sext);
@@ -176,7 +180,7 @@ struct TileLoader {
 // True when every tensor of the pool can be addressed with a 31-bit byte offset.
 inline bool pool_fits_small(const coopt_shape* sh)
 {
-    const long long es = sh->kv_dtype == COOPT_KV_E4M3 ? 1 : 2;
+    const long long es = sh->kv_dtype == COOPT_KV_FP16 ? 2 : 1;
     return (long long)sh->num_blocks * sh->num_kv_heads * kBlock * sh->head_dim * es < (1LL << 31);
 }
 
@@ -185,7 +189,7 @@ inline bool pool_fits_small(const coopt_shape* sh)
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ int q_dim_offset(int jj, int grp)
 {
-    if constexpr (KV == COOPT_KV_E4M3)
+    if constexpr (kIsFp8<KV>)
         return 64 * (jj >> 1) + 16 * grp + 8 * (jj & 1);
     else
         return 32 * jj + 8 * grp;
@@ -226,9 +230,9 @@ __device__ __forceinline__ void load_q_operand_rows(half8_t (&qop)[HEAD_DIM / 32
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ half8_t k_operand(const BlockRegs<HEAD_DIM, KV>& r, int jj)
 {
-    if constexpr (KV == COOPT_KV_E4M3) {
+    if constexpr (kIsFp8<KV>) {
         const u32x4 w = r.k[jj >> 1];
-        return (jj & 1) ? e4m3x8_to_half8(w.z, w.w) : e4m3x8_to_half8(w.x, w.y);
+        return (jj & 1) ? fp8x8_to_half8<KV>(w.z, w.w) : fp8x8_to_half8<KV>(w.x, w.y);
     } else {
         return __builtin_bit_cast(half8_t, r.k[jj]);
     }
@@ -238,8 +242,8 @@ __device__ __forceinline__ half8_t k_operand(const BlockRegs<HEAD_DIM, KV>& r, i
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ half4_t v_operand(const BlockRegs<HEAD_DIM, KV>& r, int c)
 {
-    if constexpr (KV == COOPT_KV_E4M3) {
-        return e4m3x4_to_half4(r.v[c >> 2][c & 3]);
+    if constexpr (kIsFp8<KV>) {
+        return fp8x4_to_half4<KV>(r.v[c >> 2][c & 3]);
     } else {
         const u32x4 w = r.v[c >> 1];
         const uint2 h = (c & 1) ? uint2{w.z, w.w} : uint2{w.x, w.y};
@@ -254,7 +258,7 @@ __device__ __forceinline__ void token_masks(int cache_valid, uint32_t& m0, uint3
     m0 = 0xffffffffu;
     m1 = 0xffffffffu;
     if (cache_valid < 4) {
-        if constexpr (KV == COOPT_KV_E4M3) {
+        if constexpr (kIsFp8<KV>) {
             m0 = cache_valid <= 0 ? 0u : (0xffffffffu >> (8 * (4 - cache_valid)));
         } else {
             m0 = cache_valid <= 0 ? 0u : (cache_valid == 1 ? 0x0000ffffu : 0xffffffffu);
@@ -289,7 +293,7 @@ __device__ __forceinline__ void group_scores(BlockRegs<HEAD_DIM, KV>& A, BlockRe
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if constexpr (KV == COOPT_KV_E4M3) {
+        if constexpr (kIsFp8<KV>) {
             z[i] = sA[i] * (A.ks[i] * scale_log2e);
             z[4 + i] = sB[i] * (B.ks[i] * scale_log2e);
         } else {
@@ -303,7 +307,7 @@ __device__ __forceinline__ void group_scores(BlockRegs<HEAD_DIM, KV>& A, BlockRe
             z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);          // min drops a NaN score
             z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
         }
-        if constexpr (KV == COOPT_KV_E4M3) {
+        if constexpr (kIsFp8<KV>) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {                 // a stale scale times a zero weight
                 A.vs[i] = (i < cacheA) ? A.vs[i] : 0.0f;
@@ -315,7 +319,7 @@ __device__ __forceinline__ void group_scores(BlockRegs<HEAD_DIM, KV>& A, BlockRe
         token_masks<KV>(cacheB, b0, b1);
 #pragma unroll
         for (int j = 0; j < BlockRegs<HEAD_DIM, KV>::NL; ++j) {
-            if constexpr (KV == COOPT_KV_E4M3) {
+            if constexpr (kIsFp8<KV>) {
                 A.v[j] &= a0;
                 B.v[j] &= b0;
             } else {
@@ -356,7 +360,7 @@ __device__ __forceinline__ void group_pv(const BlockRegs<HEAD_DIM, KV>& A,
                                          const BlockRegs<HEAD_DIM, KV>& B, float (&p)[8],
                                          floatx4 (&acc)[HEAD_DIM / 16])
 {
-    if constexpr (KV == COOPT_KV_E4M3) {
+    if constexpr (kIsFp8<KV>) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             p[i] *= A.vs[i];
@@ -379,7 +383,7 @@ __device__ __forceinline__ void group_pv(const BlockRegs<HEAD_DIM, KV>& A,
 // tail / vis / cache arguments as in group_scores.
 //   m: reference max of column n in log2 units (within kRescaleSlack of the true running max),
 //      identical in the four lanes (n, 0..3).
-//   l: this lane's share of the running sum, acc[c][r] = O^T[16c + 4grp + r][n], both times 2^kPShift.
+//   l: this lane's share of the running sum, acc[c][r] = O^T[16c + 4grp + r][n], both times 2^kPShiftOf<KV>.
 // Requirement: whenever m is still -inf, the group holds a token visible to column n.
 template <int HEAD_DIM, int KV>
 __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRegs<HEAD_DIM, KV>& B,
@@ -401,7 +405,7 @@ __device__ __forceinline__ void group_update(BlockRegs<HEAD_DIM, KV>& A, BlockRe
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
         m = nm;
     }
-    const float mm = m - kPShift;
+    const float mm = m - kPShiftOf<KV>;
     float p[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -434,7 +438,7 @@ __device__ __forceinline__ void group_update_block_reduce(
     const float nm = fmaxf(m, fmaxf(fmaxf(red[n], red[16 + n]), fmaxf(red[32 + n], red[48 + n])));
     const float alpha = __builtin_amdgcn_exp2f(m - nm);       // m = -inf at the start gives 0
     m = nm;
-    const float mm = m - kPShift;
+    const float mm = m - kPShiftOf<KV>;
     float p[8], ps = 0.0f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {

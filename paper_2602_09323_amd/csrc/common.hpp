@@ -19,6 +19,14 @@ constexpr int kBlock = 16;          // tokens per cache block (the only supporte
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kE4M3Max = 448.0f;
+constexpr float kE5M2Max = 57344.0f;
+
+// One-byte floating-point caches (OCP E4M3 or E5M2 codes with binary32 scales) against fp16 ones.
+template <int KV>
+inline constexpr bool kIsFp8 = KV != COOPT_KV_FP16;
+// Largest finite value of the cache's code: what a row's absmax is mapped to.
+template <int KV>
+inline constexpr float kFp8Max = KV == COOPT_KV_E5M2 ? kE5M2Max : kE4M3Max;
 
 // Element index of (token, dim) inside one cache tile; ES = bytes per element, E = elements per
 // 16 bytes.  K tiles are [d/E chunks][16 tokens][E]; V tiles are [d/(4E)][4][16][E/4][4 tokens].
@@ -51,7 +59,8 @@ inline int check_shape(const coopt_shape* sh)
     if (sh->max_blocks_per_seq > (1 << 24)) return COOPT_ERR_SHAPE;
     if ((long long)sh->num_seqs * sh->num_q_heads > (1LL << 27)) return COOPT_ERR_SHAPE;
     if ((long long)sh->num_blocks * sh->num_kv_heads > 0x7fffffffLL) return COOPT_ERR_SHAPE;
-    if (sh->kv_dtype != COOPT_KV_FP16 && sh->kv_dtype != COOPT_KV_E4M3) return COOPT_ERR_SHAPE;
+    if (sh->kv_dtype != COOPT_KV_FP16 && sh->kv_dtype != COOPT_KV_E4M3 && sh->kv_dtype != COOPT_KV_E5M2)
+        return COOPT_ERR_SHAPE;
     return COOPT_OK;
 }
 
@@ -60,26 +69,33 @@ inline int launch_status()
     return hipGetLastError() == hipSuccess ? COOPT_OK : COOPT_ERR_LAUNCH;
 }
 
-// Two E4M3 codes (bytes 0,1 or 2,3 of w) -> two fp16, exact (every E4M3 value is an fp16 value).
-template <bool HI>
-__device__ __forceinline__ half2_t e4m3x2_to_half2(uint32_t w)
+// Two one-byte codes (bytes 0,1 or 2,3 of w) -> two fp16, exact: every E4M3 value is an fp16
+// value (the gfx950 convert does it), and an E5M2 code IS the high byte of the fp16 pattern of
+// its value (a byte shuffle does it; infinities and NaN codes map to fp16's own).
+template <int KV, bool HI>
+__device__ __forceinline__ half2_t fp8x2_to_half2(uint32_t w)
 {
-    return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w, 1.0f, HI);
+    if constexpr (KV == COOPT_KV_E5M2)
+        return __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(0u, w, HI ? 0x030c020cu : 0x010c000cu));
+    else
+        return __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((int)w, 1.0f, HI);
 }
 
-__device__ __forceinline__ half4_t e4m3x4_to_half4(uint32_t w)
+template <int KV>
+__device__ __forceinline__ half4_t fp8x4_to_half4(uint32_t w)
 {
-    half2_t lo = e4m3x2_to_half2<false>(w);
-    half2_t hi = e4m3x2_to_half2<true>(w);
+    half2_t lo = fp8x2_to_half2<KV, false>(w);
+    half2_t hi = fp8x2_to_half2<KV, true>(w);
     return half4_t{lo.x, lo.y, hi.x, hi.y};
 }
 
-__device__ __forceinline__ half8_t e4m3x8_to_half8(uint32_t w0, uint32_t w1)
+template <int KV>
+__device__ __forceinline__ half8_t fp8x8_to_half8(uint32_t w0, uint32_t w1)
 {
-    half2_t a = e4m3x2_to_half2<false>(w0);
-    half2_t b = e4m3x2_to_half2<true>(w0);
-    half2_t c = e4m3x2_to_half2<false>(w1);
-    half2_t d = e4m3x2_to_half2<true>(w1);
+    half2_t a = fp8x2_to_half2<KV, false>(w0);
+    half2_t b = fp8x2_to_half2<KV, true>(w0);
+    half2_t c = fp8x2_to_half2<KV, false>(w1);
+    half2_t d = fp8x2_to_half2<KV, true>(w1);
     return half8_t{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
 

@@ -176,7 +176,7 @@ paged_decode_kernel(const DecodeArgs a)
             a.tmp_out[(row * a.max_parts + part) * HEAD_DIM + dim] = o;
             if (dim == 0) {
                 a.max_logits[row * a.max_parts + part] = M * kLn2;
-                a.exp_sums[row * a.max_parts + part] = L * kPUnshift;
+                a.exp_sums[row * a.max_parts + part] = L * kPUnshiftOf<KV>;
             }
         }
     }
@@ -305,6 +305,9 @@ static void launch_decode(const DecodeArgs& a, const coopt_shape* sh, int waves,
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) launch_decode_pool<128, COOPT_KV_E4M3>(a, big, depth, grid, block, lds, stream);
         else launch_decode_pool<64, COOPT_KV_E4M3>(a, big, depth, grid, block, lds, stream);
+    } else if (sh->kv_dtype == COOPT_KV_E5M2) {
+        if (sh->head_dim == 128) launch_decode_pool<128, COOPT_KV_E5M2>(a, big, depth, grid, block, lds, stream);
+        else launch_decode_pool<64, COOPT_KV_E5M2>(a, big, depth, grid, block, lds, stream);
     } else {
         if (sh->head_dim == 128) launch_decode_pool<128, COOPT_KV_FP16>(a, big, depth, grid, block, lds, stream);
         else launch_decode_pool<64, COOPT_KV_FP16>(a, big, depth, grid, block, lds, stream);
@@ -352,7 +355,7 @@ static int check_decode_ptrs(const void* q, const void* k_cache, const void* v_c
                              const int32_t* cl, const coopt_shape* sh)
 {
     if (!q || !k_cache || !v_cache || !bt || !cl) return COOPT_ERR_NULL;
-    if (sh->kv_dtype == COOPT_KV_E4M3 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
+    if (sh->kv_dtype != COOPT_KV_FP16 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
     return COOPT_OK;
 }
 

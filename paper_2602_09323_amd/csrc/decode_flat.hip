@@ -180,7 +180,7 @@ struct FlatArgs {
     int32_t decode_wgs;   // workgroups (= wavefronts) of the attention launch
     int32_t append_wgs;   // fused step: workgroups at the head of the merge launch's grid whose
                           // wavefronts store one new row each (0 otherwise)
-    int32_t kv_e4m3;      // cache type, for the merge launch's row stores
+    int32_t kv_dtype;     // cache type, for the merge launch's row stores
     uint32_t ws_tag;      // names the plan the workspace's partials were laid out for (see ws_tag_of)
     float scale_log2e;
     // fused step only (new_slots != NULL): the token every sequence appends, and the cache as
@@ -534,7 +534,7 @@ __device__ __forceinline__ void patch_token(BlockRegs<HEAD_DIM, KV>& A, BlockReg
         A.v[j] = (A.v[j] & ~ma) | (val & ma);
         B.v[j] = (B.v[j] & ~mb) | (val & mb);
     }
-    if constexpr (KV == COOPT_KV_E4M3) {
+    if constexpr (kIsFp8<KV>) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const bool mine = v_lane && i == (off & 3);
@@ -558,14 +558,14 @@ __device__ __forceinline__ void take_new_token(BlockRegs<HEAD_DIM, KV>& A, Block
     constexpr int ES = BlockRegs<HEAD_DIM, KV>::ES;
     uint32_t ck = row_k, cv = row_v;                    // the row's cache elements of this lane
     float ks = 1.0f, vs = 1.0f;
-    if constexpr (KV == COOPT_KV_E4M3) {
+    if constexpr (kIsFp8<KV>) {
         float kx[E], vx[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             kx[e] = (float)__builtin_bit_cast(half_t, (uint16_t)(row_k >> (16 * e)));
             vx[e] = (float)__builtin_bit_cast(half_t, (uint16_t)(row_v >> (16 * e)));
         }
-        const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM>(kx, vx);
+        const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM, KV>(kx, vx);
         ck = qr.k_codes;
         cv = qr.v_codes;
         ks = qr.k_scale;
@@ -595,7 +595,7 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
     // vector-memory loads per group: two blocks of K and V chunks plus, for FP8, their scales;
     // in the fused step also the two new rows (requested with every group, empty where the group
     // appends nothing, so that the count is the same on every path)
-    constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (KV == COOPT_KV_E4M3 ? 2 : 0)) +
+    constexpr int kGroupLoads = 2 * (2 * BlockRegs<HEAD_DIM, KV>::NL + (kIsFp8<KV> ? 2 : 0)) +
                                 (APPEND ? 2 : 0);
     // s_waitcnt immediates (gfx9 layout: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
     constexpr int kWaitStaged = (kGroupLoads & 15) | (7 << 4) | (15 << 8) | ((kGroupLoads >> 4) << 14);
@@ -699,7 +699,7 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                             // end of the share: nothing runs behind these stores
 #pragma unroll
                             for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= inv;
-                            store_partial<HEAD_DIM>(a, ps, acc, m * kLn2, l * kPUnshift, lane);
+                            store_partial<HEAD_DIM>(a, ps, acc, m * kLn2, l * kPUnshiftOf<KV>, lane);
                             if (parked.row0 >= 0) store_parked<HEAD_DIM>(a, parked, park, lane);
                         } else {
                             // Mid-stream: vector-memory stores here would sit between the tile
@@ -710,7 +710,7 @@ __device__ __forceinline__ void stream_share(const FlatArgs& a, Source& src, uns
                             for (int c = 0; c < HEAD_DIM / 16; ++c)
                                 *reinterpret_cast<floatx4*>(park + 16 * (64 * c + lane)) = acc[c] * inv;
                             *reinterpret_cast<float*>(park + kParkAcc + 4 * lane) = m * kLn2;
-                            *reinterpret_cast<float*>(park + kParkAcc + 256 + 4 * lane) = l * kPUnshift;
+                            *reinterpret_cast<float*>(park + kParkAcc + 256 + 4 * lane) = l * kPUnshiftOf<KV>;
                             parked = ps;
                             m = -INFINITY;
                             l = 0.0f;
@@ -874,15 +874,19 @@ __device__ __forceinline__ void append_new_row(const FlatArgs& a, int pair, int 
     const int64_t blk = slot / kBlock;
     const int off = (int)(slot - blk * kBlock);
     const size_t tile = (size_t)(blk * a.H_k + g);
-    if (a.kv_e4m3) {
+    if (a.kv_dtype != COOPT_KV_FP16) {
         float kx[E], vx[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             kx[e] = (float)__builtin_bit_cast(half_t, kb[e]);
             vx[e] = (float)__builtin_bit_cast(half_t, vb[e]);
         }
-        quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, a.k_cache_w, a.v_cache_w,
-                                           a.k_scale_w, a.v_scale_w);
+        if (a.kv_dtype == COOPT_KV_E5M2)
+            quantise_values_to_cache<HEAD_DIM, COOPT_KV_E5M2>(kx, vx, tile, off, lane, a.k_cache_w,
+                                                              a.v_cache_w, a.k_scale_w, a.v_scale_w);
+        else
+            quantise_values_to_cache<HEAD_DIM, COOPT_KV_E4M3>(kx, vx, tile, off, lane, a.k_cache_w,
+                                                              a.v_cache_w, a.k_scale_w, a.v_scale_w);
     } else {
         uint16_t* kc = reinterpret_cast<uint16_t*>(a.k_cache_w) + tile * (kBlock * HEAD_DIM);
         uint16_t* vc = reinterpret_cast<uint16_t*>(a.v_cache_w) + tile * (kBlock * HEAD_DIM);
@@ -1254,6 +1258,9 @@ int launch_flat_split(const void* q, const void* k_cache, const void* v_cache, c
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E4M3>(a, big, plan, grid, stream);
         else launch_flat_pool<64, COOPT_KV_E4M3>(a, big, plan, grid, stream);
+    } else if (sh->kv_dtype == COOPT_KV_E5M2) {
+        if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_E5M2>(a, big, plan, grid, stream);
+        else launch_flat_pool<64, COOPT_KV_E5M2>(a, big, plan, grid, stream);
     } else {
         if (sh->head_dim == 128) launch_flat_pool<128, COOPT_KV_FP16>(a, big, plan, grid, stream);
         else launch_flat_pool<64, COOPT_KV_FP16>(a, big, plan, grid, stream);
@@ -1284,7 +1291,7 @@ int launch_flat_merge(const int32_t* context_lens, void* workspace, void* out, c
         a.v_cache_w = (uint8_t*)cache->v_cache;
         a.k_scale_w = cache->k_scale;
         a.v_scale_w = cache->v_scale;
-        a.kv_e4m3 = sh->kv_dtype == COOPT_KV_E4M3;
+        a.kv_dtype = sh->kv_dtype;
         a.append_wgs = (int32_t)(((long long)sh->num_seqs * sh->num_kv_heads + 3) / 4);
         wgs += a.append_wgs;
     }

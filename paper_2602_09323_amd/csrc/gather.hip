@@ -29,13 +29,22 @@ __device__ __forceinline__ float mul_round_to_odd(float c, float s)
     return __builtin_bit_cast(float, u);
 }
 
-// 8 E4M3 codes (two dwords) times one scale -> 8 fp16
+// 8 one-byte codes (two dwords; E4M3 or E5M2) times one scale -> 8 fp16
+template <int KV>
 __device__ __forceinline__ half8_t dequant8(uint32_t w0, uint32_t w1, float scale)
 {
-    const floatx2 c[4] = {__builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false),
-                          __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true),
-                          __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false),
-                          __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true)};
+    floatx2 c[4];
+    if constexpr (KV == COOPT_KV_E5M2) {
+        c[0] = __builtin_amdgcn_cvt_pk_f32_bf8((int)w0, false);
+        c[1] = __builtin_amdgcn_cvt_pk_f32_bf8((int)w0, true);
+        c[2] = __builtin_amdgcn_cvt_pk_f32_bf8((int)w1, false);
+        c[3] = __builtin_amdgcn_cvt_pk_f32_bf8((int)w1, true);
+    } else {
+        c[0] = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false);
+        c[1] = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+        c[2] = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false);
+        c[3] = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+    }
     half8_t r;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -55,7 +64,7 @@ gather_cached_kv_kernel(const uint8_t* __restrict__ k_cache, const uint8_t* __re
                         int first_block, int num_tiles, int H_k,
                         half_t* __restrict__ k_out, half_t* __restrict__ v_out)
 {
-    constexpr bool FP8 = KV == COOPT_KV_E4M3;
+    constexpr bool FP8 = kIsFp8<KV>;
     constexpr int ES = FP8 ? 1 : 2;                    // bytes per cache element
     constexpr int UPR = HEAD_DIM / 8;                  // 16-byte output units per row
     constexpr int NU = kBlock * UPR / 64;              // units per lane and tile
@@ -131,8 +140,8 @@ gather_cached_kv_kernel(const uint8_t* __restrict__ k_cache, const uint8_t* __re
         half8_t kh, vh;
         if constexpr (FP8) {
             const gu32x2 w = *reinterpret_cast<const gu32x2*>(my + tok * RS + piece * 8);
-            kh = dequant8(ku[i].x, ku[i].y, ks[i]);
-            vh = dequant8(w.x, w.y, vs[i]);
+            kh = dequant8<KV>(ku[i].x, ku[i].y, ks[i]);
+            vh = dequant8<KV>(w.x, w.y, vs[i]);
         } else {
             kh = __builtin_bit_cast(half8_t, ku[i]);
             vh = *reinterpret_cast<const half8_t*>(my + tok * RS + piece * 16);
@@ -160,7 +169,7 @@ extern "C" int coopt_gather_cached_kv(const void* k_cache, const void* v_cache, 
     if ((long long)tok_end > (long long)sh->max_blocks_per_seq * kBlock) return COOPT_ERR_SHAPE;
     if (tok_end == tok_begin) return COOPT_OK;
     if (!k_cache || !v_cache || !block_tables || !k_out || !v_out) return COOPT_ERR_NULL;
-    if (sh->kv_dtype == COOPT_KV_E4M3 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
+    if (sh->kv_dtype != COOPT_KV_FP16 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
     const int first_block = tok_begin / kBlock;
     const long long tiles = (long long)((tok_end + kBlock - 1) / kBlock - first_block) * sh->num_kv_heads;
     if (tiles > 0x7fffffffLL) return COOPT_ERR_SHAPE;
@@ -175,6 +184,9 @@ extern "C" int coopt_gather_cached_kv(const void* k_cache, const void* v_cache, 
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) COOPT_GATHER(128, COOPT_KV_E4M3);
         else COOPT_GATHER(64, COOPT_KV_E4M3);
+    } else if (sh->kv_dtype == COOPT_KV_E5M2) {
+        if (sh->head_dim == 128) COOPT_GATHER(128, COOPT_KV_E5M2);
+        else COOPT_GATHER(64, COOPT_KV_E5M2);
     } else {
         if (sh->head_dim == 128) COOPT_GATHER(128, COOPT_KV_FP16);
         else COOPT_GATHER(64, COOPT_KV_FP16);

@@ -1,6 +1,7 @@
 // Quantise-on-write of one (token, KV head) row by one wavefront (Opt-KV: Eq. 5, Alg. 1 phase 1):
-// dynamic per-row scale amax/448, OCP E4M3 codes, both tiles stored in matrix-core operand order.
-// Shared by the cache-write kernel and the fused decode step.
+// a scale (by default the row's own, amax / the code's largest value), OCP E4M3 or E5M2 codes,
+// both tiles stored in matrix-core operand order.  Shared by the cache-write kernels and the fused
+// decode step.  KV names the code: COOPT_KV_E4M3 (max 448) or COOPT_KV_E5M2 (max 57344).
 #pragma once
 
 #include <type_traits>
@@ -28,29 +29,53 @@ __device__ __forceinline__ float wave_max(float a)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(v, 63));
 }
 
-// Dynamic per-row scale and the scaled, clamped values (binary32, correctly rounded divisions so
-// that the stored bytes are defined bit for bit).
+// The row's absmax over the wavefront's lanes.
 template <int E>
-__device__ __forceinline__ float scale_row(const float (&x)[E], float (&y)[E])
+__device__ __forceinline__ float row_absmax(const float (&x)[E])
 {
     float amax = 0.0f;
 #pragma unroll
     for (int e = 0; e < E; ++e) amax = fmaxf(amax, fabsf(x[e]));
-    amax = wave_max(amax);
-    const float scale = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kE4M3Max);
+    return wave_max(amax);
+}
+
+// The scale that maps absmax `amax` to the code's largest value (binary32, correctly rounded
+// division so that the stored scale is defined bit for bit; an all-zero row gets 1).
+template <int KV>
+__device__ __forceinline__ float scale_of_absmax(float amax)
+{
+    return (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kFp8Max<KV>);
+}
+
+// The scaled, clamped values under `scale` (correctly rounded division again).
+template <int KV, int E>
+__device__ __forceinline__ void scale_values(const float (&x)[E], float scale, float (&y)[E])
+{
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         float q = __fdiv_rn(x[e], scale);
-        y[e] = fminf(fmaxf(q, -kE4M3Max), kE4M3Max);
+        y[e] = fminf(fmaxf(q, -kFp8Max<KV>), kFp8Max<KV>);
     }
+}
+
+// Dynamic per-row scale and the scaled, clamped values.
+template <int KV, int E>
+__device__ __forceinline__ float scale_row(const float (&x)[E], float (&y)[E])
+{
+    const float scale = scale_of_absmax<KV>(row_absmax<E>(x));
+    scale_values<KV, E>(x, scale, y);
     return scale;
 }
 
-// binary32 -> OCP E4M3 by the gfx950 convert (round to nearest even; inputs are already in
-// [-448, 448], so the instruction's overflow behaviour never comes into play).
+// binary32 -> OCP E4M3 / E5M2 by the gfx950 converts (round to nearest even; inputs are already
+// inside the code's finite range, so the instructions' overflow behaviour never comes into play).
+template <int KV>
 __device__ __forceinline__ uint32_t encode_pair(float a, float b)
 {
-    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
+    if constexpr (KV == COOPT_KV_E5M2)
+        return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, 0, false) & 0xffffu;
+    else
+        return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
 }
 
 // The row's codes and scales.  Lane i holds elements i*E .. i*E+E-1 (E = HEAD_DIM/64).
@@ -63,19 +88,24 @@ struct QuantRow {
 
 // Quantises one K row and one V row (HEAD_DIM values each, lane i holding elements i*E .. i*E+E-1
 // as binary32): the rows' scales and codes, nothing stored.
-template <int HEAD_DIM>
+// k_given / v_given > 0: the scales to use (a static or a block's scale) instead of the rows' own.
+template <int HEAD_DIM, int KV>
 __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_values(const float (&kx)[HEAD_DIM / 64],
-                                                              const float (&vx)[HEAD_DIM / 64])
+                                                              const float (&vx)[HEAD_DIM / 64],
+                                                              float k_given = 0.0f,
+                                                              float v_given = 0.0f)
 {
     constexpr int E = HEAD_DIM / 64;
     QuantRow<HEAD_DIM> qr;
     float y[E];
-    qr.k_scale = scale_row<E>(kx, y);
-    if constexpr (E == 2) qr.k_codes = encode_pair(y[0], y[1]);
-    else qr.k_codes = encode_pair(y[0], 0.0f) & 0xffu;
-    qr.v_scale = scale_row<E>(vx, y);
-    if constexpr (E == 2) qr.v_codes = encode_pair(y[0], y[1]);
-    else qr.v_codes = encode_pair(y[0], 0.0f) & 0xffu;
+    qr.k_scale = k_given > 0.0f ? k_given : scale_of_absmax<KV>(row_absmax<E>(kx));
+    scale_values<KV, E>(kx, qr.k_scale, y);
+    if constexpr (E == 2) qr.k_codes = encode_pair<KV>(y[0], y[1]);
+    else qr.k_codes = encode_pair<KV>(y[0], 0.0f) & 0xffu;
+    qr.v_scale = v_given > 0.0f ? v_given : scale_of_absmax<KV>(row_absmax<E>(vx));
+    scale_values<KV, E>(vx, qr.v_scale, y);
+    if constexpr (E == 2) qr.v_codes = encode_pair<KV>(y[0], y[1]);
+    else qr.v_codes = encode_pair<KV>(y[0], 0.0f) & 0xffu;
     return qr;
 }
 
@@ -105,13 +135,13 @@ __device__ __forceinline__ void store_quant_row(const QuantRow<HEAD_DIM>& qr, si
 }
 
 // Both: quantises the rows and stores codes and scales.  Returns what it stored.
-template <int HEAD_DIM>
+template <int HEAD_DIM, int KV>
 __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_values_to_cache(
     const float (&kx)[HEAD_DIM / 64], const float (&vx)[HEAD_DIM / 64], size_t tile, int off, int lane,
     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache, float* __restrict__ k_scale,
-    float* __restrict__ v_scale)
+    float* __restrict__ v_scale, float k_given = 0.0f, float v_given = 0.0f)
 {
-    const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM>(kx, vx);
+    const QuantRow<HEAD_DIM> qr = quantise_values<HEAD_DIM, KV>(kx, vx, k_given, v_given);
     store_quant_row<HEAD_DIM>(qr, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
     return qr;
 }
@@ -127,7 +157,7 @@ __device__ __forceinline__ void load_row_values(const half_t* __restrict__ row, 
 }
 
 // The same from the rows in memory (HEAD_DIM fp16 values each).
-template <int HEAD_DIM>
+template <int HEAD_DIM, int KV>
 __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
     const half_t* __restrict__ k_row, const half_t* __restrict__ v_row, size_t tile, int off, int lane,
     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache, float* __restrict__ k_scale,
@@ -136,7 +166,7 @@ __device__ __forceinline__ QuantRow<HEAD_DIM> quantise_row_to_cache(
     float kx[HEAD_DIM / 64], vx[HEAD_DIM / 64];
     load_row_values<HEAD_DIM>(k_row, lane, kx);
     load_row_values<HEAD_DIM>(v_row, lane, vx);
-    return quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
+    return quantise_values_to_cache<HEAD_DIM, KV>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
 }
 
 }  // namespace coopt

@@ -17,20 +17,27 @@ __device__ __forceinline__ bool in_skip_set(const uint32_t* skip_set, int tok)
     return skip_set != nullptr && ((skip_set[tok >> 5] >> (tok & 31)) & 1u);
 }
 
-template <int HEAD_DIM>
+// scale_mode (see coopt_kv_cache_write_fp8_scaled): COOPT_SCALE_TOKEN = every row's own scale;
+// COOPT_SCALE_STATIC = k_static[head] / v_static[head]; COOPT_SCALE_BLOCK = one scale for all rows
+// of this call that land in the row's cache block (the largest of their absmaxes): the wavefront
+// scans the call's slots for the others and takes their rows' absmax itself (every row of a block
+// does the same scan -- this is the comparison scheme, not the method's).
+template <int HEAD_DIM, int KV>
 __global__ void __launch_bounds__(256)
 kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
                     const int64_t* __restrict__ slot_mapping,
                     const uint32_t* __restrict__ skip_set, int num_rows, int H_k,
                     uint8_t* __restrict__ k_cache, uint8_t* __restrict__ v_cache,
-                    float* __restrict__ k_scale, float* __restrict__ v_scale)
+                    float* __restrict__ k_scale, float* __restrict__ v_scale, int scale_mode,
+                    const float* __restrict__ k_static, const float* __restrict__ v_static)
 {
+    constexpr int E = HEAD_DIM / 64;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);        // token * H_k + head
     if (row >= num_rows) return;
     const int tok = row / H_k, head = row - tok * H_k;
     const int lane = threadIdx.x & 63;
     // the rows are asked for together with the slot, not after it: one memory round trip
-    float kx[HEAD_DIM / 64], vx[HEAD_DIM / 64];
+    float kx[E], vx[E];
     load_row_values<HEAD_DIM>(k + (size_t)row * HEAD_DIM, lane, kx);
     load_row_values<HEAD_DIM>(v + (size_t)row * HEAD_DIM, lane, vx);
     const int64_t slot = slot_mapping[tok];
@@ -39,7 +46,36 @@ kv_write_fp8_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
     const int64_t blk = slot / kBlock;
     const int off = (int)(slot - blk * kBlock);
     const size_t tile = (size_t)(blk * H_k + head);
-    quantise_values_to_cache<HEAD_DIM>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale);
+    float k_given = 0.0f, v_given = 0.0f;                       // 0: the row's own scale
+    if (scale_mode == COOPT_SCALE_STATIC) {
+        k_given = k_static[head];
+        v_given = v_static[head];
+    } else if (scale_mode == COOPT_SCALE_BLOCK) {
+        float ka = row_absmax<E>(kx), va = row_absmax<E>(vx);
+        const int num_tokens = num_rows / H_k;
+        for (int base = 0; base < num_tokens; base += 64) {
+            const int t2 = base + lane;
+            bool same = false;
+            if (t2 < num_tokens && t2 != tok) {
+                const int64_t s2 = slot_mapping[t2];
+                same = s2 >= 0 && s2 / kBlock == blk && !in_skip_set(skip_set, t2);
+            }
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(same);
+            while (todo) {                                      // wave-uniform
+                const int other = base + __builtin_ctzll(todo);
+                todo &= todo - 1;
+                float k2[E], v2[E];
+                load_row_values<HEAD_DIM>(k + ((size_t)other * H_k + head) * HEAD_DIM, lane, k2);
+                load_row_values<HEAD_DIM>(v + ((size_t)other * H_k + head) * HEAD_DIM, lane, v2);
+                ka = fmaxf(ka, row_absmax<E>(k2));
+                va = fmaxf(va, row_absmax<E>(v2));
+            }
+        }
+        k_given = scale_of_absmax<KV>(ka);
+        v_given = scale_of_absmax<KV>(va);
+    }
+    quantise_values_to_cache<HEAD_DIM, KV>(kx, vx, tile, off, lane, k_cache, v_cache, k_scale, v_scale,
+                                           k_given, v_given);
 }
 
 // ---- bulk form (prefill chunks, cache fills): many tokens per call.
@@ -65,8 +101,8 @@ __device__ __forceinline__ float group_max(float a)
 
 typedef unsigned int wu32x4 __attribute__((ext_vector_type(4)));
 
-// 16 fp16 values (two 16-byte words) -> their group's scale and 16 E4M3 codes, element e in byte e
-template <int CH>
+// 16 fp16 values (two 16-byte words) -> their group's scale and 16 one-byte codes, element e in byte e
+template <int CH, int KV>
 __device__ __forceinline__ wu32x4 quantise_chunk(wu32x4 lo, wu32x4 hi, float& scale)
 {
     float x[16];
@@ -84,22 +120,28 @@ __device__ __forceinline__ wu32x4 quantise_chunk(wu32x4 lo, wu32x4 hi, float& sc
 #pragma unroll
     for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(x[e]));
     amax = group_max<CH>(amax);
-    scale = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, kE4M3Max);
+    scale = scale_of_absmax<KV>(amax);
     wu32x4 codes;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         float y[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            y[e] = fminf(fmaxf(__fdiv_rn(x[4 * d + e], scale), -kE4M3Max), kE4M3Max);
-        int w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w, true);
+            y[e] = fminf(fmaxf(__fdiv_rn(x[4 * d + e], scale), -kFp8Max<KV>), kFp8Max<KV>);
+        int w;
+        if constexpr (KV == COOPT_KV_E5M2) {
+            w = __builtin_amdgcn_cvt_pk_bf8_f32(y[0], y[1], 0, false);
+            w = __builtin_amdgcn_cvt_pk_bf8_f32(y[2], y[3], w, true);
+        } else {
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w, true);
+        }
         codes[d] = (uint32_t)w;
     }
     return codes;
 }
 
-template <int HEAD_DIM>
+template <int HEAD_DIM, int KV>
 __global__ void __launch_bounds__(256)
 kv_write_fp8_bulk_kernel(const half_t* __restrict__ k, const half_t* __restrict__ v,
                          const int64_t* __restrict__ slot_mapping,
@@ -137,8 +179,8 @@ kv_write_fp8_bulk_kernel(const half_t* __restrict__ k, const half_t* __restrict_
     const wu32x4 k_lo = kp[0], k_hi = kp[1], v_lo = vp[0], v_hi = vp[1];
 
     float ks, vs;
-    const wu32x4 kc = quantise_chunk<CH>(k_lo, k_hi, ks);
-    const wu32x4 vc = quantise_chunk<CH>(v_lo, v_hi, vs);
+    const wu32x4 kc = quantise_chunk<CH, KV>(k_lo, k_hi, ks);
+    const wu32x4 vc = quantise_chunk<CH, KV>(v_lo, v_hi, vs);
 
     uint8_t* ktile = k_cache + tile * (kBlock * HEAD_DIM);
     uint8_t* vtile = v_cache + tile * (kBlock * HEAD_DIM);
@@ -304,45 +346,63 @@ using namespace coopt;
 // From this many tokens per call on, the bulk kernel (a call of a decode step has one per sequence).
 constexpr int kBulkWriteTokens = 64;
 
+template <int HEAD_DIM, int KV>
+static void launch_write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
+                             const uint32_t* skip_set, int32_t num_tokens, uint8_t* k_cache,
+                             uint8_t* v_cache, float* k_scale, float* v_scale, int scale_mode,
+                             const float* k_static, const float* v_static, int H_k,
+                             hipStream_t stream)
+{
+    const dim3 block(256);
+    if (num_tokens >= kBulkWriteTokens && scale_mode == COOPT_SCALE_TOKEN) {
+        // 64 / (d/16) consecutive tokens of one head per wavefront
+        constexpr int per_wave = 64 / (HEAD_DIM / 16);
+        const long long units = (long long)((num_tokens + per_wave - 1) / per_wave) * H_k;
+        const dim3 grid((unsigned)((units + 3) / 4));
+        hipLaunchKernelGGL((kv_write_fp8_bulk_kernel<HEAD_DIM, KV>), grid, block, 0, stream,
+                           (const half_t*)k, (const half_t*)v, slot_mapping, skip_set, num_tokens, H_k,
+                           k_cache, v_cache, k_scale, v_scale);
+        return;
+    }
+    const long long rows = (long long)num_tokens * H_k;
+    const dim3 grid((unsigned)((rows + 3) / 4));
+    hipLaunchKernelGGL((kv_write_fp8_kernel<HEAD_DIM, KV>), grid, block, 0, stream, (const half_t*)k,
+                       (const half_t*)v, slot_mapping, skip_set, (int)rows, H_k, k_cache, v_cache,
+                       k_scale, v_scale, scale_mode, k_static, v_static);
+}
+
 static int write_fp8(const void* k, const void* v, const int64_t* slot_mapping,
                      const uint32_t* skip_set, int32_t num_tokens, uint8_t* k_cache,
-                     uint8_t* v_cache, float* k_scale, float* v_scale, const coopt_shape* shape,
+                     uint8_t* v_cache, float* k_scale, float* v_scale, int scale_mode,
+                     const float* k_static, const float* v_static, const coopt_shape* shape,
                      void* hip_stream)
 {
     int st = check_shape(shape);
     if (st != COOPT_OK) return st;
-    if (shape->kv_dtype != COOPT_KV_E4M3 || num_tokens < 0) return COOPT_ERR_SHAPE;
+    if ((shape->kv_dtype != COOPT_KV_E4M3 && shape->kv_dtype != COOPT_KV_E5M2) || num_tokens < 0)
+        return COOPT_ERR_SHAPE;
+    if (scale_mode != COOPT_SCALE_TOKEN && scale_mode != COOPT_SCALE_BLOCK &&
+        scale_mode != COOPT_SCALE_STATIC)
+        return COOPT_ERR_SHAPE;
     if (num_tokens == 0) return COOPT_OK;
     if (!k || !v || !slot_mapping || !k_cache || !v_cache || !k_scale || !v_scale)
         return COOPT_ERR_NULL;
+    if (scale_mode == COOPT_SCALE_STATIC && (!k_static || !v_static)) return COOPT_ERR_NULL;
     const long long rows = (long long)num_tokens * shape->num_kv_heads;
     if (rows > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     hipStream_t stream = (hipStream_t)hip_stream;
-    const dim3 block(256);
-    if (num_tokens >= kBulkWriteTokens) {
-        // 64 / (d/16) consecutive tokens of one head per wavefront
-        const int per_wave = shape->head_dim == 128 ? 8 : 16;
-        const long long units = (long long)((num_tokens + per_wave - 1) / per_wave) * shape->num_kv_heads;
-        const dim3 grid((unsigned)((units + 3) / 4));
-        if (shape->head_dim == 128)
-            hipLaunchKernelGGL(kv_write_fp8_bulk_kernel<128>, grid, block, 0, stream, (const half_t*)k,
-                               (const half_t*)v, slot_mapping, skip_set, num_tokens,
-                               shape->num_kv_heads, k_cache, v_cache, k_scale, v_scale);
-        else
-            hipLaunchKernelGGL(kv_write_fp8_bulk_kernel<64>, grid, block, 0, stream, (const half_t*)k,
-                               (const half_t*)v, slot_mapping, skip_set, num_tokens,
-                               shape->num_kv_heads, k_cache, v_cache, k_scale, v_scale);
-        return launch_status();
+    const int H_k = shape->num_kv_heads;
+#define COOPT_WRITE(D, KV)                                                                          \
+    launch_write_fp8<D, KV>(k, v, slot_mapping, skip_set, num_tokens, k_cache, v_cache, k_scale,    \
+                            v_scale, scale_mode, k_static, v_static, H_k, stream)
+    if (shape->kv_dtype == COOPT_KV_E5M2) {
+        if (shape->head_dim == 128) COOPT_WRITE(128, COOPT_KV_E5M2);
+        else COOPT_WRITE(64, COOPT_KV_E5M2);
+    } else {
+        if (shape->head_dim == 128) COOPT_WRITE(128, COOPT_KV_E4M3);
+        else COOPT_WRITE(64, COOPT_KV_E4M3);
     }
-    const dim3 grid((unsigned)((rows + 3) / 4));
-    if (shape->head_dim == 128)
-        hipLaunchKernelGGL(kv_write_fp8_kernel<128>, grid, block, 0, stream, (const half_t*)k,
-                           (const half_t*)v, slot_mapping, skip_set, (int)rows, shape->num_kv_heads,
-                           k_cache, v_cache, k_scale, v_scale);
-    else
-        hipLaunchKernelGGL(kv_write_fp8_kernel<64>, grid, block, 0, stream, (const half_t*)k,
-                           (const half_t*)v, slot_mapping, skip_set, (int)rows, shape->num_kv_heads,
-                           k_cache, v_cache, k_scale, v_scale);
+#undef COOPT_WRITE
     return launch_status();
 }
 
@@ -391,7 +451,18 @@ extern "C" int coopt_kv_cache_write_fp8(const void* k, const void* v, const int6
                                         void* hip_stream)
 {
     return write_fp8(k, v, slot_mapping, nullptr, num_tokens, k_cache, v_cache, k_scale, v_scale,
-                     shape, hip_stream);
+                     COOPT_SCALE_TOKEN, nullptr, nullptr, shape, hip_stream);
+}
+
+extern "C" int coopt_kv_cache_write_fp8_scaled(const void* k, const void* v,
+                                               const int64_t* slot_mapping, int32_t num_tokens,
+                                               uint8_t* k_cache, uint8_t* v_cache, float* k_scale,
+                                               float* v_scale, int32_t scale_mode,
+                                               const float* k_static, const float* v_static,
+                                               const coopt_shape* shape, void* hip_stream)
+{
+    return write_fp8(k, v, slot_mapping, nullptr, num_tokens, k_cache, v_cache, k_scale, v_scale,
+                     scale_mode, k_static, v_static, shape, hip_stream);
 }
 
 extern "C" int coopt_kv_cache_write_fp16(const void* k, const void* v, const int64_t* slot_mapping,
@@ -410,5 +481,5 @@ extern "C" int coopt_kv_cache_write_skipset(const void* k, const void* v,
     if (shape && shape->kv_dtype == COOPT_KV_FP16)
         return write_fp16(k, v, slot_mapping, skip_set, num_tokens, k_cache, v_cache, shape, hip_stream);
     return write_fp8(k, v, slot_mapping, skip_set, num_tokens, (uint8_t*)k_cache, (uint8_t*)v_cache,
-                     k_scale, v_scale, shape, hip_stream);
+                     k_scale, v_scale, COOPT_SCALE_TOKEN, nullptr, nullptr, shape, hip_stream);
 }

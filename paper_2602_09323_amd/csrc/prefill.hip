@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(64 * kPrefillWaves, 2)
 prefill_chunk_kernel(const PrefillArgs a)
 {
     using St = PrefillStage<HEAD_DIM>;
-    constexpr bool FP8 = KV == COOPT_KV_E4M3;
+    constexpr bool FP8 = kIsFp8<KV>;
     constexpr int NL = BlockRegs<HEAD_DIM, KV>::NL;   // 16-byte pieces per lane of a K (or V) tile
     constexpr int NLH = (NL + 1) / 2;                 // V pieces per V wave
     constexpr int NP = NL > 2 * NLH ? NL : 2 * NLH;   // producer registers per wave
@@ -206,6 +206,51 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int nblk = (wg_max + kBlock - 1) / kBlock;
     const int num_groups = (nblk + 1) >> 1;
     const int32_t* bt = a.block_tables + (size_t)seq * a.max_blocks;
+
+    // ---- the pair's largest v_scale as a power of two.  The weights P * v_scale enter the second
+    // product as fp16 (5 exponent bits); value rows can be of any magnitude (an E5M2 cache's scales
+    // are 2^-7 of an E4M3 cache's, small value rows' smaller still), so every v_scale is divided by
+    // the power of two just above the largest one among the tokens this workgroup reads: the
+    // weights of the rows that matter then sit at fp16's upper end whatever the rows' magnitude.
+    // The row sum divides each weight by the same normalised scale, so the factor stays in the
+    // numerator alone and is taken out, exactly, in the final division.  One pass over the pair's
+    // scales (64 bytes per block) before the stream starts.
+    float vnorm = 1.0f, vdenorm = 1.0f;
+    if constexpr (FP8) {
+        __shared__ float vmax_of_wave[kPrefillWaves];
+        float mx = 0.0f;
+        constexpr int kBatch = 8;                          // loads in flight per lane
+        for (int b0 = 0; b0 < nblk; b0 += 4 * kPrefillWaves * kBatch) {
+            int id[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {             // lane group grp takes block b, all 16 tokens
+                const int b = b0 + (u * kPrefillWaves + wave_id) * 4 + grp;
+                id[u] = b < nblk ? bt[b] : -1;
+            }
+            float sc[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int b = b0 + (u * kPrefillWaves + wave_id) * 4 + grp;
+                const bool in = id[u] >= 0 && b * kBlock + n < min(wg_max, t);
+                sc[u] = in ? a.cv.v_scale[((size_t)id[u] * a.H_k + g) * kBlock + n] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) mx = fmaxf(mx, sc[u]);      // (fmaxf drops a NaN)
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        if (lane == 0) vmax_of_wave[wave_id] = mx;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kPrefillWaves; ++i) mx = fmaxf(mx, vmax_of_wave[i]);
+        // mx = f * 2^e with f in [1, 2): vnorm = 2^-(e+1), exact; nothing to normalise if no scale is positive
+        const uint32_t ebits = (__builtin_bit_cast(uint32_t, mx) >> 23) & 0xffu;
+        if (mx > 0.0f && ebits > 0u && ebits < 253u) {
+            vnorm = __builtin_bit_cast(float, (253u - ebits) << 23);
+            vdenorm = __builtin_bit_cast(float, (ebits + 1u) << 23);
+        }
+    }
+
 
     float m[NR];
     floatx4 lacc[NR];       // rows 0 and 1 (lanes of group 0, registers 0 and 1): the row sums / 2^8
@@ -278,8 +323,8 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
                 if constexpr (FP8) {
-                    *reinterpret_cast<half8_t*>(kdst + (2 * j) * 1024) = e4m3x8_to_half8(pr[j].x, pr[j].y);
-                    *reinterpret_cast<half8_t*>(kdst + (2 * j + 1) * 1024) = e4m3x8_to_half8(pr[j].z, pr[j].w);
+                    *reinterpret_cast<half8_t*>(kdst + (2 * j) * 1024) = fp8x8_to_half8<KV>(pr[j].x, pr[j].y);
+                    *reinterpret_cast<half8_t*>(kdst + (2 * j + 1) * 1024) = fp8x8_to_half8<KV>(pr[j].z, pr[j].w);
                 } else {
                     *reinterpret_cast<u32x4*>(kdst + j * 1024) = pr[j];
                 }
@@ -303,7 +348,7 @@ prefill_chunk_kernel(const PrefillArgs a)
                         const u32x4 wa = pr[2 * jj] & a0, wb = pr[2 * jj + 1] & b0;
 #pragma unroll
                         for (int cc = 0; cc < 4; ++cc) {
-                            const half4_t va = e4m3x4_to_half4(wa[cc]), vb = e4m3x4_to_half4(wb[cc]);
+                            const half4_t va = fp8x4_to_half4<KV>(wa[cc]), vb = fp8x4_to_half4<KV>(wb[cc]);
                             *reinterpret_cast<half8_t*>(st + St::kV + (4 * (vj0 + jj) + cc) * 1024 + 16 * lane) =
                                 half8_t{va[0], va[1], va[2], va[3], vb[0], vb[1], vb[2], vb[3]};
                         }
@@ -317,7 +362,8 @@ prefill_chunk_kernel(const PrefillArgs a)
                     }
                 }
             }
-            // v_scale of this wave's block (wave 2: A, wave 3: B), zero for tokens not in the cache
+            // v_scale of this wave's block (wave 2: A, wave 3: B) times the pair's normaliser (an
+            // exact power of two, the same for every token), zero for tokens not in the cache
             // (a stale scale), and the operand of the row-sum product: row 0 = 2^-8 / v_scale cut
             // to fp16, row 1 = the remainder, rows 2..15 zero; block A's tokens are the lane's
             // first four halves, block B's the other four
@@ -326,7 +372,7 @@ prefill_chunk_kernel(const PrefillArgs a)
             half4_t rr;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                vs[i] = FP8 ? ((i < cache) ? psc[i] : 0.0f) : 1.0f;
+                vs[i] = FP8 ? ((i < cache) ? psc[i] * vnorm : 0.0f) : 1.0f;
                 // (the hardware reciprocal, 1 ulp: far inside what the fp16 pair keeps)
                 const float r = fminf(vs[i] > 0.0f ? 0.00390625f * __builtin_amdgcn_rcpf(vs[i]) : 0.0f, 65504.0f);
                 const float hi = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, r) & 0xffffe000u);
@@ -438,7 +484,8 @@ prefill_chunk_kernel(const PrefillArgs a)
     for (int r = 0; r < NR; ++r) {
         // column n's sum sits in rows 0 and 1 of lacc: lane (n, 0), registers 0 and 1
         const float L = __shfl(lacc[r][0] + lacc[r][1], n) * 256.0f;
-        const float inv = 1.0f / L;                       // the common power of two of acc and l cancels
+        // (the 2^kPShift common to acc and l cancels; the normaliser of the v_scales is in acc alone)
+        const float inv = (1.0f / L) * vdenorm;
         const int row = row0[r] + n;
         if (first_tile + r < end_tile && row < C) {
             half_t* dst = a.out + ((size_t)(qs + row) * a.H_q + head[r]) * HEAD_DIM + 4 * grp;
@@ -471,7 +518,7 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     if (sh->num_seqs == 0 || num_query_rows == 0 || max_chunk_len == 0) return COOPT_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !context_lens || !query_start || !out)
         return COOPT_ERR_NULL;
-    if (sh->kv_dtype == COOPT_KV_E4M3 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
+    if (sh->kv_dtype != COOPT_KV_FP16 && (!k_scale || !v_scale)) return COOPT_ERR_NULL;
 
     PrefillArgs a{};
     a.q = (const half_t*)q;
@@ -534,6 +581,9 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E4M3, true); else COOPT_PREFILL(128, COOPT_KV_E4M3, false); }
         else { if (big) COOPT_PREFILL(64, COOPT_KV_E4M3, true); else COOPT_PREFILL(64, COOPT_KV_E4M3, false); }
+    } else if (sh->kv_dtype == COOPT_KV_E5M2) {
+        if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E5M2, true); else COOPT_PREFILL(128, COOPT_KV_E5M2, false); }
+        else { if (big) COOPT_PREFILL(64, COOPT_KV_E5M2, true); else COOPT_PREFILL(64, COOPT_KV_E5M2, false); }
     } else {
         if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_FP16, true); else COOPT_PREFILL(128, COOPT_KV_FP16, false); }
         else { if (big) COOPT_PREFILL(64, COOPT_KV_FP16, true); else COOPT_PREFILL(64, COOPT_KV_FP16, false); }

@@ -47,7 +47,8 @@ def dev(a: np.ndarray) -> torch.Tensor:
 def shape_of(w, num_seqs=None) -> coopt.Shape:
     return coopt.Shape(w.S if num_seqs is None else num_seqs, w.H_q, w.H_k, w.d, w.B, w.NB,
                        w.max_blocks,
-                       coopt.COOPT_KV_E4M3 if w.kv_dtype == "e4m3" else coopt.COOPT_KV_FP16,
+                       {"e4m3": coopt.COOPT_KV_E4M3, "e5m2": coopt.COOPT_KV_E5M2,
+                        "fp16": coopt.COOPT_KV_FP16}[w.kv_dtype],
                        float(np.float32(w.softmax_scale)))
 
 
@@ -58,10 +59,10 @@ def cache_to_dev(cache):
 
 def alloc_dev_cache(w, fill_byte=0):
     """Device cache in the boundary layouts, every byte preset to fill_byte."""
-    es = 1 if w.kv_dtype == "e4m3" else 2
+    es = 2 if w.kv_dtype == "fp16" else 1
     k_cache = torch.full((w.NB, w.H_k, w.B * w.d * es), fill_byte, dtype=torch.uint8, device="cuda")
     v_cache = torch.full((w.NB, w.H_k, w.B * w.d * es), fill_byte, dtype=torch.uint8, device="cuda")
-    if w.kv_dtype == "e4m3":
+    if w.kv_dtype != "fp16":
         k_scale = torch.full((w.NB, w.H_k, w.B * 4), fill_byte, dtype=torch.uint8, device="cuda")
         v_scale = torch.full((w.NB, w.H_k, w.B * 4), fill_byte, dtype=torch.uint8, device="cuda")
     else:
@@ -76,7 +77,7 @@ def hip_write(w, dcache, idx=None, slots=None):
     s = (w.slots if idx is None else w.slots[idx]) if slots is None else slots
     dk, dv, ds = dev(k.view(np.uint16)), dev(v.view(np.uint16)), dev(s.astype(np.int64))
     shape = shape_of(w)
-    if w.kv_dtype == "e4m3":
+    if w.kv_dtype != "fp16":
         coopt.kv_cache_write_fp8(dk, dv, ds, *dcache, shape)
     else:
         coopt.kv_cache_write_fp16(dk, dv, ds, dcache[0], dcache[1], shape)
@@ -86,7 +87,7 @@ def hip_write(w, dcache, idx=None, slots=None):
 def dev_cache_to_host(w, dcache):
     """Device cache -> numpy arrays typed like the oracle's host cache."""
     k_cache, v_cache, k_scale, v_scale = dcache
-    if w.kv_dtype == "e4m3":
+    if w.kv_dtype != "fp16":
         return (k_cache.cpu().numpy(), v_cache.cpu().numpy(),
                 k_scale.cpu().numpy().view(np.float32), v_scale.cpu().numpy().view(np.float32))
     return (k_cache.cpu().numpy().view(np.float16), v_cache.cpu().numpy().view(np.float16), None, None)

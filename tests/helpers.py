@@ -23,7 +23,7 @@ def v_tile_index(d, E, B=16):
 
 
 def _E(w):
-    return 16 if w.kv_dtype == "e4m3" else 8
+    return 8 if w.kv_dtype == "fp16" else 16
 
 
 def k_logical(w, k_cache):
@@ -47,11 +47,11 @@ def v_store_logical(w, v_cache, logical):
 def alloc_cache(w, fill_byte=None):
     """Empty paged cache for workload ``w`` (numpy, host): tiles of B*d elements per (block, head)
     in the boundary's tile order, scales [NB, H_k, B]."""
-    dt = np.uint8 if w.kv_dtype == "e4m3" else np.float16
+    dt = np.float16 if w.kv_dtype == "fp16" else np.uint8
     k_cache = np.zeros((w.NB, w.H_k, w.B * w.d), dtype=dt)
     v_cache = np.zeros((w.NB, w.H_k, w.B * w.d), dtype=dt)
     k_scale = v_scale = None
-    if w.kv_dtype == "e4m3":
+    if w.kv_dtype != "fp16":
         k_scale = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32)
         v_scale = np.zeros((w.NB, w.H_k, w.B), dtype=np.float32)
     if fill_byte is not None:
@@ -76,6 +76,9 @@ def oracle_fill(oracle, w, idx=None, cache=None):
     if w.kv_dtype == "e4m3":
         oracle.kv_cache_write_fp8(k, v, slots, k_cache, v_cache, k_scale, v_scale,
                                   H_k=w.H_k, d=w.d, B=w.B)
+    elif w.kv_dtype == "e5m2":
+        oracle.kv_cache_write_fp8_scaled(k, v, slots, k_cache, v_cache, k_scale, v_scale,
+                                         H_k=w.H_k, d=w.d, B=w.B, fmt="e5m2", scale_mode="token")
     else:
         oracle.kv_cache_write_fp16(k, v, slots, k_cache, v_cache, H_k=w.H_k, d=w.d, B=w.B)
     return cache

@@ -82,7 +82,7 @@ def _shape(**kw):
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block_size=32), dict(num_q_heads=41),
-                                 dict(num_q_heads=8 * 17), dict(kv_dtype=2), dict(num_blocks=0),
+                                 dict(num_q_heads=8 * 17), dict(kv_dtype=3), dict(num_blocks=0),
                                  dict(num_kv_heads=0), dict(num_seqs=(1 << 20) + 1),
                                  dict(num_q_heads=8192, num_kv_heads=1024),
                                  dict(max_blocks_per_seq=(1 << 24) + 1),
@@ -117,6 +117,13 @@ def test_null_pointers_and_bad_arguments(lib):
     assert lib.coopt_kv_cache_write_skipset(None, one, one, one, 1, one, one, one, one, ctypes.byref(sh), None) == -1
     assert lib.coopt_kv_cache_write_skipset(one, one, one, None, 0, one, one, one, one, ctypes.byref(sh), None) == 0
     assert lib.coopt_kv_cache_write_skipset(one, one, one, one, 1, one, one, one, one, None, None) == -1
+    # the write under another scale rule: the mode is checked, static scales are required for it
+    scaled = lib.coopt_kv_cache_write_fp8_scaled
+    assert scaled(one, one, one, 1, one, one, one, one, 3, None, None, ctypes.byref(sh), None) == -2
+    assert scaled(one, one, one, 1, one, one, one, one, 2, None, one, ctypes.byref(sh), None) == -1
+    assert scaled(one, one, one, 1, one, one, one, None, 1, None, None, ctypes.byref(sh), None) == -1
+    assert scaled(one, one, one, 0, one, one, one, one, 1, None, None, ctypes.byref(sh), None) == 0
+    assert scaled(one, one, one, 1, one, one, one, one, 0, None, None, ctypes.byref(_shape(kv_dtype=0)), None) == -2
     # fused step: the new rows and a workspace are required
     assert lib.coopt_paged_gqa_decode_step(None, one, one, one, one, one, one, one, one, one, one, one, ctypes.c_size_t(need2), None, ctypes.byref(sh2), None) == -1
     assert lib.coopt_paged_gqa_decode_step(one, one, one, one, one, one, one, one, one, one, one, None, ctypes.c_size_t(need2), None, ctypes.byref(sh2), None) == -1

@@ -1,0 +1,200 @@
+"""GPU parity for the comparison schemes of the cache (the alternatives Opt-KV's dynamic per-token
+E4M3 scale stands against): OCP E5M2 codes, a scale per cache block, a static scale per KV head.
+Writes are compared with the oracle bit for bit (codes and scales); every read entry point runs
+over an E5M2 cache and over caches written under the other scale rules, against the oracle of the
+same scheme, to the attention tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_09323_amd as coopt
+import workloads
+from gpu_utils import (alloc_dev_cache, assert_close, cache_to_dev, dev, dev_cache_to_host, planned,
+                       shape_of)
+from helpers import alloc_cache
+
+pytestmark = pytest.mark.gpu
+
+MODES = {"token": coopt.COOPT_SCALE_TOKEN, "block": coopt.COOPT_SCALE_BLOCK, "static": coopt.COOPT_SCALE_STATIC}
+
+
+def _static_scales(w, fmt):
+    """A scale fixed in advance: from the first 24 tokens of the first sequence (later rows may saturate)."""
+    cmax = np.float32(448.0 if fmt == "e4m3" else 57344.0)
+    ks = (np.abs(w.k_ctx[:24].astype(np.float32)).max(axis=(0, 2)) / cmax).astype(np.float32)
+    vs = (np.abs(w.v_ctx[:24].astype(np.float32)).max(axis=(0, 2)) / cmax).astype(np.float32)
+    return ks, vs
+
+
+def _oracle_write(orc, w, fmt, mode, cache, idx, slots=None):
+    kw = {}
+    if mode == "static":
+        kw["k_static"], kw["v_static"] = _static_scales(w, fmt)
+    s = np.ascontiguousarray(w.slots[idx] if slots is None else slots)
+    orc.kv_cache_write_fp8_scaled(np.ascontiguousarray(w.k_ctx[idx]), np.ascontiguousarray(w.v_ctx[idx]), s,
+                                  *cache, H_k=w.H_k, d=w.d, B=w.B, fmt=fmt, scale_mode=mode, **kw)
+
+
+def _hip_write(w, fmt, mode, dcache, idx, slots=None):
+    ks = vs = None
+    if mode == "static":
+        ks, vs = (dev(a) for a in _static_scales(w, fmt))
+    s = w.slots[idx] if slots is None else slots
+    coopt.kv_cache_write_fp8_scaled(dev(w.k_ctx[idx].view(np.uint16)), dev(w.v_ctx[idx].view(np.uint16)),
+                                    dev(np.ascontiguousarray(s).astype(np.int64)), *dcache, shape_of(w),
+                                    MODES[mode], ks, vs)
+    torch.cuda.synchronize()
+
+
+def _same(w, dcache, cache, what):
+    for name, g, r in zip(("k_cache", "v_cache", "k_scale", "v_scale"), dev_cache_to_host(w, dcache), cache):
+        assert np.array_equal(g.reshape(-1).view(np.uint8), r.reshape(-1).view(np.uint8)), f"{what}: {name}"
+
+
+@pytest.mark.parametrize("fmt", ["e4m3", "e5m2"])
+@pytest.mark.parametrize("mode", ["token", "block", "static"])
+@pytest.mark.parametrize("d,H_k", [(128, 2), (64, 3)])
+def test_writes_bit_exact(oracle_mod, fmt, mode, d, H_k):
+    """History in calls of mixed sizes (1 token, a few, hundreds: the row kernel and, for the
+    per-token rule, the bulk kernel), some slots negative; poison-filled caches on both sides."""
+    lens = [300, 47, 16, 1, 129]
+    w = workloads.make_custom("sv", seed=101, S=len(lens), H_q=2 * H_k, H_k=H_k, d=d, B=16, NB=48,
+                              context_lens=lens, kv_dtype=fmt, k_outlier_frac=0.05)
+    host = alloc_cache(w, fill_byte=0x5A)
+    devc = alloc_dev_cache(w, fill_byte=0x5A)
+    for a in (host[2], host[3]):
+        a.view(np.uint8)[...] = 0x5A
+    rng = np.random.default_rng(7)
+    total = w.total_tokens
+    cuts = [0, 1, 4, 70, 71, 200, 333, total]
+    for a, b in zip(cuts, cuts[1:]):
+        idx = np.arange(a, b)
+        slots = w.slots[idx].copy()
+        slots[rng.random(len(idx)) < 0.1] = -1                       # Eq. 5: filtered tokens
+        _oracle_write(oracle_mod, w, fmt, mode, host, idx, slots)
+        _hip_write(w, fmt, mode, devc, idx, slots)
+        _same(w, devc, host, f"{fmt} {mode} d={d} tokens [{a},{b})")
+
+
+def test_every_fp16_input_value_e5m2(oracle_mod):
+    """All 63 488 finite fp16 values through the E5M2 write: rows of 64 consecutive bit patterns
+    (so every value also meets every position of a lane pair), both signs, row and bulk kernel."""
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = bits.view(np.float16)
+    bits = bits[np.isfinite(vals)]
+    n = len(bits) // 64
+    rows = bits[:n * 64].reshape(n, 1, 64).view(np.float16)
+    T = n
+    w = workloads.make_custom("all16", seed=102, S=1, H_q=1, H_k=1, d=64, B=16, NB=(T + 15) // 16 + 1,
+                              context_lens=[T], kv_dtype="e5m2")
+    w.k_ctx = rows.copy()
+    w.v_ctx = rows[::-1].copy()
+    for lo, hi in ((0, T), (0, 40)):                                  # bulk kernel, row kernel
+        host = alloc_cache(w)
+        devc = alloc_dev_cache(w, fill_byte=0)
+        idx = np.arange(lo, hi)
+        _oracle_write(oracle_mod, w, "e5m2", "token", host, idx)
+        _hip_write(w, "e5m2", "token", devc, idx)
+        _same(w, devc, host, f"all fp16 values, tokens [{lo},{hi})")
+
+
+def _read_everything(orc, w, cache, fmt, what, record=None):
+    """Every read entry point over `cache` (host arrays, any scale rule) against the oracle."""
+    H_q, H_k, d = w.H_q, w.H_k, w.d
+    ref = orc.paged_gqa_decode(w.q, *cache, w.block_tables, w.context_lens, H_q=H_q, H_k=H_k, d=d, B=16,
+                               softmax_scale=w.softmax_scale, fmt=fmt)
+    shape = shape_of(w)
+    q, bt, dl = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    full = cache_to_dev(cache)
+
+    def new_out():
+        return torch.full((w.S, H_q, d), -7.0, dtype=torch.float16, device="cuda")
+
+    def host(o):
+        torch.cuda.synchronize()
+        return o.cpu().numpy().astype(np.float64)
+
+    for workspace in (ws, None):
+        out = new_out()
+        planned.paged_gqa_decode(q, *full, bt, dl, out, workspace, shape)
+        assert_close(host(out), ref, f"{what}: decode, workspace={workspace is not None}", record)
+    sched = torch.zeros(planned.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
+    planned.decode_schedule_prepare(bt, dl, None, sched, shape)
+    out = new_out()
+    planned.paged_gqa_decode_scheduled(None, None, None, q, *full, dl, out, ws, sched, shape)
+    assert_close(host(out), ref, f"{what}: scheduled decode", record)
+    part = 64
+    max_parts = (w.max_blocks * 16 + part - 1) // part
+    tmp = torch.full((w.S, H_q, max_parts, d), float("nan"), dtype=torch.float32, device="cuda")
+    ml = torch.full((w.S, H_q, max_parts), float("nan"), dtype=torch.float32, device="cuda")
+    es = torch.full_like(ml, float("nan"))
+    out = new_out()
+    planned.paged_gqa_decode_partitioned(q, *full, bt, dl, part, tmp, ml, es, max_parts, shape)
+    coopt.paged_gqa_reduce(tmp, ml, es, dl, part, max_parts, out, shape)
+    assert_close(host(out), ref, f"{what}: partitioned + reduce", record)
+    # chunked prefill: the last C tokens of every sequence as the chunk
+    C = 20
+    lens = np.maximum(w.context_lens, C).astype(np.int32)
+    if np.array_equal(lens, w.context_lens):
+        qs = (np.arange(w.S + 1) * C).astype(np.int32)
+        qrows = np.random.default_rng(5).standard_normal((w.S * C, H_q, d), dtype=np.float32).astype(np.float16)
+        pref = orc.paged_gqa_prefill_chunk(qrows, *cache, w.block_tables, w.context_lens, qs, H_q=H_q,
+                                           H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale, fmt=fmt)
+        pout = torch.full((w.S * C, H_q, d), -7.0, dtype=torch.float16, device="cuda")
+        coopt.paged_gqa_prefill_chunk(dev(qrows.view(np.uint16)), *full, bt, dl, dev(qs), w.S * C, C, pout, shape)
+        assert_close(host(pout), pref, f"{what}: chunked prefill", record)
+    # dequantising gather: bit-exact
+    for s, lo, hi in ((0, 0, int(w.context_lens[0])), (w.S - 1, 3, int(w.context_lens[-1]))):
+        k_ref, v_ref = orc.gather_cached_kv(*cache, w.block_tables, s, lo, hi, H_k=H_k, d=d, B=16, fmt=fmt)
+        k_out = torch.full((hi - lo, H_k, d), 7.0, dtype=torch.float16, device="cuda")
+        v_out = torch.full_like(k_out, 7.0)
+        coopt.gather_cached_kv(*full, bt, s, lo, hi, k_out, v_out, shape)
+        torch.cuda.synchronize()
+        assert np.array_equal(k_out.cpu().numpy().view(np.uint16), k_ref.astype(np.float16).view(np.uint16)), what
+        assert np.array_equal(v_out.cpu().numpy().view(np.uint16), v_ref.astype(np.float16).view(np.uint16)), what
+    return ref
+
+
+@pytest.mark.parametrize("fmt,mode", [("e5m2", "token"), ("e5m2", "block"), ("e4m3", "block"),
+                                      ("e4m3", "static"), ("e5m2", "static")])
+@pytest.mark.parametrize("H_q,H_k,d", [(40, 8, 128), (6, 2, 64)])
+def test_reads_over_every_scheme(oracle_mod, fmt, mode, H_q, H_k, d, record_property):
+    lens = [33, 700, 20, 257, 512, 100]
+    w = workloads.make_custom("rv", seed=103, S=len(lens), H_q=H_q, H_k=H_k, d=d, B=16, NB=128,
+                              context_lens=lens, kv_dtype=fmt, k_outlier_frac=0.02, max_blocks=48)
+    cache = alloc_cache(w)
+    _oracle_write(oracle_mod, w, fmt, mode, cache, np.arange(w.total_tokens))
+    _read_everything(oracle_mod, w, cache, fmt, f"{fmt} {mode} {H_q}/{H_k}/{d}", record_property)
+
+
+@pytest.mark.parametrize("H_q,H_k,d", [(40, 8, 128), (6, 2, 64)])
+def test_fused_step_over_an_e5m2_cache(oracle_mod, H_q, H_k, d):
+    """The fused step (dynamic per-token scale, the method's rule) with E5M2 codes: cache bytes bit
+    for bit, outputs to the tolerance, live and from a prepared schedule."""
+    lens = [1, 2, 17, 33, 300, 700, 512, 64]
+    w = workloads.make_custom("fs", seed=104, S=len(lens), H_q=H_q, H_k=H_k, d=d, B=16, NB=128,
+                              context_lens=lens, kv_dtype="e5m2", max_blocks=48)
+    cache = alloc_cache(w)
+    _oracle_write(oracle_mod, w, "e5m2", "token", cache, np.arange(w.total_tokens))
+    ref = oracle_mod.paged_gqa_decode(w.q, *cache, w.block_tables, w.context_lens, H_q=H_q, H_k=H_k, d=d,
+                                      B=16, softmax_scale=w.softmax_scale, fmt="e5m2")
+    shape = shape_of(w)
+    q, bt, dl = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
+    new = w.new_index()
+    k_new, v_new = dev(w.k_ctx[new].view(np.uint16)), dev(w.v_ctx[new].view(np.uint16))
+    slots = dev(w.slots[new].astype(np.int64))
+    ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    sched = torch.zeros(planned.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
+    for prepared in (False, True):
+        dcache = alloc_dev_cache(w, fill_byte=0)
+        _hip_write(w, "e5m2", "token", dcache, w.history_index())
+        out = torch.full((w.S, H_q, d), -7.0, dtype=torch.float16, device="cuda")
+        if prepared:
+            planned.decode_schedule_prepare(bt, dl, slots, sched, shape)
+            planned.paged_gqa_decode_scheduled(k_new, v_new, slots, q, *dcache, dl, out, ws, sched, shape)
+        else:
+            planned.paged_gqa_decode_step(k_new, v_new, slots, q, *dcache, bt, dl, out, ws, shape)
+        torch.cuda.synchronize()
+        assert_close(out.cpu().numpy().astype(np.float64), ref, f"e5m2 fused step, prepared={prepared}")
+        _same(w, dcache, cache, f"e5m2 fused step, prepared={prepared}")

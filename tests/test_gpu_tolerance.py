@@ -24,7 +24,8 @@ def _every_decode_entry_point(orc, w, what, record=None, check=assert_close):
     """All decode entry points on workload w against the oracle; returns the oracle's rows."""
     cache = oracle_fill(orc, w)
     ref = orc.paged_gqa_decode(w.q, *cache, w.block_tables, w.context_lens, H_q=w.H_q, H_k=w.H_k,
-                               d=w.d, B=w.B, softmax_scale=w.softmax_scale)
+                               d=w.d, B=w.B, softmax_scale=w.softmax_scale,
+                               fmt="e5m2" if w.kv_dtype == "e5m2" else "e4m3")
     shape = shape_of(w)
     q, bt, dl = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
     ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
@@ -47,7 +48,7 @@ def _every_decode_entry_point(orc, w, what, record=None, check=assert_close):
     slots = dev(w.slots[new].astype(np.int64))
     sched = torch.zeros(planned.decode_schedule_bytes(shape), dtype=torch.uint8, device="cuda")
     for prepared in (False, True):
-        dcache = alloc_dev_cache(w, fill_byte=0x7F if w.kv_dtype == "e4m3" else 0)
+        dcache = alloc_dev_cache(w, fill_byte=0x7F if w.kv_dtype != "fp16" else 0)
         hip_write(w, dcache, idx=w.history_index())
         out = new_out()
         if prepared:
@@ -122,7 +123,7 @@ def test_one_key_dominates_a_long_context(oracle_mod, kv_dtype, record_property)
 
 
 @pytest.mark.parametrize("gain", [1e-3, 1e2])
-@pytest.mark.parametrize("kv_dtype", ["e4m3", "fp16"])
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "e5m2", "fp16"])
 def test_value_rows_far_from_unit_scale(oracle_mod, kv_dtype, gain, record_property):
     """V ~ N(0, gain^2): the bar scales with the rows (relative to unit-scale rows the arithmetic is
     the same up to powers of two and the fp16 formats' ends)."""
@@ -135,6 +136,35 @@ def test_value_rows_far_from_unit_scale(oracle_mod, kv_dtype, gain, record_prope
         return assert_close(got / gain, ref / gain, what, record)
 
     _every_decode_entry_point(oracle_mod, w, f"V x {gain:g}, {kv_dtype}", record_property, check=check)
+
+
+@pytest.mark.parametrize("gain", [1e-3, 1.0, 1e2, "mixed"])
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "e5m2", "fp16"])
+def test_prefill_value_rows_of_any_magnitude(oracle_mod, kv_dtype, gain, record_property):
+    """Chunked prefill with V ~ N(0, gain^2), and with a pair's rows spread over six decades
+    ("mixed": per token a gain 10^u, u uniform in [-4, 2]; the bar is set by the largest rows).
+    An E5M2 cache's scales are 2^-7 of an E4M3 cache's, so this also walks the fp16 weights'
+    exponent range from both ends."""
+    S, C, hist = 4, 48, [0, 17, 300, 1000]
+    w = workloads.make_custom("pf_gain", seed=95, S=S, H_q=10, H_k=2, d=128, B=16, NB=120,
+                              context_lens=[h + C for h in hist], new_per_seq=C, kv_dtype=kv_dtype)
+    v = w.v_ctx.astype(np.float32)
+    if gain == "mixed":
+        per_token = 10.0 ** np.random.default_rng(96).uniform(-4, 2, size=(v.shape[0], v.shape[1], 1))
+        v, unit = v * per_token.astype(np.float32), 1e2
+    else:
+        v, unit = v * np.float32(gain), gain
+    w.v_ctx = v.astype(np.float16)
+    cache = oracle_fill(oracle_mod, w)
+    ref = oracle_mod.paged_gqa_prefill_chunk(w.q, *cache, w.block_tables, w.context_lens, w.query_start,
+                                             H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B, softmax_scale=w.softmax_scale,
+                                             fmt="e5m2" if kv_dtype == "e5m2" else "e4m3")
+    out = torch.full((S * C, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
+    coopt.paged_gqa_prefill_chunk(dev(w.q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables),
+                                  dev(w.context_lens), dev(w.query_start), S * C, C, out, shape_of(w))
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy().astype(np.float64) / unit, ref / unit, f"prefill V x {gain}, {kv_dtype}",
+                 record_property)
 
 
 def test_outlier_workload_full_size(oracle_mod, record_property):
