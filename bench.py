@@ -89,11 +89,14 @@ def parse_args():
                          "over the KV pools (coopt_decode_schedule_prepare, inside the timed region: "
                          "the layers of one decoding step share block tables and lengths) and runs "
                          "the layers from it; 'live' derives it inside every launch")
-    ap.add_argument("--op", choices=["step", "gather", "stream-read"], default="step",
+    ap.add_argument("--op", choices=["step", "gather", "stream-read", "schemes"], default="step",
                     help="step: the decode / prefill step of the workload (default).  gather: "
                          "coopt_gather_cached_kv of every sequence's whole context (one launch per "
                          "sequence), reported in GB/s against the HBM peak.  stream-read: the "
-                         "read-only streaming probe over 2 GiB, every launch shape it tries")
+                         "read-only streaming probe over 2 GiB, every launch shape it tries.  "
+                         "schemes: E4M3 / E5M2 codes with a per-token, per-block or static scale on the "
+                         "long-context outlier workload (config 3 unless --config names another): "
+                         "step time and attention error against an fp16 cache")
     ap.add_argument("--preroll", type=int, default=300,
                     help="untimed launches of the step before the warm-up steps, so that a short run "
                          "is not timed while the clocks are still coming up (disclosed in the line)")
@@ -143,6 +146,10 @@ def main():
     if args.op == "stream-read":
         print(json.dumps(stream_read_ceiling(probe, torch, dev, detail=True)), flush=True)
         return
+    if args.op == "schemes":
+        w = workloads.make(3 if args.config is None else args.config)
+        print(json.dumps(bench_schemes(args, w, coopt, torch, dev, plan)), flush=True)
+        return
     cfg = 1 if args.config is None else args.config
     w = workloads.make(cfg)
     if args.op == "gather":
@@ -179,6 +186,45 @@ def compact(r, path):
             "kernel_us": rf.get("kernel_us_mean", round(rf.get("kernel_ms_mean", 0.0) * 1e3, 3)),
             "bound": rf["bound"], "achieved": rf["achieved"], "unit": rf["unit"], "frac": rf["frac"],
             "step_us": round(r["ms_per_step"] * 1e3, 3), "steps": r["steps"]}
+
+
+def graph_timed(torch, fn, count, layers, eager=False):
+    """Mean GPU time per call of fn(i), i = 0..count-1, in ms.  The calls are captured into HIP
+    graphs of one rotation over the pools each (the step is ~2 launches of a few us, so eager
+    launches from Python would measure the host, not the GPU) and replayed back to back on the
+    current stream between two events."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if eager:
+        e0.record()
+        for i in range(count):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count
+    graphs = []
+    for n_in in (layers, count % layers):
+        if n_in == 0 or (n_in == layers and count < layers):
+            graphs.append(None)
+            continue
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n_in):
+                fn(i)
+        graphs.append(g)
+    full, rest = graphs
+    if full is not None:
+        full.replay()                     # untimed: first replay uploads the graph
+    if rest is not None:
+        rest.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(count // layers):
+        full.replay()
+    if rest is not None:
+        rest.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / count
 
 
 def bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, warmup, cpu, stream):
@@ -268,44 +314,8 @@ def bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, warmup, c
         write_new(kc, vc, ks, vs)
         attend(i)
 
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
     def timed(fn, count):
-        """Mean GPU time per call of fn(i), i = 0..count-1, in ms.  The calls are captured into HIP
-        graphs of one rotation over the pools each (the step is ~2 launches of a few us, so eager
-        launches from Python would measure the host, not the GPU) and replayed back to back on the
-        current stream between two events."""
-        if args.no_graph:
-            e0.record()
-            for i in range(count):
-                fn(i)
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / count
-        graphs = []
-        for n_in in (layers, count % layers):
-            if n_in == 0 or (n_in == layers and count < layers):
-                graphs.append(None)
-                continue
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for i in range(n_in):
-                    fn(i)
-            graphs.append(g)
-        full, rest = graphs
-        if full is not None:
-            full.replay()                     # untimed: first replay uploads the graph
-        if rest is not None:
-            rest.replay()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(count // layers):
-            full.replay()
-        if rest is not None:
-            rest.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / count
+        return graph_timed(torch, fn, count, layers, args.no_graph)
 
     # ---- untimed pre-roll (the first launches after idle run while the clocks come up), then W
     # warm-up steps, then exactly K steps between two synchronisations
@@ -431,6 +441,92 @@ def bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, warmup, c
                             "finite": bool(np.isfinite(got).all())}
     del pools
     return result
+
+
+def bench_schemes(args, w, coopt, torch, dev, plan):
+    """The cache schemes that Opt-KV's choice (E4M3 codes, a scale per token and KV head computed at
+    write time) stands against, on one workload: E4M3 or E5M2 codes, with a scale per token, per
+    16-token block, or fixed in advance per KV head.  For each: the time of a decode step (the new
+    tokens' write under that scheme + balanced decode, one layer, pools rotated) and the error of
+    the attention output against the same step over an fp16 cache.  The fp16-cache rows come from
+    this library's own fp16 path (which the GPU tests hold to 2e-3 of the float64 oracle, an order
+    of magnitude under the differences reported here).  All schemes keep one scale entry per
+    (token, KV head) in the cache, so they move the same bytes."""
+    steps, layers = max(args.steps, 200), 8
+    hist, new = w.history_index(), w.new_index()
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    k_hist, v_hist = to_dev(w.k_ctx[hist].view(np.uint16)), to_dev(w.v_ctx[hist].view(np.uint16))
+    k_new, v_new = to_dev(w.k_ctx[new].view(np.uint16)), to_dev(w.v_ctx[new].view(np.uint16))
+    s_hist, s_new = to_dev(w.slots[hist]), to_dev(w.slots[new])
+    q, bt, lens = to_dev(w.q.view(np.uint16)), to_dev(w.block_tables), to_dev(w.context_lens)
+    calib = 256                                          # static scales: absmax of the first tokens of sequence 0
+    k_amax = np.abs(w.k_ctx[:calib].astype(np.float32)).max(axis=(0, 2))
+    v_amax = np.abs(w.v_ctx[:calib].astype(np.float32)).max(axis=(0, 2))
+    modes = {"token": coopt.COOPT_SCALE_TOKEN, "block": coopt.COOPT_SCALE_BLOCK, "static": coopt.COOPT_SCALE_STATIC}
+
+    def run(codes, scale):
+        fp16 = codes == "fp16"
+        kv = {"fp16": coopt.COOPT_KV_FP16, "e4m3": coopt.COOPT_KV_E4M3, "e5m2": coopt.COOPT_KV_E5M2}[codes]
+        shape = coopt.Shape(w.S, w.H_q, w.H_k, w.d, w.B, w.NB, w.max_blocks, kv, float(np.float32(w.softmax_scale)))
+        es = 2 if fp16 else 1
+        cmax = np.float32(448.0 if codes == "e4m3" else 57344.0)
+        k_st = to_dev((k_amax / cmax).astype(np.float32)) if scale == "static" else None
+        v_st = to_dev((v_amax / cmax).astype(np.float32)) if scale == "static" else None
+
+        def write(k, v, s, pool):
+            kc, vc, ks, vs = pool
+            if fp16:
+                coopt.kv_cache_write_fp16(k, v, s, kc, vc, shape)
+            else:
+                coopt.kv_cache_write_fp8_scaled(k, v, s, kc, vc, ks, vs, shape, modes[scale], k_st, v_st)
+
+        pools = []
+        for _ in range(layers):
+            kc = torch.zeros((w.NB, w.H_k, w.B, w.d * es), dtype=torch.uint8, device=dev)
+            vc = torch.zeros((w.NB, w.H_k, w.d, w.B * es), dtype=torch.uint8, device=dev)
+            ks = None if fp16 else torch.zeros((w.NB, w.H_k, w.B), dtype=torch.float32, device=dev)
+            vs = None if fp16 else torch.zeros((w.NB, w.H_k, w.B), dtype=torch.float32, device=dev)
+            pools.append((kc, vc, ks, vs))
+            write(k_hist, v_hist, s_hist, pools[-1])
+        out = torch.zeros((w.S, w.H_q, w.d), dtype=torch.float16, device=dev)
+        ws = torch.empty(max(16, coopt.decode_workspace_bytes(shape, plan)), dtype=torch.uint8, device=dev)
+
+        def decode(i):
+            coopt.paged_gqa_decode(q, *pools[i % layers], bt, lens, out, ws, shape, plan)
+
+        def step(i):
+            write(k_new, v_new, s_new, pools[i % layers])
+            decode(i)
+
+        graph_timed(torch, step, args.preroll, layers, args.no_graph)
+        step_us = graph_timed(torch, step, steps, layers, args.no_graph) * 1e3
+        decode_us = graph_timed(torch, decode, steps, layers, args.no_graph) * 1e3
+        rows = out.cpu().numpy().astype(np.float64)
+        del pools
+        torch.cuda.empty_cache()
+        return step_us, decode_us, rows
+
+    _, _, ref = run("fp16", None)
+    ref_rms = float(np.sqrt((ref ** 2).mean()))
+    table = []
+    for codes in ("e4m3", "e5m2"):
+        for scale in ("token", "block", "static"):
+            step_us, decode_us, rows = run(codes, scale)
+            err = rows - ref
+            table.append({"codes": codes, "scale": scale, "step_us": round(step_us, 3),
+                          "decode_us": round(decode_us, 3), "max_abs_err": float(np.abs(err).max()),
+                          "rms_err": float(np.sqrt((err ** 2).mean())),
+                          "rel_rms_err": float(np.sqrt((err ** 2).mean())) / ref_rms,
+                          "finite": bool(np.isfinite(rows).all())})
+            print("# %s %s: %s" % (codes, scale, table[-1]), file=sys.stderr, flush=True)
+    return {"metric": "cache schemes: decode step time and attention error against an fp16 cache",
+            "workload": w.name, "steps": steps, "kv_pools_rotated": layers,
+            "reference": "the same step over an fp16 cache (this library's fp16 path), rms of its rows %.4f" % ref_rms,
+            "static_scale_calibration": "absmax over the first %d tokens of sequence 0, per KV head, / largest code" % calib,
+            "method": {"codes": "e4m3", "scale": "token"}, "schemes": table}
 
 
 def stream_read_ceiling(coopt, torch, dev, detail=False):      # `coopt`: the probe's binding
