@@ -182,3 +182,39 @@ def test_llama13b_shapes_full_size(oracle_mod, cfg):
     ref = _oracle_decode(oracle_mod, w, cache)
     got = hip_decode(w, cache_to_dev(cache), split=True)
     print("full cfg%d max-abs %.2e" % (cfg, assert_close(got, ref, f"cfg{cfg}")), flush=True)
+
+
+def test_merge_refuses_partials_of_another_plan(oracle_mod):
+    """The split launch stamps the workspace with the layout its plan gives the partials; a merge
+    call with a plan that lays them out differently (or on a workspace no split call has written)
+    writes nothing.  With the split's own plan the same workspace then merges correctly."""
+    w = workloads.make_custom("tag", seed=40, S=5, H_q=10, H_k=2, d=128, B=16, NB=160,
+                              context_lens=[300, 1, 1025, 47, 640], max_blocks=80)
+    cache = oracle_fill(oracle_mod, w)
+    ref = _oracle_decode(oracle_mod, w, cache)
+    shape = shape_of(w)
+    dcache = cache_to_dev(cache)
+    dlen = dev(w.context_lens)
+    plans = [dict(tokens_per_group=128, waves_per_group=1, pipeline_depth=2, grid_waves=1024, softmax_reduction=0),
+             dict(tokens_per_group=64, waves_per_group=1, pipeline_depth=2, grid_waves=1024, softmax_reduction=0),
+             dict(tokens_per_group=128, waves_per_group=1, pipeline_depth=2, grid_waves=96, softmax_reduction=0)]
+    sizes = []
+    for p in plans:
+        planned.set_plan(**p)
+        sizes.append(planned.decode_workspace_bytes(shape))
+    ws = torch.zeros(max(sizes), dtype=torch.uint8, device="cuda")
+    out = torch.full((w.S, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
+    planned.set_plan(**plans[0])
+    planned.paged_gqa_decode_merge(dlen, ws, out, shape)            # nothing has been split into it
+    torch.cuda.synchronize()
+    assert torch.all(out == -7.0)
+    planned.paged_gqa_decode_split(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables), dlen, ws, shape)
+    for other in plans[1:]:
+        planned.set_plan(**other)
+        planned.paged_gqa_decode_merge(dlen, ws, out, shape)
+        torch.cuda.synchronize()
+        assert torch.all(out == -7.0), other
+    planned.set_plan(**plans[0])
+    planned.paged_gqa_decode_merge(dlen, ws, out, shape)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy().astype(np.float64), ref, "merge with the split's plan")
