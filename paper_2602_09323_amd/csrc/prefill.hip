@@ -56,7 +56,7 @@ struct PrefillStage {
     static constexpr int kVOps = HEAD_DIM / 16;        // O^T MFMAs per group
     static constexpr int kK = 0;                        // [2 blocks][kKOps][64 lanes] 8 halves
     static constexpr int kV = 2 * kKOps * 1024;         // [kVOps][64 lanes] 4 halves of A, 4 of B
-    static constexpr int kS = kV + kVOps * 1024;        // 16 floats each: k_scale*c A, B; v_scale A, B
+    static constexpr int kS = kV + kVOps * 1024;        // 16 floats each: k_scale*c A, B; log2 v_scale A, B
     static constexpr int kR = kS + 256;                 // [64 lanes] 8 halves: 1/v_scale rows (below)
     static constexpr int kBytes = kR + 1024;
 };
@@ -66,8 +66,8 @@ struct PrefillStage {
 // softmax (the matrix pipe then works on the next tile's scores and on this tile's P.V while the
 // vector ALU does the exponentials).
 //   kA/kB = K operands of blocks A/B, vop = V operands of the group, ksc = k_scale * softmax_scale
-//   * log2(e) and vs = v_scale of this lane's 4 tokens per block.  tail / visA / visB as in
-//   group_update (attn_tile.hpp); absent tokens are already zero in vop and vs.
+//   * log2(e) and lv = log2(v_scale) of this lane's 4 tokens per block.  tail / visA / visB as in
+//   group_update (attn_tile.hpp); absent tokens are already zero in vop and have lv = -inf.
 template <int HEAD_DIM>
 __device__ __forceinline__ void tile_scores(const half8_t (&kA)[HEAD_DIM / 32],
                                             const half8_t (&kB)[HEAD_DIM / 32],
@@ -84,58 +84,79 @@ __device__ __forceinline__ void tile_scores(const half8_t (&kA)[HEAD_DIM / 32],
 }
 
 // The weights enter the second product rounded to fp16, w~ = fp16(P * v_scale): one token's weight
-// is then off by up to 2^-11 relative, which shows in the output when that token carries the row
+// is then off by up to 2^-10 relative, which shows in the output when that token carries the row
 // (an fp16 output near |x| = 3 moves by 1.5e-3).  So the row sum is taken from the SAME rounded
 // weights, l = sum_j w~_j / v_scale_j: numerator and denominator then describe one softmax with
-// weights perturbed by 2^-11 relative, whose result differs from the exact one by at most 2^-11
-// times the weighted mean deviation of the value rows from the result -- nothing for one token or
-// a dominant one.  The sum runs on the matrix cores: `rop` is a 16-row operand whose row 0 holds
-// 2^-8 / v_scale of the group's 32 tokens cut to fp16 and row 1 the remainder (the producers
+// weights perturbed by at most 2^-10 relative, whose result differs from the exact one by at most
+// that times the weighted mean deviation of the value rows from the result -- nothing for one
+// token or a dominant one.  (For the same reason the convert may truncate: a common bias of the
+// weights cancels.)  The sum runs on the matrix cores: `rop` is a 16-row operand whose row 0
+// holds 2^-8 / v_scale of the group's 32 tokens cut to fp16 and row 1 the remainder (the producers
 // write it), so one more 16x16x32 product per tile accumulates it in rows 0 and 1 of `lacc`,
-// which replaces eight vector additions.  2^-8 keeps the reciprocals inside fp16 for every
-// v_scale a finite fp16 row can have down to 2^-24.
-template <int HEAD_DIM>
-__device__ __forceinline__ void tile_softmax_pv(floatx4 sA, floatx4 sB,
-                                                const half8_t (&vop)[HEAD_DIM / 16], half8_t rop,
-                                                floatx4 kscA, floatx4 kscB, floatx4 vsA, floatx4 vsB,
-                                                float& m, floatx4& lacc,
-                                                floatx4 (&acc)[HEAD_DIM / 16], bool tail, int visA,
-                                                int visB)
+// which replaces eight vector additions.
+//
+// v_scale reaches the weight through the exponent: the producers leave lv = log2(v_scale) beside
+// k_scale (both already normalised, see the kernel), the score of a token is z' = s * ksc + lv in
+// one fused multiply-add, and the running reference m follows the maximum of z'.  The weight
+// exp2(z' - m) = P * v_scale * 2^(...) then needs no multiplication of its own and is at most
+// 2^(kPShift + kRescaleSlack) whatever the scales are.  A token that is not in the cache has
+// lv = -inf and so the weight 0.
+// The step in four parts, so that the caller can run the parts of its tiles side by side: the
+// scores of a token (one fused multiply-add each) and their maximum; the rare raise of the running
+// reference; the weights; the two matrix products.  TAIL: some of the group's tokens are not
+// visible to every column.
+template <bool TAIL>
+__device__ __forceinline__ float tile_logits(floatx4 sA, floatx4 sB, floatx4 kscA, floatx4 kscB,
+                                             floatx4 lvA, floatx4 lvB, int visA, int visB,
+                                             float (&z)[8])
 {
-    float z[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        z[i] = sA[i] * kscA[i];
-        z[4 + i] = sB[i] * kscB[i];
+        z[i] = __builtin_fmaf(sA[i], kscA[i], lvA[i]);
+        z[4 + i] = __builtin_fmaf(sB[i], kscB[i], lvB[i]);
     }
-    if (tail) {
+    if constexpr (TAIL) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            z[i] = fminf(z[i], (i < visA) ? INFINITY : -INFINITY);          // min drops a NaN score
-            z[4 + i] = fminf(z[4 + i], (i < visB) ? INFINITY : -INFINITY);
+        for (int i = 0; i < 4; ++i) {                   // (a select also drops a NaN score)
+            z[i] = (i < visA) ? z[i] : -INFINITY;
+            z[4 + i] = (i < visB) ? z[4 + i] : -INFINITY;
         }
     }
-    const float bm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])),
-                           fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-    if (__builtin_amdgcn_ballot_w64(bm > m + kRescaleSlack) != 0) {   // wave-uniform, rare
-        float nm = fmaxf(bm, __shfl_xor(bm, 16));
-        nm = fmaxf(nm, __shfl_xor(nm, 32));
-        nm = fmaxf(nm, m);
-        const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = -inf at the start gives 0
-        lacc *= alpha;
+    return fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+}
+
+template <int HEAD_DIM>
+__device__ __forceinline__ void tile_raise(float bm, float& m, floatx4& lacc, floatx4 (&acc)[HEAD_DIM / 16])
+{
+    float nm = fmaxf(bm, __shfl_xor(bm, 16));
+    nm = fmaxf(nm, __shfl_xor(nm, 32));
+    nm = fmaxf(nm, m);
+    const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = -inf at the start gives 0
+    lacc *= alpha;
 #pragma unroll
-        for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
-        m = nm;
-    }
+    for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
+    m = nm;
+}
+
+__device__ __forceinline__ half8_t tile_weights(const float (&z)[8], float m)
+{
     const float mm = m - kPShift;
-    float p[8];
+    half8_t pop;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(z[i] - mm) * vsA[i];    // invisible: exp2(-inf) = 0
-        p[4 + i] = __builtin_amdgcn_exp2f(z[4 + i] - mm) * vsB[i];
+    for (int i = 0; i < 8; i += 2) {
+        const half2_t h = __builtin_bit_cast(
+            half2_t, __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(z[i] - mm),      // invisible: exp2(-inf) = 0
+                                                __builtin_amdgcn_exp2f(z[i + 1] - mm)));
+        pop[i] = h.x;
+        pop[i + 1] = h.y;
     }
-    const half8_t pop = {(half_t)p[0], (half_t)p[1], (half_t)p[2], (half_t)p[3],
-                         (half_t)p[4], (half_t)p[5], (half_t)p[6], (half_t)p[7]};
+    return pop;
+}
+
+template <int HEAD_DIM>
+__device__ __forceinline__ void tile_pv(const half8_t (&vop)[HEAD_DIM / 16], half8_t rop, half8_t pop,
+                                        floatx4& lacc, floatx4 (&acc)[HEAD_DIM / 16])
+{
     lacc = mfma_16x16x32(rop, pop, lacc);
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] = mfma_16x16x32(vop[c], pop, acc[c]);
@@ -290,19 +311,25 @@ prefill_chunk_kernel(const PrefillArgs a)
     const TileLoader<HEAD_DIM, KV, BIG> loader(a.cv, lane, a.pool_tiles);
     u32x4 prs[kOwn][NP];
     floatx4 pscs[kOwn];
-    const int vj0 = wave == 2 ? 0 : NLH;                   // first V piece of a V wave
-    const int vcnt = wave == 2 ? NLH : NL - NLH;           // and how many it brings
+    // The four producer roles of a team -- 0: K of block A, 1: K of block B, 2 and 3: the two halves
+    // of the V pieces of both blocks (and the v_scale work of block A, B).  A V role costs twice a
+    // K role (890 against 440 cycles per group), but rotating the roles over the team's waves from
+    // group to group, which evens the waves out, made the whole kernel 3 % slower, so they are fixed.
+    auto role_of = [&](int) { return wave; };
     auto produce_issue = [&](int p, int blockA, int blockB, u32x4 (&pr)[NP], floatx4& psc) {
+        const int role = role_of(p);
+        const int vj0 = role == 2 ? 0 : NLH;               // first V piece of a V role
+        const int vcnt = role == 2 ? NLH : NL - NLH;       // and how many it brings
         const bool okA = 2 * p < nblk, okB = 2 * p + 1 < nblk;
         const int tA = blockA * a.H_k + g;
         const int tB = blockB * a.H_k + g;
         // (one comparison for "is my block there": a choice between the two flags okA and okB
         // would be made in vector registers, the very ones the loads issued a moment ago will
         // fill, and cost a wait for those loads)
-        const int mine = wave & 1;                         // waves 0, 2: block A; waves 1, 3: block B
+        const int mine = role & 1;                         // roles 0, 2: block A; roles 1, 3: block B
         const bool ok_mine = 2 * p + mine < nblk;
         const int t_mine = mine ? tB : tA;
-        if (wave < 2) {
+        if (role < 2) {
 #pragma unroll
             for (int j = 0; j < NL; ++j) pr[j] = loader.load_piece(a.cv.k_cache, t_mine, j, ok_mine);
             if constexpr (FP8) psc = loader.load_scales(a.cv.k_scale, t_mine, ok_mine);
@@ -318,8 +345,11 @@ prefill_chunk_kernel(const PrefillArgs a)
         }
     };
     auto produce_store = [&](int p, unsigned char* st, const u32x4 (&pr)[NP], const floatx4& psc) {
-        if (wave < 2) {
-            unsigned char* kdst = st + St::kK + wave * (St::kKOps * 1024) + 16 * lane;
+        const int role = role_of(p);
+        const int vj0 = role == 2 ? 0 : NLH;
+        const int vcnt = role == 2 ? NLH : NL - NLH;
+        if (role < 2) {
+            unsigned char* kdst = st + St::kK + role * (St::kKOps * 1024) + 16 * lane;
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
                 if constexpr (FP8) {
@@ -331,7 +361,7 @@ prefill_chunk_kernel(const PrefillArgs a)
             }
             if constexpr (FP8) {
                 if (n == 0)
-                    *reinterpret_cast<floatx4*>(st + St::kS + 64 * wave + 16 * grp) = psc * a.scale_log2e;
+                    *reinterpret_cast<floatx4*>(st + St::kS + 64 * role + 16 * grp) = psc * a.scale_log2e;
             }
         } else {
             // this lane's 4 tokens of block A start at 32p + 4grp, of block B 16 later
@@ -362,26 +392,27 @@ prefill_chunk_kernel(const PrefillArgs a)
                     }
                 }
             }
-            // v_scale of this wave's block (wave 2: A, wave 3: B) times the pair's normaliser (an
+            // v_scale of this role's block (role 2: A, role 3: B) times the pair's normaliser (an
             // exact power of two, the same for every token), zero for tokens not in the cache
             // (a stale scale), and the operand of the row-sum product: row 0 = 2^-8 / v_scale cut
             // to fp16, row 1 = the remainder, rows 2..15 zero; block A's tokens are the lane's
             // first four halves, block B's the other four
-            const int cache = wave == 2 ? cacheA : cacheB;
-            floatx4 vs;
+            const int cache = role == 2 ? cacheA : cacheB;
+            floatx4 lv;
             half4_t rr;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                vs[i] = FP8 ? ((i < cache) ? psc[i] * vnorm : 0.0f) : 1.0f;
+                const float vs = FP8 ? ((i < cache) ? psc[i] * vnorm : 0.0f) : 1.0f;
+                lv[i] = __builtin_amdgcn_logf(vs);                   // log2; -inf for an absent token
                 // (the hardware reciprocal, 1 ulp: far inside what the fp16 pair keeps)
-                const float r = fminf(vs[i] > 0.0f ? 0.00390625f * __builtin_amdgcn_rcpf(vs[i]) : 0.0f, 65504.0f);
+                const float r = fminf(vs > 0.0f ? 0.00390625f * __builtin_amdgcn_rcpf(vs) : 0.0f, 65504.0f);
                 const float hi = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, r) & 0xffffe000u);
                 rr[i] = n == 0 ? (half_t)hi : (n == 1 ? (half_t)(r - hi) : (half_t)0.0f);
             }
             if constexpr (FP8) {
-                if (n == 0) *reinterpret_cast<floatx4*>(st + St::kS + 64 * wave + 16 * grp) = vs;
+                if (n == 0) *reinterpret_cast<floatx4*>(st + St::kS + 64 * role + 16 * grp) = lv;
             }
-            *reinterpret_cast<half4_t*>(st + St::kR + 16 * lane + 8 * (wave - 2)) = rr;
+            *reinterpret_cast<half4_t*>(st + St::kR + 16 * lane + 8 * (role - 2)) = rr;
         }
     };
 
@@ -398,15 +429,15 @@ prefill_chunk_kernel(const PrefillArgs a)
         for (int c = 0; c < St::kVOps; ++c)
             vop[c] = *reinterpret_cast<const half8_t*>(st + St::kV + c * 1024 + 16 * lane);
         const half8_t rop = *reinterpret_cast<const half8_t*>(st + St::kR + 16 * lane);
-        floatx4 kscA, kscB, vsA, vsB;
+        floatx4 kscA, kscB, lvA, lvB;
         if constexpr (FP8) {
             kscA = *reinterpret_cast<const floatx4*>(st + St::kS + 16 * grp);
             kscB = *reinterpret_cast<const floatx4*>(st + St::kS + 64 + 16 * grp);
-            vsA = *reinterpret_cast<const floatx4*>(st + St::kS + 128 + 16 * grp);
-            vsB = *reinterpret_cast<const floatx4*>(st + St::kS + 192 + 16 * grp);
+            lvA = *reinterpret_cast<const floatx4*>(st + St::kS + 128 + 16 * grp);
+            lvB = *reinterpret_cast<const floatx4*>(st + St::kS + 192 + 16 * grp);
         } else {
             kscA = kscB = floatx4{a.scale_log2e, a.scale_log2e, a.scale_log2e, a.scale_log2e};
-            vsA = vsB = floatx4{1.f, 1.f, 1.f, 1.f};
+            lvA = lvB = floatx4{0.f, 0.f, 0.f, 0.f};              // log2 of a unit scale
         }
         const int baseA = 2 * gi * kBlock;
         const int tokA = baseA + 4 * grp;
@@ -415,11 +446,60 @@ prefill_chunk_kernel(const PrefillArgs a)
         floatx4 sA[NR], sB[NR];
 #pragma unroll
         for (int r = 0; r < NR; ++r) tile_scores<HEAD_DIM>(kA, kB, qop[r], sA[r], sB[r]);
+        // every tile's scores and maxima first, ONE (rare) branch for all of them, and then a
+        // single stretch of straight-line code in which the weights of one tile (vector ALU,
+        // exponentials) and the matrix products of the tile before it can run side by side
+        float z[NR][8], bm[NR];
+        if (tail) {
 #pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            const int visA = limit[r] - tokA;
-            tile_softmax_pv<HEAD_DIM>(sA[r], sB[r], vop, rop, kscA, kscB, vsA, vsB, m[r], lacc[r],
-                                      acc[r], tail, visA, hasB ? visA - kBlock : 0);
+            for (int r = 0; r < NR; ++r) {
+                const int visA = limit[r] - tokA;
+                bm[r] = tile_logits<true>(sA[r], sB[r], kscA, kscB, lvA, lvB, visA, hasB ? visA - kBlock : 0, z[r]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                bm[r] = tile_logits<false>(sA[r], sB[r], kscA, kscB, lvA, lvB, 0, 0, z[r]);
+        }
+        bool raise = false;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) raise = raise || bm[r] > m[r] + kRescaleSlack;
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {            // wave-uniform, rare
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                if (__builtin_amdgcn_ballot_w64(bm[r] > m[r] + kRescaleSlack) != 0)
+                    tile_raise<HEAD_DIM>(bm[r], m[r], lacc[r], acc[r]);
+        }
+        if constexpr (NR == 2) {
+            // tile 0's weights; then tile 0's products with tile 1's weights between them, a pair
+            // of exponentials to every two products (the matrix pipe and the vector ALU then work
+            // side by side: each order is pinned by a scheduling fence); then tile 1's products
+            const half8_t pop0 = tile_weights(z[0], m[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            const float mm1 = m[1] - kPShift;
+            half8_t pop1;
+            lacc[0] = mfma_16x16x32(rop, pop0, lacc[0]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int c = 2 * i; c < 2 * i + 2; ++c)
+                    if (c < HEAD_DIM / 16) acc[0][c] = mfma_16x16x32(vop[c], pop0, acc[0][c]);
+                const half2_t h = __builtin_bit_cast(
+                    half2_t, __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(z[1][2 * i] - mm1),
+                                                        __builtin_amdgcn_exp2f(z[1][2 * i + 1] - mm1)));
+                pop1[2 * i] = h.x;
+                pop1[2 * i + 1] = h.y;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int c = 8; c < HEAD_DIM / 16; ++c) acc[0][c] = mfma_16x16x32(vop[c], pop0, acc[0][c]);
+            tile_pv<HEAD_DIM>(vop, rop, pop1, lacc[1], acc[1]);
+        } else {
+            half8_t pop[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) pop[r] = tile_weights(z[r], m[r]);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) tile_pv<HEAD_DIM>(vop, rop, pop[r], lacc[r], acc[r]);
         }
     };
 
