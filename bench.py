@@ -36,6 +36,10 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 PMC_TRAFFIC = {
     # (workload, launch mode) -> counters of the kernel that `roofline` times, and the hash of the
     # kernel sources they were measured on (kernel_sources_sha16): quoted only while that matches
+    ("llama13b_gqa_fp8_decode", "fused"): {"fetch_kib": 36678.9, "fetch_scale": 2.0, "write_kib": 3152.1,
+                                           "write_scale": 1.0, "sources_sha16": "f67412d6569893ab"},
+    ("llama13b_gqa_fp8_decode", "plain"): {"fetch_kib": 36582.8, "fetch_scale": 2.0, "write_kib": 3152.1,
+                                           "write_scale": 1.0, "sources_sha16": "f67412d6569893ab"},
 }
 
 
@@ -165,6 +169,12 @@ def main():
         # the other configurations, each for at least 200 steps: kernel, roofline fraction, step
         steps = max(args.steps, 200)
         rows = [compact(result, "balanced")]
+        # the same step with the schedule derived inside every launch (coopt_paged_gqa_decode_step)
+        live = argparse.Namespace(**vars(args))
+        live.schedule = "live"
+        r = bench_decode(live, w, coopt, probe, torch, dev, plan, "balanced", steps, max(args.warmup, 20),
+                         cpu=False, stream=False)
+        rows.append(compact(r, "balanced, schedule derived in every launch"))
         for c, path in ((2, "balanced"), (3, "balanced"), (3, "partitioned")):
             del w
             torch.cuda.empty_cache()
