@@ -101,6 +101,11 @@ def parse_args():
                          "schemes: E4M3 / E5M2 codes with a per-token, per-block or static scale on the "
                          "long-context outlier workload (config 3 unless --config names another): "
                          "step time and attention error against an fp16 cache")
+    ap.add_argument("--probe-mb", type=float, default=0.0,
+                    help="with --op stream-read: read buffers of this many MB instead (as many distinct "
+                         "ones as fit 12 GB, at most 40, in rotation, launches back to back in HIP "
+                         "graphs like the decode launches): what ONE read-only launch of a decode "
+                         "launch's size reaches")
     ap.add_argument("--preroll", type=int, default=300,
                     help="untimed launches of the step before the warm-up steps, so that a short run "
                          "is not timed while the clocks are still coming up (disclosed in the line)")
@@ -148,7 +153,10 @@ def main():
         return
 
     if args.op == "stream-read":
-        print(json.dumps(stream_read_ceiling(probe, torch, dev, detail=True)), flush=True)
+        if args.probe_mb > 0:
+            print(json.dumps(stream_read_sized(probe, torch, dev, args.probe_mb)), flush=True)
+        else:
+            print(json.dumps(stream_read_ceiling(probe, torch, dev, detail=True)), flush=True)
         return
     if args.op == "schemes":
         w = workloads.make(3 if args.config is None else args.config)
@@ -537,6 +545,28 @@ def bench_schemes(args, w, coopt, torch, dev, plan):
             "reference": "the same step over an fp16 cache (this library's fp16 path), rms of its rows %.4f" % ref_rms,
             "static_scale_calibration": "absmax over the first %d tokens of sequence 0, per KV head, / largest code" % calib,
             "method": {"codes": "e4m3", "scale": "token"}, "schemes": table}
+
+
+def stream_read_sized(probe, torch, dev, mb):
+    """The read-only probe over buffers of `mb` MB, timed like a decode launch: distinct buffers in
+    rotation (so that the memory-side cache cannot serve them), launches back to back in HIP
+    graphs between two events, the inter-launch gap included."""
+    n = int(mb * 1e6) // 4096 * 4096
+    layers = max(2, min(40, int(12e9 // n)))
+    bufs = [torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(layers)]
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    shapes = {}
+    for wgs in (256, 512, 1024, 2048, 4096, 8192):
+        def fn(i):
+            probe.stream_read_probe(bufs[i % layers], wgs, sink)
+        graph_timed(torch, fn, 300, layers)
+        us = graph_timed(torch, fn, 1000, layers) * 1e3
+        shapes[wgs] = {"us_per_launch": round(us, 2), "gbs": round(n / us / 1e3, 1)}
+    best = min(shapes, key=lambda k: shapes[k]["us_per_launch"])
+    return {"metric": "read-only launch of %.1f MB (coopt_stream_read_probe), HIP-graph timing" % mb,
+            "bytes": n, "buffers_rotated": layers, "launches_timed": 1000,
+            "best_workgroups": best, "us_per_launch": shapes[best]["us_per_launch"], "gbs": shapes[best]["gbs"],
+            "workgroups_of_256_lanes": shapes}
 
 
 def stream_read_ceiling(coopt, torch, dev, detail=False):      # `coopt`: the probe's binding
