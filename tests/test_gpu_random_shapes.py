@@ -2,7 +2,7 @@
 workspace, from a prepared schedule, the fused step with some sequences appending nothing, fixed
 partitions + reduce), the dequantising gather (bit-exact) and chunked prefill with a different
 chunk length per sequence, each against the oracle on the same seeded inputs.  Head counts, head
-size, cache type, length mix, pool size and decode plan are all drawn from the seed, and the seed is
+size, cache type (E4M3, E5M2, fp16), length mix, pool size and decode plan are all drawn from the seed, and the seed is
 in every failure message."""
 import numpy as np
 import pytest
@@ -52,7 +52,7 @@ def _same_bytes(got, want, what):
 def _decode_case(orc, seed):
     rng = np.random.default_rng(seed)
     d = int(rng.choice([64, 128]))
-    kv = str(rng.choice(["e4m3", "fp16"]))
+    kv = str(rng.choice(["e4m3", "fp16", "e5m2"]))
     H_k = int(rng.choice([1, 2, 3, 4, 8]))
     H_q = H_k * int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
     S = int(rng.integers(1, 40))
@@ -67,8 +67,9 @@ def _decode_case(orc, seed):
     what = f"seed={seed} d={d} kv={kv} heads={H_q}/{H_k} S={S} cap={cap} NB={NB} plan={plan}"
     _set_plan(plan)
     cache = oracle_fill(orc, w)
+    fmt = "e5m2" if kv == "e5m2" else "e4m3"
     ref = orc.paged_gqa_decode(w.q, *cache, w.block_tables, w.context_lens, H_q=H_q, H_k=H_k, d=d,
-                               B=16, softmax_scale=w.softmax_scale)
+                               B=16, softmax_scale=w.softmax_scale, fmt=fmt)
     shape = shape_of(w)
     ws = torch.empty(max(16, planned.decode_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
     q, bt, dl = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens)
@@ -132,7 +133,7 @@ def _decode_case(orc, seed):
         s = int(rng.integers(0, S))
         lo = int(rng.integers(0, lens[s]))
         hi = int(rng.integers(lo, lens[s] + 1))
-        k_ref, v_ref = orc.gather_cached_kv(*cache, w.block_tables, s, lo, hi, H_k=H_k, d=d, B=16)
+        k_ref, v_ref = orc.gather_cached_kv(*cache, w.block_tables, s, lo, hi, H_k=H_k, d=d, B=16, fmt=fmt)
         k_out = torch.full((hi - lo + 2, H_k, d), 7.0, dtype=torch.float16, device="cuda")
         v_out = torch.full_like(k_out, 7.0)
         coopt.gather_cached_kv(*full, bt, s, lo, hi, k_out[1:-1], v_out[1:-1], shape)
@@ -147,7 +148,7 @@ def _decode_case(orc, seed):
 def _prefill_case(orc, seed):
     rng = np.random.default_rng(seed)
     d = int(rng.choice([64, 128]))
-    kv = str(rng.choice(["e4m3", "fp16"]))
+    kv = str(rng.choice(["e4m3", "fp16", "e5m2"]))
     H_k = int(rng.choice([1, 2, 3, 8]))
     H_q = H_k * int(rng.choice([1, 2, 4, 5, 8]))
     S = int(rng.integers(1, 6))
@@ -169,7 +170,8 @@ def _prefill_case(orc, seed):
     q = rng.standard_normal((rows, H_q, d), dtype=np.float32).astype(np.float16)
     cache = oracle_fill(orc, w)
     ref = orc.paged_gqa_prefill_chunk(q, *cache, w.block_tables, context_lens, query_start, H_q=H_q,
-                                      H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale)
+                                      H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale,
+                                      fmt="e5m2" if kv == "e5m2" else "e4m3")
     out = torch.full((rows, H_q, d), -7.0, dtype=torch.float16, device="cuda")
     coopt.paged_gqa_prefill_chunk(dev(q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables),
                                   dev(context_lens), dev(query_start), rows, max(chunk), out, shape_of(w))
