@@ -313,9 +313,11 @@ prefill_chunk_kernel(const PrefillArgs a)
     floatx4 pscs[kOwn];
     // The four producer roles of a team -- 0: K of block A, 1: K of block B, 2 and 3: the two halves
     // of the V pieces of both blocks (and the v_scale work of block A, B).  A V role costs twice a
-    // K role (890 against 440 cycles per group), but rotating the roles over the team's waves from
-    // group to group, which evens the waves out, made the whole kernel 3 % slower, so they are fixed.
-    auto role_of = [&](int) { return wave; };
+    // K role (890 against 440 cycles per group).  The two teams take the roles crosswise: waves w
+    // and w + 4 share a SIMD, so with the second team's roles shifted by two every SIMD carries
+    // one K role and one V role (1 % faster than the same roles in both teams; shifts of one or
+    // three, and rotating the roles from group to group inside a team, were slower).
+    auto role_of = [&](int) { return (wave + 2 * team) & 3; };
     auto produce_issue = [&](int p, int blockA, int blockB, u32x4 (&pr)[NP], floatx4& psc) {
         const int role = role_of(p);
         const int vj0 = role == 2 ? 0 : NLH;               // first V piece of a V role
