@@ -447,6 +447,13 @@ def bench_decode(args, w, coopt, probe, torch, dev, plan, path, steps, warmup, c
         sr = stream_read_ceiling(probe, torch, dev)
         result["roofline"]["stream_read_gbs"] = sr["gbs"]
         result["roofline"]["frac_of_stream_read"] = round(achieved / sr["gbs"], 4)
+        # and what ONE read-only launch of this launch's own size reaches, timed the same way
+        del pools
+        pools = []
+        torch.cuda.empty_cache()
+        ro = stream_read_sized(probe, torch, dev, alg / 1e6)
+        result["roofline"]["read_only_launch_us"] = ro["us_per_launch"]
+        result["roofline"]["frac_of_read_only_launch"] = round(ro["us_per_launch"] / kern_us, 4)
     if cpu:
         base, ref = cpu_baseline(w, ab)
         result["cpu_baseline"] = base
