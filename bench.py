@@ -82,6 +82,9 @@ def parse_args():
                     help="decode through coopt_paged_gqa_decode (balanced split + merge) or through "
                          "coopt_paged_gqa_decode_partitioned + coopt_paged_gqa_reduce with the "
                          "workload's partition size (512 if it names none)")
+    ap.add_argument("--prefill-entry", choices=["workspace", "plain"], default="workspace",
+                    help="config 4: coopt_paged_gqa_prefill_chunk_ws (a workspace for the launch's last "
+                         "round) or coopt_paged_gqa_prefill_chunk")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
     ap.add_argument("--plan", type=str, default="",
                     help="decode plan fields in header order, comma separated (tuning)")
@@ -632,8 +635,21 @@ def bench_prefill(args, w, coopt, torch, dev, steps, warmup, cpu):
         pools.append((kc, vc, ks, vs))
     torch.cuda.synchronize()
 
-    def attend(i):
+    # The entry point with a workspace for the launch's last, partly filled round (its tiles then run
+    # as half-streams in full-size workgroups plus a merge); --prefill-entry plain times the one
+    # without (half-size workgroups for those tiles).
+    with_ws = args.prefill_entry == "workspace"
+    ws_bytes = coopt.prefill_workspace_bytes(shape, C) if with_ws else 0
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev) if with_ws else None
+
+    def attend_plain(i):
         coopt.paged_gqa_prefill_chunk(q, *pools[i % layers], bt, lens, qs, n_rows, C, out, shape)
+
+    def attend(i):
+        if with_ws:
+            coopt.paged_gqa_prefill_chunk_ws(q, *pools[i % layers], bt, lens, qs, n_rows, C, out, ws, shape)
+        else:
+            attend_plain(i)
 
     def step(i):
         coopt.kv_cache_write_fp8(k_new, v_new, s_new, *pools[i % layers], shape)
@@ -657,6 +673,9 @@ def bench_prefill(args, w, coopt, torch, dev, steps, warmup, cpu):
     step_ms = timed(step, steps)
     wall_ms = (time.perf_counter() - t0) * 1e3
     kern_ms = timed(attend, steps)
+    plain_ms = timed(attend_plain, steps) if with_ws else kern_ms
+    attend(0)                             # the rows the parity check reads come from the timed entry point
+    torch.cuda.synchronize()
     # 2 products of 2*d flops per (row, query head, visible token)
     pairs = sum(C * (int(t) - C) + C * (C + 1) // 2 for t in w.context_lens)
     flops = 4.0 * w.d * w.H_q * pairs
@@ -669,14 +688,21 @@ def bench_prefill(args, w, coopt, torch, dev, steps, warmup, cpu):
         "config": {"workload": w.name, "num_seqs": w.S, "q_heads": w.H_q, "kv_heads": w.H_k,
                    "head_dim": w.d, "block_size": w.B, "history_tokens": int(w.context_lens[0]) - C,
                    "chunk_tokens": C, "kv_pools_rotated": layers,
-                   "step": "kv_cache_write of the chunk + paged_gqa_prefill_chunk, one layer",
+                   "step": "kv_cache_write of the chunk + %s, one layer" %
+                           ("paged_gqa_prefill_chunk_ws" if with_ws else "paged_gqa_prefill_chunk"),
+                   "workspace_bytes": int(ws_bytes),
                    "launch": "eager"},
         "wall_ms_timed_region": round(wall_ms, 2),
-        "roofline": {"bound": "mfma", "kernel": "prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk: its two launches, full and half-size workgroups)",
+        "roofline": {"bound": "mfma",
+                     "kernel": ("prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk_ws: full workgroups, then the "
+                                "last tiles as half-streams in full workgroups, and the merge of the halves)")
+                     if with_ws else
+                     "prefill_chunk_kernel (coopt_paged_gqa_prefill_chunk: its two launches, full and half-size workgroups)",
                      "achieved": round(flops / kern_ms / 1e9, 1), "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(flops / kern_ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4),
                      "traffic": None, "algorithmic_flops_per_launch": flops,
-                     "kernel_ms_mean": round(kern_ms, 4)},
+                     "kernel_ms_mean": round(kern_ms, 4),
+                     "without_workspace_kernel_ms_mean": round(plain_ms, 4)},
     }
     if cpu:
         base, rows, ref = cpu_baseline_prefill(w, flops)

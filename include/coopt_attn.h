@@ -375,6 +375,31 @@ int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache, const void
                                   void* hip_stream);
 
 /*
+ * The same chunked prefill (Abstract: chunking of long sequences; Eq. 1 per row) with a workspace
+ * for the launch's last, partly filled round.  Where the tiles of a chunk do not fill a whole
+ * number of rounds of workgroups, coopt_paged_gqa_prefill_chunk runs the last tiles of every
+ * (sequence, KV head) pair in smaller workgroups; with a workspace they run in full-size
+ * workgroups that each stream one half of the pair's cache, leave (m, l, unnormalised sums) per
+ * tile and half in the workspace, and a merge launch combines the halves by the online-softmax
+ * rule (Opt-Pa Eq. 10).  Results agree with coopt_paged_gqa_prefill_chunk within the rounding of
+ * that merge (same tolerance against the definition); rows outside those tiles are the same bits.
+ *   workspace        device memory, at least coopt_prefill_workspace_bytes(shape, max_chunk_len)
+ *                    bytes (0 when the launch has no such round: then it may be NULL and the call
+ *                    is coopt_paged_gqa_prefill_chunk); contents on entry are ignored, on return
+ *                    they are scratch.  The caller owns it; calls that share it must not overlap.
+ *   workspace_bytes  its size; COOPT_ERR_WORKSPACE if too small, COOPT_ERR_NULL if needed and NULL
+ * Allocates nothing, synchronises nothing; three launches at most.
+ */
+size_t coopt_prefill_workspace_bytes(const coopt_shape* shape, int32_t max_chunk_len);
+int coopt_paged_gqa_prefill_chunk_ws(const void* q, const void* k_cache, const void* v_cache,
+                                     const float* k_scale, const float* v_scale,
+                                     const int32_t* block_tables, const int32_t* context_lens,
+                                     const int32_t* query_start, int32_t num_query_rows,
+                                     int32_t max_chunk_len, void* out, void* workspace,
+                                     size_t workspace_bytes, const coopt_shape* shape,
+                                     void* hip_stream);
+
+/*
  * Dequantising gather (the read half of Opt-KV, Eq. 6; the paper's gather_cached_kv): contiguous
  * fp16 K and V of logical tokens [tok_begin, tok_end) of sequence `seq`:
  *   k_out, v_out [tok_end - tok_begin][H_k][d] fp16, value = fp16(code * scale) (round to nearest

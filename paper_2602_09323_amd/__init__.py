@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     kv_cache_write_fp16, kv_cache_write_fp8, kv_cache_write_fp8_scaled, kv_cache_write_skipset, lib_path, load_library,
     make_decode_plan, paged_gqa_decode, paged_gqa_decode_merge, paged_gqa_decode_noalloc, paged_gqa_decode_partitioned,
     paged_gqa_decode_scheduled, paged_gqa_decode_split, paged_gqa_decode_step,
-    paged_gqa_prefill_chunk, paged_gqa_reduce, status_string)
+    paged_gqa_prefill_chunk, paged_gqa_prefill_chunk_ws, paged_gqa_reduce, prefill_workspace_bytes,
+    status_string)

@@ -36,6 +36,7 @@ EXPORTS = [
     "coopt_gather_cached_kv", "coopt_decode_schedule_bytes", "coopt_decode_schedule_prepare",
     "coopt_paged_gqa_decode_scheduled", "coopt_status_string",
     "coopt_paged_gqa_decode_noalloc", "coopt_decode_builtin_workspace_bytes",
+    "coopt_paged_gqa_prefill_chunk_ws", "coopt_prefill_workspace_bytes",
 ]
 
 
@@ -93,6 +94,10 @@ def load_library():
                                                            i32, plp, shp, vp]
         lib.coopt_paged_gqa_reduce.argtypes = [vp, vp, vp, vp, i32, i32, vp, shp, vp]
         lib.coopt_paged_gqa_prefill_chunk.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, shp, vp]
+        lib.coopt_paged_gqa_prefill_chunk_ws.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz,
+                                                         shp, vp]
+        lib.coopt_prefill_workspace_bytes.argtypes = [shp, i32]
+        lib.coopt_prefill_workspace_bytes.restype = sz
         lib.coopt_gather_cached_kv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, shp, vp]
         lib.coopt_decode_schedule_bytes.argtypes = [shp, plp]
         lib.coopt_decode_schedule_bytes.restype = sz
@@ -106,6 +111,7 @@ def load_library():
         lib.coopt_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
             if name not in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes",
+                            "coopt_prefill_workspace_bytes",
                             "coopt_status_string", "coopt_default_decode_plan",
                             "coopt_decode_builtin_workspace_bytes"):
                 getattr(lib, name).restype = ctypes.c_int
@@ -387,6 +393,32 @@ def paged_gqa_prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables,
         _dev(query_start, f"{what}: query_start", dtype=_i32(), min_bytes=z["lens"] + 4),
         int(num_query_rows), int(max_chunk_len),
         _dev(out, f"{what}: out", elem=2, min_bytes=rows_bytes), ctypes.byref(shape), _stream(stream))
+
+
+def prefill_workspace_bytes(shape: Shape, max_chunk_len: int) -> int:
+    return int(load_library().coopt_prefill_workspace_bytes(ctypes.byref(shape), int(max_chunk_len)))
+
+
+def paged_gqa_prefill_chunk_ws(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens,
+                               query_start, num_query_rows: int, max_chunk_len: int, out, workspace,
+                               shape: Shape, stream=None) -> None:
+    """workspace: a device buffer of at least prefill_workspace_bytes(shape, max_chunk_len) bytes
+    (None where that is 0)."""
+    what = "paged_gqa_prefill_chunk_ws"
+    z = _sizes(shape)
+    rows_bytes = int(num_query_rows) * shape.num_q_heads * shape.head_dim * 2
+    need = prefill_workspace_bytes(shape, max_chunk_len)
+    pws, nws = (None, ctypes.c_size_t(0)) if workspace is None else (
+        _dev(workspace, f"{what}: workspace", min_bytes=need), ctypes.c_size_t(_nbytes(workspace)))
+    _call("coopt_paged_gqa_prefill_chunk_ws",
+          _dev(q, f"{what}: q", elem=2, min_bytes=rows_bytes),
+          *_cache_ptrs(k_cache, v_cache, k_scale, v_scale, shape),
+          _dev(block_tables, f"{what}: block_tables", dtype=_i32(), min_bytes=z["tables"]),
+          _dev(context_lens, f"{what}: context_lens", dtype=_i32(), min_bytes=z["lens"]),
+          _dev(query_start, f"{what}: query_start", dtype=_i32(), min_bytes=z["lens"] + 4),
+          int(num_query_rows), int(max_chunk_len),
+          _dev(out, f"{what}: out", elem=2, min_bytes=rows_bytes), pws, nws, ctypes.byref(shape),
+          _stream(stream))
 
 
 def decode_schedule_bytes(shape: Shape, plan: Optional[DecodePlan] = None) -> int:

@@ -20,6 +20,11 @@
 //   * Workgroup ids are dealt to the 8 XCDs round-robin, so the mapping puts all workgroups of a
 //     pair on ONE XCD: the pair's 2 MB of cache are fetched from HBM once and re-read from that
 //     XCD's L2 by the pair's other workgroups.
+//   * A launch runs in rounds of one workgroup per CU.  The tiles of a last round that would be
+//     mostly empty go to a second launch: of half-size workgroups, or -- when the caller brings a
+//     workspace -- of full-size workgroups that each stream one half of the pair's stages and
+//     leave (m, l, unnormalised sums) per tile, which a merge launch combines (Opt-Pa Eq. 10 over
+//     two parts).
 // The only difference from decode in the arithmetic is that the visible-token limit is per column
 // (causal).
 #include "attn_tile.hpp"
@@ -41,12 +46,19 @@ struct PrefillArgs {
     int32_t tile_base;        // this launch covers tiles [tile_base, tile_limit) of every pair
     int32_t tile_limit;
     float scale_log2e;
+    // split launch (the last tiles of every pair, two workgroups per 16 tiles: the first streams
+    // the first half of the pair's stages, the second the rest; each leaves per tile and half
+    // 16 x (m, l) and the 16 x HEAD_DIM unnormalised sums in `part`, which a merge launch combines)
+    float* part;
+    int32_t split;            // 0: whole streams, rows written to out;  1: half streams, partials
+    int32_t tail_cap;         // tiles per pair the split launch covers (sizes `part`)
 };
 
 constexpr int kPrefillWaves = 8;                // two teams of four producer roles
 constexpr int kPrefillGroupsPerStage = 4;      // two-block groups between two barriers
 // Groups of a stage produced by the first team (waves 0-3); the second team takes the rest.
 constexpr int kPrefillFirstTeamGroups = 3;
+constexpr float kNoReference = -1.0e30f;        // a running reference below every score
 constexpr int kPrefillCUs = 256;               // MI355X: the launch shape is planned for its CU count
 
 // Byte offsets inside one LDS stage (one group = blocks A and B of one KV head).
@@ -131,7 +143,7 @@ __device__ __forceinline__ void tile_raise(float bm, float& m, floatx4& lacc, fl
     float nm = fmaxf(bm, __shfl_xor(bm, 16));
     nm = fmaxf(nm, __shfl_xor(nm, 32));
     nm = fmaxf(nm, m);
-    const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = -inf at the start gives 0
+    const float alpha = __builtin_amdgcn_exp2f(m - nm);   // m = kNoReference at the start gives 0
     lacc *= alpha;
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) acc[c] *= alpha;
@@ -193,7 +205,9 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int tiles_per_head = (C + 15) / 16;
     const int total_tiles = a.G * tiles_per_head;
     const int end_tile = min(total_tiles, a.tile_limit);
-    const int wg_first_tile = a.tile_base + (k8 % a.wgs_per_pair) * (kPrefillWaves * NR);
+    const int in_pair = k8 % a.wgs_per_pair;
+    const int half = a.split ? (in_pair & 1) : 0;
+    const int wg_first_tile = a.tile_base + (a.split ? in_pair >> 1 : in_pair) * (kPrefillWaves * NR);
     if (wg_first_tile >= end_tile) return;             // the whole workgroup leaves together
     const int first_tile = wg_first_tile + wave_id * NR;
     const bool active = first_tile < end_tile;         // a wave without tiles still produces
@@ -278,7 +292,10 @@ prefill_chunk_kernel(const PrefillArgs a)
     floatx4 acc[NR][HEAD_DIM / 16];
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-        m[r] = -INFINITY;
+        // (finite, not -inf: a workgroup that streams the second half of a pair's stages meets
+        // columns that see none of a group's tokens before any they do see, and the weights
+        // exp2(z - m) of such a column must come out as exp2(-inf) = 0, not exp2(-inf + inf))
+        m[r] = kNoReference;
         lacc[r] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < HEAD_DIM / 16; ++c) acc[r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -505,38 +522,43 @@ prefill_chunk_kernel(const PrefillArgs a)
         }
     };
 
-    // A stage holds GPS consecutive groups; one barrier per stage.
+    // A stage holds GPS consecutive groups; one barrier per stage.  The workgroup streams stages
+    // s_lo .. s_hi-1: all of them, or one half of them in a split launch (an empty half leaves
+    // the neutral partial m = kNoReference, l = 0).
     const int num_stages = (num_groups + GPS - 1) / GPS;
+    const int s_lo = (a.split && half == 1) ? num_stages / 2 : 0;
+    const int s_hi = (a.split && half == 0) ? num_stages / 2 : num_stages;
+    const int g_end = min(num_groups, s_hi * GPS);            // groups below this one are mine
     auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
     // (a wave keeps registers for the sub-groups of its own team)
-    uint32_t ids = load_ids(0);
+    uint32_t ids = load_ids(s_lo);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (owner(sub) == team && sub < num_groups)
-            produce_issue(sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1), prs[own_index(sub)],
-                          pscs[own_index(sub)]);
-    ids = load_ids(1);
-    uint32_t ids_next = load_ids(2);
+        if (owner(sub) == team && s_lo * GPS + sub < g_end)
+            produce_issue(s_lo * GPS + sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1),
+                          prs[own_index(sub)], pscs[own_index(sub)]);
+    ids = load_ids(s_lo + 1);
+    uint32_t ids_next = load_ids(s_lo + 2);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (owner(sub) == team && sub < num_groups)
-            produce_store(sub, slot(0, sub), prs[own_index(sub)], pscs[own_index(sub)]);
+        if (owner(sub) == team && s_lo * GPS + sub < g_end)
+            produce_store(s_lo * GPS + sub, slot(s_lo, sub), prs[own_index(sub)], pscs[own_index(sub)]);
 #pragma unroll
     for (int sub = 0; sub < GPS; ++sub)
-        if (owner(sub) == team && GPS + sub < num_groups)
-            produce_issue(GPS + sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1),
+        if (owner(sub) == team && (s_lo + 1) * GPS + sub < g_end)
+            produce_issue((s_lo + 1) * GPS + sub, id_of(ids, own_index(sub), 0), id_of(ids, own_index(sub), 1),
                           prs[own_index(sub)], pscs[own_index(sub)]);
     __syncthreads();
-    for (int si = 0; si < num_stages; ++si) {
+    for (int si = s_lo; si < s_hi; ++si) {
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int gi = si * GPS + sub;
-            if (gi < num_groups && 2 * gi * kBlock < my_max) consume(slot(si, sub), gi);
+            if (gi < g_end && 2 * gi * kBlock < my_max) consume(slot(si, sub), gi);
         }
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int gn = (si + 1) * GPS + sub;
-            if (owner(sub) == team && gn < num_groups)
+            if (owner(sub) == team && gn < g_end)
                 produce_store(gn, slot(si + 1, sub), prs[own_index(sub)], pscs[own_index(sub)]);
         }
         // the numbers fetched a stage ago go to scalar registers before anything new is issued,
@@ -553,7 +575,7 @@ prefill_chunk_kernel(const PrefillArgs a)
 #pragma unroll
         for (int sub = 0; sub < GPS; ++sub) {
             const int g2 = (si + 2) * GPS + sub;
-            if (owner(sub) == team && g2 < num_groups)
+            if (owner(sub) == team && g2 < g_end)
                 produce_issue(g2, blk[own_index(sub)][0], blk[own_index(sub)][1], prs[own_index(sub)],
                               pscs[own_index(sub)]);
         }
@@ -567,6 +589,21 @@ prefill_chunk_kernel(const PrefillArgs a)
         // column n's sum sits in rows 0 and 1 of lacc: lane (n, 0), registers 0 and 1
         const float L = __shfl(lacc[r][0] + lacc[r][1], n) * 256.0f;
         // (the 2^kPShift common to acc and l cancels; the normaliser of the v_scales is in acc alone)
+        if (a.split) {
+            // this half's share of the tile: reference, row sum and unnormalised sums per column
+            if (first_tile + r < end_tile) {
+                float* dst = a.part + (((size_t)pair * a.tail_cap + (first_tile + r - a.tile_base)) * 2 + half) *
+                                          (16 * (HEAD_DIM + 2));
+                if (grp == 0) {
+                    dst[n] = m[r];
+                    dst[16 + n] = L;
+                }
+#pragma unroll
+                for (int c = 0; c < HEAD_DIM / 16; ++c)
+                    *reinterpret_cast<floatx4*>(dst + 32 + n * HEAD_DIM + 16 * c + 4 * grp) = acc[r][c] * vdenorm;
+            }
+            continue;
+        }
         const float inv = (1.0f / L) * vdenorm;
         const int row = row0[r] + n;
         if (first_tile + r < end_tile && row < C) {
@@ -582,9 +619,101 @@ prefill_chunk_kernel(const PrefillArgs a)
     }
 }
 
+// Combines the two halves a split launch left for every tile: with M = max(m_0, m_1) and
+// e_h = 2^(m_h - M), row = (A_0 e_0 + A_1 e_1) / (l_0 e_0 + l_1 e_1) (the merge rule of the online
+// softmax, Opt-Pa Eq. 10, over two parts).  One wavefront per tile, lane (n, grp) as in the kernel.
+template <int HEAD_DIM>
+__global__ void __launch_bounds__(256)
+prefill_split_merge_kernel(const PrefillArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, grp = lane >> 4;
+    const long long id = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);      // pair * tail_cap + tile
+    if (id >= (long long)a.num_pairs * a.tail_cap) return;
+    const int pair = (int)(id / a.tail_cap);
+    const int tile = a.tile_base + (int)(id - (long long)pair * a.tail_cap);
+    const int seq = pair / a.H_k;
+    const int g = pair - seq * a.H_k;
+    const int qs = a.query_start[seq];
+    const int C = a.query_start[seq + 1] - qs;
+    if (C <= 0) return;
+    const int tiles_per_head = (C + 15) / 16;
+    if (tile >= a.G * tiles_per_head) return;
+    const int hh = tile / tiles_per_head;
+    const int row = (tile - hh * tiles_per_head) * 16 + n;
+    if (row >= C) return;
+    const float* p0 = a.part + (size_t)id * 2 * (16 * (HEAD_DIM + 2));
+    const float* p1 = p0 + 16 * (HEAD_DIM + 2);
+    const float m0 = p0[n], m1 = p1[n];
+    const float M = fmaxf(m0, m1);        // a row sees at least one token: not both kNoReference
+    const float e0 = __builtin_amdgcn_exp2f(m0 - M), e1 = __builtin_amdgcn_exp2f(m1 - M);
+    const float inv = 1.0f / (p0[16 + n] * e0 + p1[16 + n] * e1);
+    half_t* dst = a.out + ((size_t)(qs + row) * a.H_q + g * a.G + hh) * HEAD_DIM + 4 * grp;
+#pragma unroll
+    for (int c = 0; c < HEAD_DIM / 16; ++c) {
+        const floatx4 x0 = *reinterpret_cast<const floatx4*>(p0 + 32 + n * HEAD_DIM + 16 * c + 4 * grp);
+        const floatx4 x1 = *reinterpret_cast<const floatx4*>(p1 + 32 + n * HEAD_DIM + 16 * c + 4 * grp);
+        half4_t h;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) h[i] = (half_t)((x0[i] * e0 + x1[i] * e1) * inv);
+        *reinterpret_cast<half4_t*>(dst + 16 * c) = h;
+    }
+}
+
+// How the tiles of every pair are dealt to launches.  One workgroup (8 waves, 2 tiles each) fills
+// a CU, so a launch runs in rounds of one workgroup per CU, and a last round that is mostly empty
+// costs a full one.  Where that happens the last tiles of every pair go to a second launch: of
+// half-size workgroups (one tile per wave), which takes about 0.65-0.8 of a round -- or, when the
+// caller brings a workspace, of full-size workgroups that each stream HALF of the pair's stages
+// (half a round; the halves are combined by prefill_split_merge_kernel).
+struct PrefillLaunchPlan {
+    int tiles, pairs8, a_per_pair, b_per_pair, rest;
+    PrefillLaunchPlan(const coopt_shape* sh, int max_chunk_len)
+    {
+        const int G = sh->num_q_heads / sh->num_kv_heads;
+        tiles = G * ((max_chunk_len + 15) / 16);
+        pairs8 = (sh->num_seqs * sh->num_kv_heads + 7) / 8 * 8;
+        const int full_per_pair = (tiles + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves);
+        a_per_pair = full_per_pair;
+        b_per_pair = 0;
+        rest = 0;
+        auto rounds = [](long long wgs) { return (double)((wgs + kPrefillCUs - 1) / kPrefillCUs); };
+        const long long W = (long long)pairs8 * full_per_pair;
+        const int cand = (int)((W / kPrefillCUs) * kPrefillCUs / pairs8);   // full rounds only
+        if (cand >= 1 && cand < full_per_pair) {
+            const int r = tiles - cand * 2 * kPrefillWaves;
+            const int small = (r + kPrefillWaves - 1) / kPrefillWaves;
+            const double split = rounds((long long)pairs8 * cand) + 0.65 * rounds((long long)pairs8 * small);
+            if (split < rounds(W)) {
+                a_per_pair = cand;
+                b_per_pair = small;
+                rest = r;
+            }
+        }
+    }
+    // workgroups per pair of the split form of the second launch
+    int split_per_pair() const { return 2 * ((rest + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves)); }
+    size_t workspace_bytes(const coopt_shape* sh) const
+    {
+        if (!b_per_pair) return 0;
+        return (size_t)sh->num_seqs * sh->num_kv_heads * rest * 2 * 16 * (sh->head_dim + 2) * sizeof(float);
+    }
+};
+
 }  // namespace coopt
 
 using namespace coopt;
+
+extern "C" size_t coopt_prefill_workspace_bytes(const coopt_shape* sh, int32_t max_chunk_len)
+{
+    if (check_shape(sh) != COOPT_OK || max_chunk_len <= 0 || sh->num_seqs == 0) return 0;
+    return PrefillLaunchPlan(sh, max_chunk_len).workspace_bytes(sh);
+}
+
+static int prefill_chunk(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                         const float* v_scale, const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* query_start, int32_t num_query_rows, int32_t max_chunk_len,
+                         void* out, void* workspace, const coopt_shape* sh, void* hip_stream);
 
 extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache, const void* v_cache,
                                              const float* k_scale, const float* v_scale,
@@ -593,6 +722,36 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
                                              const int32_t* query_start, int32_t num_query_rows,
                                              int32_t max_chunk_len, void* out,
                                              const coopt_shape* sh, void* hip_stream)
+{
+    return prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, query_start,
+                         num_query_rows, max_chunk_len, out, nullptr, sh, hip_stream);
+}
+
+extern "C" int coopt_paged_gqa_prefill_chunk_ws(const void* q, const void* k_cache, const void* v_cache,
+                                                const float* k_scale, const float* v_scale,
+                                                const int32_t* block_tables,
+                                                const int32_t* context_lens,
+                                                const int32_t* query_start, int32_t num_query_rows,
+                                                int32_t max_chunk_len, void* out, void* workspace,
+                                                size_t workspace_bytes, const coopt_shape* sh,
+                                                void* hip_stream)
+{
+    int st = check_shape(sh);
+    if (st != COOPT_OK) return st;
+    if (max_chunk_len > 0 && sh->num_seqs > 0) {
+        const size_t need = PrefillLaunchPlan(sh, max_chunk_len).workspace_bytes(sh);
+        if (need > 0 && !workspace) return COOPT_ERR_NULL;
+        if (workspace_bytes < need) return COOPT_ERR_WORKSPACE;
+        if (need == 0) workspace = nullptr;
+    }
+    return prefill_chunk(q, k_cache, v_cache, k_scale, v_scale, block_tables, context_lens, query_start,
+                         num_query_rows, max_chunk_len, out, workspace, sh, hip_stream);
+}
+
+static int prefill_chunk(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
+                         const float* v_scale, const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* query_start, int32_t num_query_rows, int32_t max_chunk_len,
+                         void* out, void* workspace, const coopt_shape* sh, void* hip_stream)
 {
     int st = check_shape(sh);
     if (st != COOPT_OK) return st;
@@ -615,30 +774,13 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
     a.max_blocks = sh->max_blocks_per_seq;
     a.pool_tiles = sh->num_blocks * sh->num_kv_heads;
     a.scale_log2e = sh->softmax_scale * kLog2e;
-
-    // One workgroup (8 waves, 2 tiles each) fills a CU, so the launch runs in rounds of one
-    // workgroup per CU, and a last round that is mostly empty costs a full one.  Where that
-    // happens, the last tiles of every pair go to a second launch of half-size workgroups (one
-    // tile per wave), which takes about 0.65 of a round.
-    const int tiles = a.G * ((max_chunk_len + 15) / 16);
     a.num_pairs = sh->num_seqs * sh->num_kv_heads;
-    const int pairs8 = (a.num_pairs + 7) / 8 * 8;
-    const int full_per_pair = (tiles + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves);
-    int a_per_pair = full_per_pair, b_per_pair = 0;
-    {
-        auto rounds = [](long long wgs) { return (double)((wgs + kPrefillCUs - 1) / kPrefillCUs); };
-        const long long W = (long long)pairs8 * full_per_pair;
-        const int cand = (int)((W / kPrefillCUs) * kPrefillCUs / pairs8);   // full rounds only
-        if (cand >= 1 && cand < full_per_pair) {
-            const int rest = tiles - cand * 2 * kPrefillWaves;
-            const int small = (rest + kPrefillWaves - 1) / kPrefillWaves;
-            const double split = rounds((long long)pairs8 * cand) + 0.65 * rounds((long long)pairs8 * small);
-            if (split < rounds(W)) {
-                a_per_pair = cand;
-                b_per_pair = small;
-            }
-        }
-    }
+
+    const PrefillLaunchPlan lp(sh, max_chunk_len);
+    const int pairs8 = lp.pairs8, a_per_pair = lp.a_per_pair, b_per_pair = lp.b_per_pair;
+    const bool split = b_per_pair && workspace;
+    const int split_per_pair = lp.split_per_pair();
+    if ((long long)pairs8 * (a_per_pair + b_per_pair + split_per_pair) > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     const dim3 block(64 * kPrefillWaves);
     const size_t lds = 2 * kPrefillGroupsPerStage *
                        (size_t)(sh->head_dim == 128 ? PrefillStage<128>::kBytes : PrefillStage<64>::kBytes);
@@ -654,12 +796,23 @@ extern "C" int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache,
         if (b_per_pair) {                                                                           \
             a.tile_base = a.tile_limit;                                                             \
             a.tile_limit = 0x7fffffff;                                                              \
+        }                                                                                           \
+        if (split) {                                                                                \
+            a.wgs_per_pair = split_per_pair;                                                        \
+            a.part = (float*)workspace;                                                             \
+            a.split = 1;                                                                            \
+            a.tail_cap = lp.rest;                                                                   \
+            hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 2, BIG>),                               \
+                               dim3((unsigned)((long long)pairs8 * split_per_pair)), block, lds, stream, a); \
+            const long long waves = (long long)a.num_pairs * lp.rest;                               \
+            hipLaunchKernelGGL((prefill_split_merge_kernel<D>), dim3((unsigned)((waves + 3) / 4)),   \
+                               dim3(256), 0, stream, a);                                            \
+        } else if (b_per_pair) {                                                                    \
             a.wgs_per_pair = b_per_pair;                                                            \
             hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 1, BIG>),                               \
                                dim3((unsigned)((long long)pairs8 * b_per_pair)), block, lds, stream, a); \
         }                                                                                           \
     } while (0)
-    if ((long long)pairs8 * full_per_pair > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     if (sh->kv_dtype == COOPT_KV_E4M3) {
         if (sh->head_dim == 128) { if (big) COOPT_PREFILL(128, COOPT_KV_E4M3, true); else COOPT_PREFILL(128, COOPT_KV_E4M3, false); }
         else { if (big) COOPT_PREFILL(64, COOPT_KV_E4M3, true); else COOPT_PREFILL(64, COOPT_KV_E4M3, false); }

@@ -11,14 +11,27 @@ from helpers import oracle_fill
 pytestmark = pytest.mark.gpu
 
 
-def _hip_prefill(w, dcache, lens=None, query_start=None, max_chunk=None):
+def _prefill_call(with_workspace, q, dcache, bt, dl, qs, rows, max_chunk, out, shape):
+    """The plain entry point, or the one that takes a workspace for the launch's last round (the
+    workspace poisoned with NaN: whatever the merge reads must have been written by this call).
+    Returns the workspace size the shape asks for."""
+    if not with_workspace:
+        coopt.paged_gqa_prefill_chunk(q, *dcache, bt, dl, qs, rows, max_chunk, out, shape)
+        return 0
+    need = coopt.prefill_workspace_bytes(shape, max_chunk)
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda") if need else None
+    coopt.paged_gqa_prefill_chunk_ws(q, *dcache, bt, dl, qs, rows, max_chunk, out, ws, shape)
+    return need
+
+
+def _hip_prefill(w, dcache, lens=None, query_start=None, max_chunk=None, with_workspace=False):
     shape = shape_of(w)
     qs = w.query_start if query_start is None else query_start
     n_rows = int(qs[-1])
     out = torch.full((n_rows, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.paged_gqa_prefill_chunk(dev(w.q.view(np.uint16)), *dcache, dev(w.block_tables),
-                                  dev(w.context_lens if lens is None else lens), dev(qs), n_rows,
-                                  w.new_per_seq if max_chunk is None else max_chunk, out, shape)
+    _prefill_call(with_workspace, dev(w.q.view(np.uint16)), dcache, dev(w.block_tables),
+                  dev(w.context_lens if lens is None else lens), dev(qs), n_rows,
+                  w.new_per_seq if max_chunk is None else max_chunk, out, shape)
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64)
 
@@ -51,11 +64,16 @@ def test_chunk_written_on_device_then_attended(oracle_mod):
     assert_close(_hip_prefill(w, devc), ref, "cfg4/16")
 
 
-@pytest.mark.parametrize("kv_dtype,chunks", [("e4m3", [512] * 8), ("fp16", [512, 500, 17, 512, 1, 300, 512, 496])])
-def test_two_launch_split_every_row(oracle_mod, kv_dtype, chunks):
+@pytest.mark.parametrize("with_workspace", [False, True])
+@pytest.mark.parametrize("kv_dtype,chunks", [("e4m3", [512] * 8), ("fp16", [512, 500, 17, 512, 1, 300, 512, 496]),
+                                             ("e5m2", [512, 40, 512, 512, 130, 512, 3, 512])])
+def test_two_launch_split_every_row(oracle_mod, kv_dtype, chunks, with_workspace):
     """As many workgroups as the full configuration (64 pairs, up to 160 tiles each), so the entry
     point splits the work into its two launches, over a short history so that the oracle can check
-    every row; the second case has a different chunk length per sequence."""
+    every row; the other cases have a different chunk length per sequence.  With a workspace the
+    second launch streams half of every pair's stages per workgroup and a third one merges the
+    halves (histories of 0 to 250 tokens: halves of one to five stages, and sequences whose last
+    tiles do not exist)."""
     S, H_q, H_k, d = len(chunks), 40, 8, 128
     history = [48, 0, 100, 16, 33, 64, 7, 250]
     lens = [h + c for h, c in zip(history, chunks)]
@@ -67,11 +85,13 @@ def test_two_launch_split_every_row(oracle_mod, kv_dtype, chunks):
     q = np.random.default_rng(78).standard_normal((rows, H_q, d), dtype=np.float32).astype(np.float16)
     cache = oracle_fill(oracle_mod, w)
     ref = oracle_mod.paged_gqa_prefill_chunk(q, *cache, w.block_tables, w.context_lens, query_start, H_q=H_q,
-                                             H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale)
+                                             H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale,
+                                             fmt="e5m2" if kv_dtype == "e5m2" else "e4m3")
     out = torch.full((rows, H_q, d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.paged_gqa_prefill_chunk(dev(q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables),
-                                  dev(w.context_lens), dev(query_start), rows, max(chunks), out, shape_of(w))
+    need = _prefill_call(with_workspace, dev(q.view(np.uint16)), cache_to_dev(cache), dev(w.block_tables),
+                         dev(w.context_lens), dev(query_start), rows, max(chunks), out, shape_of(w))
     torch.cuda.synchronize()
+    assert not with_workspace or need > 0          # this shape does have a partly filled last round
     assert_close(out.cpu().numpy().astype(np.float64), ref, f"two launches {kv_dtype} {chunks}")
 
 
@@ -83,18 +103,29 @@ def test_chunked_prefill_full_size(oracle_mod, record_property):
     w = workloads.make(4)
     print(f"full cfg4: tokens={w.total_tokens}", flush=True)
     cache = oracle_fill(oracle_mod, w)
-    got = _hip_prefill(w, cache_to_dev(cache))
-    assert np.isfinite(got).all()
+    dcache = cache_to_dev(cache)
+    got = _hip_prefill(w, dcache)
+    got_ws = _hip_prefill(w, dcache, with_workspace=True)
+    assert np.isfinite(got).all() and np.isfinite(got_ws).all()
     rng = np.random.default_rng(0)
     C = w.new_per_seq
     local = np.array([0, 1, 15, 16, 17, C // 2, C - 2, C - 1])
     rows = np.unique(np.concatenate([local, (w.S - 1) * C + local, rng.integers(0, w.S * C, 8)])).astype(np.int32)
-    ref = _oracle_prefill(oracle_mod, w, cache, rows=rows)
-    print("full cfg4 sample max-abs %.2e" % assert_close(got[rows], ref, "cfg4 sample", record_property), flush=True)
+    ref_rows = _oracle_prefill(oracle_mod, w, cache, rows=rows)
+    print("full cfg4 sample max-abs %.2e" % assert_close(got[rows], ref_rows, "cfg4 sample", record_property), flush=True)
     whole = np.arange(5 * C, 6 * C, dtype=np.int32)                  # sequence 5, every row
     ref = _oracle_prefill(oracle_mod, w, cache, rows=whole)
     print("full cfg4 sequence 5, every row: max-abs %.2e" %
           assert_close(got[whole], ref, "cfg4 whole sequence", record_property), flush=True)
+    # the entry point with a workspace (the last 32 tiles of every pair in two halves + a merge):
+    # the same rows of the other tiles bit for bit, every checked row within the bar
+    print("full cfg4 with workspace, sequence 5: max-abs %.2e" %
+          assert_close(got_ws[whole], ref, "cfg4 whole sequence, workspace", record_property), flush=True)
+    assert_close(got_ws[rows], ref_rows, "cfg4 sample, workspace")
+    same = (got_ws == got).all(axis=2)                         # [row, head]
+    tiles_per_head = C // 16
+    tile = np.arange(w.H_q)[None, :] % (w.H_q // w.H_k) * tiles_per_head + (np.arange(w.S * C)[:, None] % C) // 16
+    assert same[tile < 128].all(), "rows of the first launch differ between the two entry points"
 
 
 def test_gather_cached_kv(oracle_mod):
