@@ -182,6 +182,34 @@ def test_probe_arguments(probe_lib):
     assert f(None, ctypes.c_size_t(0), 64, None, None) == 0
 
 
+def test_prefill_workspace_size_and_refusals(lib):
+    """The workspace of coopt_paged_gqa_prefill_chunk_ws: zero where the tiles fill whole rounds
+    of 256 workgroups (or fewer than one), otherwise 2 halves x 16 columns x (d + 2) floats per
+    tile of the last round and (sequence, KV head) pair.  Refusals come before any launch."""
+    cs = ctypes.c_size_t
+    one = ctypes.c_void_p(16)
+    size = lib.coopt_prefill_workspace_bytes
+    cfg4 = _shape(num_seqs=8, num_q_heads=40, num_kv_heads=8, head_dim=128, num_blocks=8192,
+                  max_blocks_per_seq=544)
+    # 64 pairs x 160 tiles = 640 workgroups of 16 tiles: two rounds of 256 and 32 tiles a pair left
+    assert size(ctypes.byref(cfg4), 512) == 64 * 32 * 2 * 16 * 130 * 4
+    assert size(ctypes.byref(cfg4), 16) == 0            # 5 tiles a pair: one workgroup each, a single round
+    assert size(ctypes.byref(cfg4), 0) == 0
+    whole = _shape(num_seqs=8, num_q_heads=32, num_kv_heads=8, head_dim=128, num_blocks=8192,
+                   max_blocks_per_seq=544)
+    assert size(ctypes.byref(whole), 512) == 0          # 64 pairs x 8 workgroups: two whole rounds
+    assert size(ctypes.byref(_shape(head_dim=96)), 512) == 0      # a shape the library refuses
+    run = lib.coopt_paged_gqa_prefill_chunk_ws
+    need = size(ctypes.byref(cfg4), 512)
+    args = (one, one, one, one, one, one, one, one, 4096, 512, one)
+    assert run(*args, None, cs(need), ctypes.byref(cfg4), None) == -1
+    assert run(*args, one, cs(need - 1), ctypes.byref(cfg4), None) == -3
+    assert run(*args[:-1], None, one, cs(need), ctypes.byref(cfg4), None) == -1       # out is required
+    assert run(one, one, one, one, one, one, one, one, 0, 512, one, None, cs(0), ctypes.byref(cfg4), None) == -1
+    assert run(one, one, one, one, one, one, one, one, 0, 0, one, None, cs(0), ctypes.byref(cfg4), None) == 0
+    assert run(*args, one, cs(need), ctypes.byref(_shape(head_dim=96)), None) == -2
+
+
 def test_binding_refuses_bad_tensors_before_any_launch(lib, monkeypatch):
     """The C side sees raw pointers only, so the binding checks residence, contiguity, integer
     widths and sizes against the shape; none of these calls reaches the library."""
@@ -190,7 +218,7 @@ def test_binding_refuses_bad_tensors_before_any_launch(lib, monkeypatch):
     class SizeQueriesOnly:
         def __getattr__(self, name):
             if name in ("coopt_decode_workspace_bytes", "coopt_decode_schedule_bytes",
-                        "coopt_status_string", "coopt_default_decode_plan"):
+                        "coopt_prefill_workspace_bytes", "coopt_status_string", "coopt_default_decode_plan"):
                 return getattr(lib, name)
             raise AssertionError(f"{name} was reached: the binding did not refuse the call")
 
