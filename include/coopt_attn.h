@@ -376,13 +376,16 @@ int coopt_paged_gqa_prefill_chunk(const void* q, const void* k_cache, const void
 
 /*
  * The same chunked prefill (Abstract: chunking of long sequences; Eq. 1 per row) with a workspace
- * for the launch's last, partly filled round.  Where the tiles of a chunk do not fill a whole
- * number of rounds of workgroups, coopt_paged_gqa_prefill_chunk runs the last tiles of every
- * (sequence, KV head) pair in smaller workgroups; with a workspace they run in full-size
- * workgroups that each stream one half of the pair's cache, leave (m, l, unnormalised sums) per
- * tile and half in the workspace, and a merge launch combines the halves by the online-softmax
- * rule (Opt-Pa Eq. 10).  Results agree with coopt_paged_gqa_prefill_chunk within the rounding of
- * that merge (same tolerance against the definition); rows outside those tiles are the same bits.
+ * for the launch's last, partly filled round of workgroups (one workgroup = 256 query rows of one
+ * (sequence, KV head) pair; a round = one workgroup per compute unit).  Where the tiles of a chunk
+ * do not fill a whole number of rounds, coopt_paged_gqa_prefill_chunk runs the last tiles of
+ * every pair in smaller workgroups, or leaves the round partly empty; with a workspace they run
+ * in full-size workgroups, 2 to 8 per 256 rows, that each stream one of as many equal runs of the
+ * pair's cache, leave (m, l, unnormalised sums) per 16 rows and run in the workspace, and a merge
+ * launch combines the runs by the online-softmax rule (Opt-Pa Eq. 10).  A launch of fewer
+ * workgroups than compute units is all "last round": this is the call for one or a few
+ * sequences.  Results agree with coopt_paged_gqa_prefill_chunk within the rounding of that merge
+ * (same tolerance against the definition); rows outside those tiles are the same bits.
  *   workspace        device memory, at least coopt_prefill_workspace_bytes(shape, max_chunk_len)
  *                    bytes (0 when the launch has no such round: then it may be NULL and the call
  *                    is coopt_paged_gqa_prefill_chunk); contents on entry are ignored, on return

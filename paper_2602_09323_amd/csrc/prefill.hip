@@ -46,11 +46,11 @@ struct PrefillArgs {
     int32_t tile_base;        // this launch covers tiles [tile_base, tile_limit) of every pair
     int32_t tile_limit;
     float scale_log2e;
-    // split launch (the last tiles of every pair, two workgroups per 16 tiles: the first streams
-    // the first half of the pair's stages, the second the rest; each leaves per tile and half
-    // 16 x (m, l) and the 16 x HEAD_DIM unnormalised sums in `part`, which a merge launch combines)
+    // split launch (the last tiles of every pair, `split` workgroups per 16 tiles: workgroup p of
+    // them streams the p-th of `split` equal runs of the pair's stages and leaves per tile 16 x
+    // (m, l) and the 16 x HEAD_DIM unnormalised sums in `part`, which a merge launch combines)
     float* part;
-    int32_t split;            // 0: whole streams, rows written to out;  1: half streams, partials
+    int32_t split;            // 0: whole streams, rows written to out;  >= 2: that many parts, partials
     int32_t tail_cap;         // tiles per pair the split launch covers (sizes `part`)
 };
 
@@ -206,8 +206,9 @@ prefill_chunk_kernel(const PrefillArgs a)
     const int total_tiles = a.G * tiles_per_head;
     const int end_tile = min(total_tiles, a.tile_limit);
     const int in_pair = k8 % a.wgs_per_pair;
-    const int half = a.split ? (in_pair & 1) : 0;
-    const int wg_first_tile = a.tile_base + (a.split ? in_pair >> 1 : in_pair) * (kPrefillWaves * NR);
+    const int parts = max(a.split, 1);
+    const int part = in_pair % parts;                  // which run of the pair's stages is mine
+    const int wg_first_tile = a.tile_base + (in_pair / parts) * (kPrefillWaves * NR);
     if (wg_first_tile >= end_tile) return;             // the whole workgroup leaves together
     const int first_tile = wg_first_tile + wave_id * NR;
     const bool active = first_tile < end_tile;         // a wave without tiles still produces
@@ -523,11 +524,11 @@ prefill_chunk_kernel(const PrefillArgs a)
     };
 
     // A stage holds GPS consecutive groups; one barrier per stage.  The workgroup streams stages
-    // s_lo .. s_hi-1: all of them, or one half of them in a split launch (an empty half leaves
-    // the neutral partial m = kNoReference, l = 0).
+    // s_lo .. s_hi-1: all of them, or one of `parts` equal runs in a split launch (an empty run
+    // leaves the neutral partial m = kNoReference, l = 0).
     const int num_stages = (num_groups + GPS - 1) / GPS;
-    const int s_lo = (a.split && half == 1) ? num_stages / 2 : 0;
-    const int s_hi = (a.split && half == 0) ? num_stages / 2 : num_stages;
+    const int s_lo = (int)((long long)num_stages * part / parts);
+    const int s_hi = (int)((long long)num_stages * (part + 1) / parts);
     const int g_end = min(num_groups, s_hi * GPS);            // groups below this one are mine
     auto slot = [&](int si, int sub) { return lds + ((si & 1) * GPS + sub) * St::kBytes; };
     // (a wave keeps registers for the sub-groups of its own team)
@@ -590,9 +591,9 @@ prefill_chunk_kernel(const PrefillArgs a)
         const float L = __shfl(lacc[r][0] + lacc[r][1], n) * 256.0f;
         // (the 2^kPShift common to acc and l cancels; the normaliser of the v_scales is in acc alone)
         if (a.split) {
-            // this half's share of the tile: reference, row sum and unnormalised sums per column
+            // this run's share of the tile: reference, row sum and unnormalised sums per column
             if (first_tile + r < end_tile) {
-                float* dst = a.part + (((size_t)pair * a.tail_cap + (first_tile + r - a.tile_base)) * 2 + half) *
+                float* dst = a.part + (((size_t)pair * a.tail_cap + (first_tile + r - a.tile_base)) * parts + part) *
                                           (16 * (HEAD_DIM + 2));
                 if (grp == 0) {
                     dst[n] = m[r];
@@ -619,13 +620,14 @@ prefill_chunk_kernel(const PrefillArgs a)
     }
 }
 
-// Combines the two halves a split launch left for every tile: with M = max(m_0, m_1) and
-// e_h = 2^(m_h - M), row = (A_0 e_0 + A_1 e_1) / (l_0 e_0 + l_1 e_1) (the merge rule of the online
-// softmax, Opt-Pa Eq. 10, over two parts).  One wavefront per tile, lane (n, grp) as in the kernel.
+// Combines the parts a split launch left for every tile: with M = max_p m_p and e_p = 2^(m_p - M),
+// row = sum_p A_p e_p / sum_p l_p e_p (the merge rule of the online softmax, Opt-Pa Eq. 10).  One
+// wavefront per tile, lane (n, grp) as in the kernel.
 template <int HEAD_DIM>
 __global__ void __launch_bounds__(256)
 prefill_split_merge_kernel(const PrefillArgs a)
 {
+    constexpr int kPart = 16 * (HEAD_DIM + 2);          // floats per tile and part
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, grp = lane >> 4;
     const long long id = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);      // pair * tail_cap + tile
@@ -642,20 +644,24 @@ prefill_split_merge_kernel(const PrefillArgs a)
     const int hh = tile / tiles_per_head;
     const int row = (tile - hh * tiles_per_head) * 16 + n;
     if (row >= C) return;
-    const float* p0 = a.part + (size_t)id * 2 * (16 * (HEAD_DIM + 2));
-    const float* p1 = p0 + 16 * (HEAD_DIM + 2);
-    const float m0 = p0[n], m1 = p1[n];
-    const float M = fmaxf(m0, m1);        // a row sees at least one token: not both kNoReference
-    const float e0 = __builtin_amdgcn_exp2f(m0 - M), e1 = __builtin_amdgcn_exp2f(m1 - M);
-    const float inv = 1.0f / (p0[16 + n] * e0 + p1[16 + n] * e1);
+    const int parts = a.split;
+    const float* p0 = a.part + (size_t)id * parts * kPart;
+    float M = kNoReference;                 // (a row sees at least one token: some part has a real m)
+    for (int p = 0; p < parts; ++p) M = fmaxf(M, p0[p * kPart + n]);
+    float den = 0.0f;
+    for (int p = 0; p < parts; ++p)
+        den += p0[p * kPart + 16 + n] * __builtin_amdgcn_exp2f(p0[p * kPart + n] - M);
+    const float inv = 1.0f / den;
     half_t* dst = a.out + ((size_t)(qs + row) * a.H_q + g * a.G + hh) * HEAD_DIM + 4 * grp;
 #pragma unroll
     for (int c = 0; c < HEAD_DIM / 16; ++c) {
-        const floatx4 x0 = *reinterpret_cast<const floatx4*>(p0 + 32 + n * HEAD_DIM + 16 * c + 4 * grp);
-        const floatx4 x1 = *reinterpret_cast<const floatx4*>(p1 + 32 + n * HEAD_DIM + 16 * c + 4 * grp);
+        floatx4 x = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < parts; ++p)
+            x += *reinterpret_cast<const floatx4*>(p0 + p * kPart + 32 + n * HEAD_DIM + 16 * c + 4 * grp) *
+                 __builtin_amdgcn_exp2f(p0[p * kPart + n] - M);
         half4_t h;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) h[i] = (half_t)((x0[i] * e0 + x1[i] * e1) * inv);
+        for (int i = 0; i < 4; ++i) h[i] = (half_t)(x[i] * inv);
         *reinterpret_cast<half4_t*>(dst + 16 * c) = h;
     }
 }
@@ -664,11 +670,15 @@ prefill_split_merge_kernel(const PrefillArgs a)
 // a CU, so a launch runs in rounds of one workgroup per CU, and a last round that is mostly empty
 // costs a full one.  Where that happens the last tiles of every pair go to a second launch: of
 // half-size workgroups (one tile per wave), which takes about 0.65-0.8 of a round -- or, when the
-// caller brings a workspace, of full-size workgroups that each stream HALF of the pair's stages
-// (half a round; the halves are combined by prefill_split_merge_kernel).
+// caller brings a workspace, of full-size workgroups, `parts` per 16 tiles, that each stream one
+// of `parts` equal runs of the pair's stages, with `parts` (2 to 8) chosen so that the round is as
+// short as it gets (a launch of fewer workgroups than CUs is all "last round": a single
+// sequence's chunk is spread over the chip this way); the parts are combined by
+// prefill_split_merge_kernel.
+constexpr int kPrefillMaxParts = 8;
 struct PrefillLaunchPlan {
-    int tiles, pairs8, a_per_pair, b_per_pair, rest;
-    PrefillLaunchPlan(const coopt_shape* sh, int max_chunk_len)
+    int tiles, pairs8, a_per_pair, b_per_pair, rest, parts;
+    PrefillLaunchPlan(const coopt_shape* sh, int max_chunk_len, bool with_workspace)
     {
         const int G = sh->num_q_heads / sh->num_kv_heads;
         tiles = G * ((max_chunk_len + 15) / 16);
@@ -677,11 +687,33 @@ struct PrefillLaunchPlan {
         a_per_pair = full_per_pair;
         b_per_pair = 0;
         rest = 0;
+        parts = 0;
         auto rounds = [](long long wgs) { return (double)((wgs + kPrefillCUs - 1) / kPrefillCUs); };
         const long long W = (long long)pairs8 * full_per_pair;
         const int cand = (int)((W / kPrefillCUs) * kPrefillCUs / pairs8);   // full rounds only
-        if (cand >= 1 && cand < full_per_pair) {
-            const int r = tiles - cand * 2 * kPrefillWaves;
+        if (cand >= full_per_pair) return;                                   // whole rounds
+        const int r = tiles - cand * 2 * kPrefillWaves;                      // tiles of the last round, per pair
+        if (with_workspace) {
+            // p parts make p times the workgroups, each 1/p as long; a part costs about 2 % of a
+            // round on top (its start, its partial rows, its share of the merge)
+            const long long last = (long long)pairs8 * ((r + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves));
+            int best = 1;
+            double best_cost = rounds(last);
+            for (int p = 2; p <= kPrefillMaxParts; ++p) {
+                const double cost = rounds(last * p) / p + 0.02 * (p - 1);
+                if (cost < best_cost) {
+                    best_cost = cost;
+                    best = p;
+                }
+            }
+            if (best >= 2) {
+                a_per_pair = cand;
+                rest = r;
+                parts = best;
+                return;
+            }
+        }
+        if (cand >= 1) {
             const int small = (r + kPrefillWaves - 1) / kPrefillWaves;
             const double split = rounds((long long)pairs8 * cand) + 0.65 * rounds((long long)pairs8 * small);
             if (split < rounds(W)) {
@@ -692,11 +724,11 @@ struct PrefillLaunchPlan {
         }
     }
     // workgroups per pair of the split form of the second launch
-    int split_per_pair() const { return 2 * ((rest + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves)); }
+    int split_per_pair() const { return parts * ((rest + 2 * kPrefillWaves - 1) / (2 * kPrefillWaves)); }
     size_t workspace_bytes(const coopt_shape* sh) const
     {
-        if (!b_per_pair) return 0;
-        return (size_t)sh->num_seqs * sh->num_kv_heads * rest * 2 * 16 * (sh->head_dim + 2) * sizeof(float);
+        if (parts < 2) return 0;
+        return (size_t)sh->num_seqs * sh->num_kv_heads * rest * parts * 16 * (sh->head_dim + 2) * sizeof(float);
     }
 };
 
@@ -707,7 +739,7 @@ using namespace coopt;
 extern "C" size_t coopt_prefill_workspace_bytes(const coopt_shape* sh, int32_t max_chunk_len)
 {
     if (check_shape(sh) != COOPT_OK || max_chunk_len <= 0 || sh->num_seqs == 0) return 0;
-    return PrefillLaunchPlan(sh, max_chunk_len).workspace_bytes(sh);
+    return PrefillLaunchPlan(sh, max_chunk_len, true).workspace_bytes(sh);
 }
 
 static int prefill_chunk(const void* q, const void* k_cache, const void* v_cache, const float* k_scale,
@@ -739,7 +771,7 @@ extern "C" int coopt_paged_gqa_prefill_chunk_ws(const void* q, const void* k_cac
     int st = check_shape(sh);
     if (st != COOPT_OK) return st;
     if (max_chunk_len > 0 && sh->num_seqs > 0) {
-        const size_t need = PrefillLaunchPlan(sh, max_chunk_len).workspace_bytes(sh);
+        const size_t need = PrefillLaunchPlan(sh, max_chunk_len, true).workspace_bytes(sh);
         if (need > 0 && !workspace) return COOPT_ERR_NULL;
         if (workspace_bytes < need) return COOPT_ERR_WORKSPACE;
         if (need == 0) workspace = nullptr;
@@ -776,9 +808,9 @@ static int prefill_chunk(const void* q, const void* k_cache, const void* v_cache
     a.scale_log2e = sh->softmax_scale * kLog2e;
     a.num_pairs = sh->num_seqs * sh->num_kv_heads;
 
-    const PrefillLaunchPlan lp(sh, max_chunk_len);
+    const PrefillLaunchPlan lp(sh, max_chunk_len, workspace != nullptr);
     const int pairs8 = lp.pairs8, a_per_pair = lp.a_per_pair, b_per_pair = lp.b_per_pair;
-    const bool split = b_per_pair && workspace;
+    const bool split = lp.parts >= 2;
     const int split_per_pair = lp.split_per_pair();
     if ((long long)pairs8 * (a_per_pair + b_per_pair + split_per_pair) > 0x7fffffffLL) return COOPT_ERR_SHAPE;
     const dim3 block(64 * kPrefillWaves);
@@ -789,18 +821,17 @@ static int prefill_chunk(const void* q, const void* k_cache, const void* v_cache
 #define COOPT_PREFILL(D, KV, BIG)                                                                   \
     do {                                                                                            \
         a.tile_base = 0;                                                                            \
-        a.tile_limit = b_per_pair ? a_per_pair * 2 * kPrefillWaves : 0x7fffffff;                    \
+        a.tile_limit = (b_per_pair || split) ? a_per_pair * 2 * kPrefillWaves : 0x7fffffff;         \
         a.wgs_per_pair = a_per_pair;                                                                \
-        hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 2, BIG>),                                   \
-                           dim3((unsigned)((long long)pairs8 * a_per_pair)), block, lds, stream, a); \
-        if (b_per_pair) {                                                                           \
-            a.tile_base = a.tile_limit;                                                             \
-            a.tile_limit = 0x7fffffff;                                                              \
-        }                                                                                           \
+        if (a_per_pair > 0)                                                                         \
+            hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 2, BIG>),                               \
+                               dim3((unsigned)((long long)pairs8 * a_per_pair)), block, lds, stream, a); \
+        a.tile_base = a.tile_limit;                                                                 \
+        a.tile_limit = 0x7fffffff;                                                                  \
         if (split) {                                                                                \
             a.wgs_per_pair = split_per_pair;                                                        \
             a.part = (float*)workspace;                                                             \
-            a.split = 1;                                                                            \
+            a.split = lp.parts;                                                                     \
             a.tail_cap = lp.rest;                                                                   \
             hipLaunchKernelGGL((prefill_chunk_kernel<D, KV, 2, BIG>),                               \
                                dim3((unsigned)((long long)pairs8 * split_per_pair)), block, lds, stream, a); \

@@ -184,8 +184,9 @@ def test_probe_arguments(probe_lib):
 
 def test_prefill_workspace_size_and_refusals(lib):
     """The workspace of coopt_paged_gqa_prefill_chunk_ws: zero where the tiles fill whole rounds
-    of 256 workgroups (or fewer than one), otherwise 2 halves x 16 columns x (d + 2) floats per
-    tile of the last round and (sequence, KV head) pair.  Refusals come before any launch."""
+    of 256 workgroups, otherwise parts x 16 columns x (d + 2) floats per tile of the last round
+    and (sequence, KV head) pair, parts (2 to 8) = the split that makes that round shortest on 256
+    CUs.  Refusals come before any launch."""
     cs = ctypes.c_size_t
     one = ctypes.c_void_p(16)
     size = lib.coopt_prefill_workspace_bytes
@@ -193,7 +194,15 @@ def test_prefill_workspace_size_and_refusals(lib):
                   max_blocks_per_seq=544)
     # 64 pairs x 160 tiles = 640 workgroups of 16 tiles: two rounds of 256 and 32 tiles a pair left
     assert size(ctypes.byref(cfg4), 512) == 64 * 32 * 2 * 16 * 130 * 4
-    assert size(ctypes.byref(cfg4), 16) == 0            # 5 tiles a pair: one workgroup each, a single round
+    # 5 tiles a pair: 64 workgroups, a quarter of a round, so every pair's stages are cut in four
+    assert size(ctypes.byref(cfg4), 16) == 64 * 5 * 4 * 16 * 130 * 4
+    one_seq = _shape(num_seqs=1, num_q_heads=40, num_kv_heads=8, head_dim=128, num_blocks=8192,
+                     max_blocks_per_seq=544)
+    assert size(ctypes.byref(one_seq), 16) == 8 * 5 * 7 * 16 * 130 * 4     # 8 workgroups: seven parts (at most eight)
+    assert size(ctypes.byref(one_seq), 512) == 8 * 160 * 3 * 16 * 130 * 4  # 80 workgroups: three parts fill 240 CUs
+    three = _shape(num_seqs=3, num_q_heads=40, num_kv_heads=8, head_dim=128, num_blocks=8192,
+                   max_blocks_per_seq=544)
+    assert size(ctypes.byref(three), 512) == 0          # 240 workgroups: no number of parts makes the round shorter
     assert size(ctypes.byref(cfg4), 0) == 0
     whole = _shape(num_seqs=8, num_q_heads=32, num_kv_heads=8, head_dim=128, num_blocks=8192,
                    max_blocks_per_seq=544)

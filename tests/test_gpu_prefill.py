@@ -46,12 +46,36 @@ def _oracle_prefill(oracle, w, cache, rows=None):
 @pytest.mark.parametrize("ctx,C,H_q,H_k,d", [(40, 24, 10, 2, 128), (0, 33, 4, 2, 64), (100, 1, 5, 1, 128),
                                              (7, 130, 6, 3, 128), (256, 64, 40, 8, 128)])
 def test_small_chunks(oracle_mod, kv_dtype, ctx, C, H_q, H_k, d):
+    """A few workgroups only.  Through the entry point with a workspace such a launch is all "last
+    round": every pair's stages are cut into up to eight runs (more runs than some of these
+    streams have stages, so some parts are empty), one workgroup each, and merged."""
     w = workloads.make_custom("pf", seed=51, S=3, H_q=H_q, H_k=H_k, d=d, B=16, NB=96,
                               context_lens=[ctx + C] * 3, new_per_seq=C, kv_dtype=kv_dtype)
     cache = oracle_fill(oracle_mod, w)
     ref = _oracle_prefill(oracle_mod, w, cache)
-    got = _hip_prefill(w, cache_to_dev(cache))
-    assert_close(got, ref, f"prefill ctx={ctx} C={C} {kv_dtype}")
+    dcache = cache_to_dev(cache)
+    assert_close(_hip_prefill(w, dcache), ref, f"prefill ctx={ctx} C={C} {kv_dtype}")
+    assert coopt.prefill_workspace_bytes(shape_of(w), C) > 0
+    assert_close(_hip_prefill(w, dcache, with_workspace=True), ref, f"prefill ctx={ctx} C={C} {kv_dtype}, workspace")
+
+
+@pytest.mark.parametrize("kv_dtype", ["e4m3", "e5m2", "fp16"])
+def test_one_sequence_spread_over_the_chip(oracle_mod, kv_dtype):
+    """One sequence's chunk (8 KV heads: 8 pairs of 125 tiles = 64 workgroups) over a history of
+    3000 tokens: with a workspace its stages are cut into four runs per 16 tiles."""
+    C, hist = 400, 3000
+    w = workloads.make_custom("pf_one", seed=57, S=1, H_q=40, H_k=8, d=128, B=16, NB=230,
+                              context_lens=[hist + C], new_per_seq=C, kv_dtype=kv_dtype)
+    cache = oracle_fill(oracle_mod, w)
+    ref = oracle_mod.paged_gqa_prefill_chunk(w.q, *cache, w.block_tables, w.context_lens, w.query_start,
+                                             H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B, softmax_scale=w.softmax_scale,
+                                             fmt="e5m2" if kv_dtype == "e5m2" else "e4m3")
+    shape = shape_of(w)
+    # 125 tiles a pair = 8 workgroups: 64 in the launch, four parts of each fill the 256 CUs
+    assert coopt.prefill_workspace_bytes(shape, C) == 8 * 125 * 4 * 16 * 130 * 4
+    dcache = cache_to_dev(cache)
+    assert_close(_hip_prefill(w, dcache), ref, f"one sequence {kv_dtype}")
+    assert_close(_hip_prefill(w, dcache, with_workspace=True), ref, f"one sequence {kv_dtype}, workspace")
 
 
 def test_chunk_written_on_device_then_attended(oracle_mod):
