@@ -85,6 +85,8 @@ def parse_args():
     ap.add_argument("--prefill-entry", choices=["workspace", "plain"], default="workspace",
                     help="config 4: coopt_paged_gqa_prefill_chunk_ws (a workspace for the launch's last "
                          "round) or coopt_paged_gqa_prefill_chunk")
+    ap.add_argument("--prefill-seqs", type=int, default=0,
+                    help="config 4 with this many sequences instead of its 8 (0 = the configuration)")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate over (0 = auto)")
     ap.add_argument("--plan", type=str, default="",
                     help="decode plan fields in header order, comma separated (tuning)")
@@ -167,6 +169,13 @@ def main():
         return
     cfg = 1 if args.config is None else args.config
     w = workloads.make(cfg)
+    if cfg == 4 and args.prefill_seqs:
+        # the named configuration's sequences, fewer of them (8192 history + 512 chunk tokens each)
+        C = w.new_per_seq
+        w = workloads.make_custom(w.name + "_%dseq" % args.prefill_seqs, seed=workloads.BASE_SEED + 4,
+                                  S=args.prefill_seqs, H_q=w.H_q, H_k=w.H_k, d=w.d, B=w.B, NB=w.NB,
+                                  context_lens=[int(w.context_lens[0])] * args.prefill_seqs, new_per_seq=C,
+                                  max_blocks=w.max_blocks)
     if args.op == "gather":
         print(json.dumps(bench_gather(args, w, coopt, torch, dev)), flush=True)
         return
