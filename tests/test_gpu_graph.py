@@ -3,8 +3,8 @@ step once and replay it; a replay has to give what the same calls give eagerly, 
 with eager work of the same library and synchronisations in between.  Captured here: the fused
 step from a prepared schedule (attention launch + merge launch, which also stores the step's new
 rows into the cache), the decode that keeps its partials in the library's built-in array, and a
-prefill chunk (two launches).  None of them allocates, sets memory or synchronises, so capture
-needs no special path -- this test is what holds them to that."""
+prefill chunk (two launches; three with a workspace).  None of them allocates, sets memory or
+synchronises, so capture needs no special path -- this test is what holds them to that."""
 import numpy as np
 import pytest
 import torch
@@ -94,7 +94,10 @@ def test_replays_of_a_captured_decode_step_equal_the_eager_step(oracle_mod):
         assert torch.isfinite(oout.float()).all()
 
 
-def test_replays_of_a_captured_prefill_chunk_equal_the_eager_call(oracle_mod):
+@pytest.mark.parametrize("with_workspace", [False, True])
+def test_replays_of_a_captured_prefill_chunk_equal_the_eager_call(oracle_mod, with_workspace):
+    """(with a workspace: three launches -- here every pair's stages in eight parts -- and the
+    partial rows of one replay are overwritten by the next and by the eager call in between)"""
     S, C, hist = 3, 80, [0, 300, 1000]
     w = workloads.make_custom("graph_prefill", seed=83, S=S, H_q=10, H_k=2, d=128, B=16, NB=120,
                               context_lens=[h + C for h in hist], new_per_seq=C)
@@ -107,7 +110,17 @@ def test_replays_of_a_captured_prefill_chunk_equal_the_eager_call(oracle_mod):
     hip_write(w, dcache)
     q, bt, dl, qs = dev(w.q.view(np.uint16)), dev(w.block_tables), dev(w.context_lens), dev(w.query_start)
     eager = torch.full((S * C, w.H_q, w.d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.paged_gqa_prefill_chunk(q, *dcache, bt, dl, qs, S * C, C, eager, shape)
+    need = coopt.prefill_workspace_bytes(shape, C)
+    assert need > 0
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+
+    def call(out):
+        if with_workspace:
+            coopt.paged_gqa_prefill_chunk_ws(q, *dcache, bt, dl, qs, S * C, C, out, ws, shape)
+        else:
+            coopt.paged_gqa_prefill_chunk(q, *dcache, bt, dl, qs, S * C, C, out, shape)
+
+    call(eager)
     torch.cuda.synchronize()
     assert_close(eager.cpu().numpy().astype(np.float64), ref, "eager prefill chunk")
 
@@ -117,7 +130,7 @@ def test_replays_of_a_captured_prefill_chunk_equal_the_eager_call(oracle_mod):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
-            coopt.paged_gqa_prefill_chunk(q, *dcache, bt, dl, qs, S * C, C, out, shape)
+            call(out)
     torch.cuda.synchronize()
     for replay in range(3):
         out.fill_(-5.0 - replay)
@@ -125,6 +138,7 @@ def test_replays_of_a_captured_prefill_chunk_equal_the_eager_call(oracle_mod):
         torch.cuda.synchronize()
         assert torch.equal(out, eager), f"replay {replay}: prefill chunk differs from the eager call"
         scratch = torch.full_like(eager, -1.0)          # an eager call between the replays
-        coopt.paged_gqa_prefill_chunk(q, *dcache, bt, dl, qs, S * C, C, scratch, shape)
+        ws.fill_(float("nan"))
+        call(scratch)
         torch.cuda.synchronize()
         assert torch.equal(scratch, eager)
