@@ -22,9 +22,9 @@
 //     XCD's L2 by the pair's other workgroups.
 //   * A launch runs in rounds of one workgroup per CU.  The tiles of a last round that would be
 //     mostly empty go to a second launch: of half-size workgroups, or -- when the caller brings a
-//     workspace -- of full-size workgroups that each stream one half of the pair's stages and
-//     leave (m, l, unnormalised sums) per tile, which a merge launch combines (Opt-Pa Eq. 10 over
-//     two parts).
+//     workspace -- of full-size workgroups, 2 to 8 per 16 tiles, that each stream one of as many
+//     equal runs of the pair's stages and leave (m, l, unnormalised sums) per tile, which a merge
+//     launch combines (Opt-Pa Eq. 10 over the parts).
 // The only difference from decode in the arithmetic is that the visible-token limit is per column
 // (causal).
 #include "attn_tile.hpp"
@@ -293,7 +293,7 @@ prefill_chunk_kernel(const PrefillArgs a)
     floatx4 acc[NR][HEAD_DIM / 16];
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-        // (finite, not -inf: a workgroup that streams the second half of a pair's stages meets
+        // (finite, not -inf: a workgroup that streams a later run of a pair's stages meets
         // columns that see none of a group's tokens before any they do see, and the weights
         // exp2(z - m) of such a column must come out as exp2(-inf) = 0, not exp2(-inf + inf))
         m[r] = kNoReference;
