@@ -173,10 +173,19 @@ def _prefill_case(orc, seed):
                                       H_k=H_k, d=d, B=16, softmax_scale=w.softmax_scale,
                                       fmt="e5m2" if kv == "e5m2" else "e4m3")
     out = torch.full((rows, H_q, d), -7.0, dtype=torch.float16, device="cuda")
-    coopt.paged_gqa_prefill_chunk(dev(q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables),
-                                  dev(context_lens), dev(query_start), rows, max(chunk), out, shape_of(w))
+    args = (dev(q.view(np.uint16)), *cache_to_dev(cache), dev(w.block_tables), dev(context_lens),
+            dev(query_start), rows, max(chunk))
+    coopt.paged_gqa_prefill_chunk(*args, out, shape_of(w))
     torch.cuda.synchronize()
     assert_close(out.cpu().numpy().astype(np.float64), ref, what)
+    # the entry point with a workspace: these launches are smaller than the chip, so every pair's
+    # stages are cut into parts (often more parts than stages) and merged
+    need = coopt.prefill_workspace_bytes(shape_of(w), max(chunk))
+    ws = torch.full((max(need, 4) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    out.fill_(-7.0)
+    coopt.paged_gqa_prefill_chunk_ws(*args, out, ws if need else None, shape_of(w))
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy().astype(np.float64), ref, what + f" workspace={need}")
 
 
 @pytest.mark.parametrize("first", [2000, 2008, 2016, 2024])
