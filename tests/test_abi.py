@@ -219,6 +219,39 @@ def test_prefill_workspace_size_and_refusals(lib):
     assert run(*args, one, cs(need), ctypes.byref(_shape(head_dim=96)), None) == -2
 
 
+def test_prefill_launch_plan_over_many_shapes(lib):
+    """The rule behind coopt_prefill_workspace_bytes, restated here and swept over batch sizes,
+    chunk lengths and group sizes: a workgroup covers 16 tiles of a pair (8 where a pair has at
+    most 8), a round is 256 workgroups, whole rounds keep whole streams, and the L workgroups of
+    the last round are cut into the p in 2..8 that minimises ceil(L p / 256) / p + 0.02 (p - 1) if
+    that beats ceil(L / 256)."""
+    import math
+    size = lib.coopt_prefill_workspace_bytes
+    for H_q, H_k in ((40, 8), (32, 8), (8, 8), (64, 4)):
+        for S in list(range(1, 20)) + [31, 32, 33, 64, 100]:
+            for C in (1, 16, 17, 64, 128, 500, 512, 2048):
+                sh = _shape(num_seqs=S, num_q_heads=H_q, num_kv_heads=H_k, head_dim=128,
+                            num_blocks=1 << 16, max_blocks_per_seq=1024)
+                tiles = (H_q // H_k) * ((C + 15) // 16)
+                wg_tiles = 8 if tiles <= 8 else 16
+                pairs8 = (S * H_k + 7) // 8 * 8
+                full = (tiles + wg_tiles - 1) // wg_tiles
+                W = pairs8 * full
+                cand = (W // 256) * 256 // pairs8
+                want = 0
+                if cand < full:
+                    rest = tiles - cand * wg_tiles
+                    last = pairs8 * ((rest + wg_tiles - 1) // wg_tiles)
+                    best, best_cost = 1, float(math.ceil(last / 256))
+                    for p in range(2, 9):
+                        cost = math.ceil(last * p / 256) / p + 0.02 * (p - 1)
+                        if cost < best_cost:
+                            best, best_cost = p, cost
+                    if best >= 2:
+                        want = S * H_k * rest * best * 16 * 130 * 4
+                assert size(ctypes.byref(sh), C) == want, (H_q, H_k, S, C)
+
+
 def test_binding_refuses_bad_tensors_before_any_launch(lib, monkeypatch):
     """The C side sees raw pointers only, so the binding checks residence, contiguity, integer
     widths and sizes against the shape; none of these calls reaches the library."""
